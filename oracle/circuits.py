@@ -1,0 +1,268 @@
+"""Oracle for SHE's layer operators (TEST INFRASTRUCTURE ONLY).
+
+Two things live here, both written from the paper's definitions:
+
+* the plain meaning of each operator on integers (Section 3.1: ReLU(x) = max(x, 0)
+  and max pooling; Section 3.2: sum of binaryshift(input_i, weightQ_i));
+* the Boolean netlists they lower to (Section 3.1: units built from 2-input
+  gates; Section 3.2: a shift only re-wires encrypted bits and replicates or
+  drops positions; Section 3.3: an adder tree whose level j uses (b+j)-bit
+  adders).  The paper's circuit figures are not available, so each netlist is
+  a stated reading; the GPU library implements the same reading independently.
+
+A netlist is evaluated either on plaintext bits (which pins its structure
+against the integer meaning) or, through ``oracle.tfhe``, on ciphertexts.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import tfhe
+
+G = tfhe.GATES
+
+_PLAIN = {
+    G["NAND"]: lambda a, b: 1 - (a & b),
+    G["AND"]: lambda a, b: a & b,
+    G["OR"]: lambda a, b: a | b,
+    G["XOR"]: lambda a, b: a ^ b,
+    G["XNOR"]: lambda a, b: 1 - (a ^ b),
+    G["NOR"]: lambda a, b: 1 - (a | b),
+    G["ANDNY"]: lambda a, b: (1 - a) & b,
+    G["ANDYN"]: lambda a, b: a & (1 - b),
+    G["ORNY"]: lambda a, b: (1 - a) | b,
+    G["ORYN"]: lambda a, b: a | (1 - b),
+}
+
+
+def plain_gate(code: int, a: int, b: int) -> int:
+    return _PLAIN[code](a, b)
+
+
+# ------------------------------------------------------------------ plain meaning
+def plain_shift_acc(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int) -> np.ndarray:
+    """x[units][terms] unsigned; result sum_i sign_i * (x_i >> |e_i|), wrapped to acc_bits, as signed ints."""
+    x = np.asarray(x, np.int64)
+    s = (x >> np.abs(np.asarray(w_exp, np.int64))) * np.asarray(w_sign, np.int64)
+    tot = s.sum(axis=-1) & ((1 << acc_bits) - 1)
+    return np.where(tot >= (1 << (acc_bits - 1)), tot - (1 << acc_bits), tot)
+
+
+def plain_relu(x: np.ndarray) -> np.ndarray:
+    return np.maximum(np.asarray(x, np.int64), 0)
+
+
+def plain_maxpool2x2(x: np.ndarray) -> np.ndarray:
+    """x[H][W][C] signed -> [H//2][W//2][C], window 2x2, stride 2 (a ragged last row/column is dropped)."""
+    x = np.asarray(x, np.int64)
+    H, W = x.shape[0] // 2 * 2, x.shape[1] // 2 * 2
+    x = x[:H, :W]
+    return np.maximum(np.maximum(x[0::2, 0::2], x[0::2, 1::2]), np.maximum(x[1::2, 0::2], x[1::2, 1::2]))
+
+
+def to_bits(v: np.ndarray, bits: int) -> np.ndarray:
+    """two's-complement bits, LSB first, new last axis"""
+    v = np.asarray(v, np.int64) & ((1 << bits) - 1)
+    return ((v[..., None] >> np.arange(bits)) & 1).astype(np.uint8)
+
+
+def from_bits(b: np.ndarray, signed: bool) -> np.ndarray:
+    b = np.asarray(b, np.int64)
+    bits = b.shape[-1]
+    v = (b << np.arange(bits)).sum(axis=-1)
+    if signed:
+        v = np.where(v >= (1 << (bits - 1)), v - (1 << bits), v)
+    return v
+
+
+# ------------------------------------------------------------------ netlists
+@dataclass
+class Netlist:
+    """Gates over wire ids.  Wires 0..n_inputs-1 are the inputs, then ZERO and ONE
+    (trivial, noiseless ciphertexts of 0 and 1), then one new wire per gate."""
+    n_inputs: int
+    gtype: list = field(default_factory=list)
+    in0: list = field(default_factory=list)
+    in1: list = field(default_factory=list)
+    out: list = field(default_factory=list)
+
+    def __post_init__(self):
+        self.ZERO = self.n_inputs
+        self.ONE = self.n_inputs + 1
+        self._next = self.n_inputs + 2
+
+    @property
+    def n_wires(self) -> int:
+        return self._next
+
+    def gate(self, name: str, a: int, b: int) -> int:
+        w = self._next
+        self._next += 1
+        self.gtype.append(G[name]); self.in0.append(a); self.in1.append(b); self.out.append(w)
+        return w
+
+    def mux(self, s: int, u: int, v: int) -> int:
+        """s ? u : v as three 2-input gates"""
+        return self.gate("OR", self.gate("AND", s, u), self.gate("ANDNY", s, v))
+
+    # ---- depth of each gate when every gate is scheduled as early as possible
+    def levels(self) -> np.ndarray:
+        lev = np.zeros(self.n_wires, np.int64)
+        for a, b, o in zip(self.in0, self.in1, self.out):
+            lev[o] = 1 + max(lev[a], lev[b])
+        return lev[np.asarray(self.out, np.int64)] if self.out else np.zeros(0, np.int64)
+
+    # ---- evaluation on plaintext bits
+    def run_plain(self, input_bits) -> np.ndarray:
+        val = np.zeros(self.n_wires, np.uint8)
+        val[: self.n_inputs] = np.asarray(input_bits, np.uint8).ravel()
+        val[self.ONE] = 1
+        for t, a, b, o in zip(self.gtype, self.in0, self.in1, self.out):
+            val[o] = plain_gate(t, int(val[a]), int(val[b]))
+        return val
+
+    # ---- evaluation on ciphertexts with the gate oracle
+    def run_encrypted(self, K: tfhe.Keys, input_cts: np.ndarray, threads: int = 1) -> np.ndarray:
+        n = K.params.n
+        pool = np.zeros((self.n_wires, n + 1), np.uint32)
+        pool[: self.n_inputs] = input_cts
+        pool[self.ZERO, n] = (-(1 << 29)) & 0xFFFFFFFF
+        pool[self.ONE, n] = 1 << 29
+        if threads <= 1:
+            tfhe.eval_gates(K, pool, self.gtype, self.in0, self.in1, self.out, 1)
+        else:
+            lev = self.levels()
+            t, a, b, o = (np.asarray(v) for v in (self.gtype, self.in0, self.in1, self.out))
+            for d in range(1, int(lev.max(initial=0)) + 1):
+                m = lev == d
+                tfhe.eval_gates(K, pool, t[m], a[m], b[m], o[m], threads)
+        return pool
+
+
+def add_unsigned(nl: Netlist, a: list, b: list, cap: int) -> list:
+    """Ripple-carry sum of two equally wide unsigned vectors (LSB first).  The
+    result has one more bit than the operands, unless that would exceed `cap`
+    bits: then the top carry is not computed and the sum wraps."""
+    w = len(a)
+    assert len(b) == w and w >= 1
+    out = [nl.gate("XOR", a[0], b[0])]
+    if w == 1 and cap == 1:
+        return out
+    c = nl.gate("AND", a[0], b[0])
+    for i in range(1, w):
+        t = nl.gate("XOR", a[i], b[i])
+        out.append(nl.gate("XOR", t, c))
+        if i == w - 1 and w >= cap:
+            return out
+        g = nl.gate("AND", a[i], b[i])
+        q = nl.gate("AND", t, c)
+        c = nl.gate("OR", g, q)
+    out.append(c)
+    return out
+
+
+def sub_wrapped(nl: Netlist, p: list, q: list) -> list:
+    """p - q modulo 2^w as p + not(q) + 1: the complement is folded into the gate
+    types (XNOR, ANDYN) and the carry chain starts from the trivial ONE."""
+    w = len(p)
+    assert len(q) == w
+    out, c = [], nl.ONE
+    for i in range(w):
+        t = nl.gate("XNOR", p[i], q[i])
+        out.append(nl.gate("XOR", t, c))
+        if i == w - 1:
+            break
+        g = nl.gate("ANDYN", p[i], q[i])
+        h = nl.gate("AND", t, c)
+        c = nl.gate("OR", g, h)
+    return out
+
+
+def adder_tree(nl: Netlist, terms: list, in_bits: int, acc_bits: int) -> list:
+    """Mixed-bitwidth accumulator: level j adds neighbours with min(in_bits+j, acc_bits)-bit
+    adders; an unpaired last vector moves up one level zero-extended.  Returns the sum
+    zero-extended to acc_bits (all ZERO for no terms)."""
+    vecs = [list(t) for t in terms]
+    width = in_bits
+    while len(vecs) > 1:
+        nxt_w = min(width + 1, acc_bits)
+        nxt = []
+        for m in range(0, len(vecs) - 1, 2):
+            nxt.append(add_unsigned(nl, vecs[m], vecs[m + 1], acc_bits))
+        if len(vecs) % 2:
+            nxt.append(vecs[-1] + [nl.ZERO] * (nxt_w - width))
+        vecs, width = nxt, nxt_w
+    if not vecs:
+        return [nl.ZERO] * acc_bits
+    return vecs[0] + [nl.ZERO] * (acc_bits - width)
+
+
+def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
+    """x >> |exp| for an unsigned vector: the low |exp| wires are dropped and the
+    top is refilled with ZERO, so the width stays the same.  No gates."""
+    s = abs(int(exp))
+    w = len(x_bits)
+    return list(x_bits[s:]) + [nl.ZERO] * min(s, w)
+
+
+def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int):
+    """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits])."""
+    w_sign = np.asarray(w_sign).reshape(units, terms)
+    w_exp = np.asarray(w_exp).reshape(units, terms)
+    nl = Netlist(units * terms * in_bits)
+    outs = []
+    for u in range(units):
+        pos, neg = [], []
+        for t in range(terms):
+            base = (u * terms + t) * in_bits
+            term = shifted_term(nl, list(range(base, base + in_bits)), w_exp[u, t])
+            (pos if w_sign[u, t] > 0 else neg).append(term)
+        P = adder_tree(nl, pos, in_bits, acc_bits)
+        if neg:
+            Q = adder_tree(nl, neg, in_bits, acc_bits)
+            outs.append(sub_wrapped(nl, P, Q))
+        else:
+            outs.append(P)
+    return nl, outs
+
+
+def build_relu(count: int, bits: int):
+    """Each value: sign wire masks every lower bit; the result's sign is ZERO."""
+    nl = Netlist(count * bits)
+    outs = []
+    for v in range(count):
+        x = list(range(v * bits, (v + 1) * bits))
+        outs.append([nl.gate("ANDNY", x[-1], x[i]) for i in range(bits - 1)] + [nl.ZERO])
+    return nl, outs
+
+
+def max_signed(nl: Netlist, x: list, y: list) -> list:
+    """Larger of two two's-complement vectors: ripple comparator from the LSB up
+    (gt = "x > y on the bits seen so far"), sign bits compared the other way
+    round, then one MUX per bit."""
+    w = len(x)
+    e = [nl.gate("XNOR", x[i], y[i]) for i in range(w)]
+    gt = nl.ZERO
+    for i in range(w - 1):
+        gt = nl.mux(e[i], gt, x[i])
+    gt = nl.mux(e[w - 1], gt, y[w - 1])
+    return [nl.mux(gt, x[i], y[i]) for i in range(w)]
+
+
+def build_maxpool(H: int, W: int, Cn: int, bits: int):
+    nl = Netlist(H * W * Cn * bits)
+
+    def px(h, w, c):
+        base = ((h * W + w) * Cn + c) * bits
+        return list(range(base, base + bits))
+
+    outs = []
+    for h in range(H // 2):
+        for w in range(W // 2):
+            for c in range(Cn):
+                top = max_signed(nl, px(2 * h, 2 * w, c), px(2 * h, 2 * w + 1, c))
+                bot = max_signed(nl, px(2 * h + 1, 2 * w, c), px(2 * h + 1, 2 * w + 1, c))
+                outs.append(max_signed(nl, top, bot))
+    return nl, outs

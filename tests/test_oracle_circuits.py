@@ -1,0 +1,166 @@
+"""Pins for the oracle's SHE operator netlists (CPU only): each netlist, run on
+plaintext bits, must equal plain integer arithmetic; gate counts must equal the
+closed forms; small instances are also run on ciphertexts with the gate oracle."""
+import itertools
+
+import numpy as np
+import pytest
+
+from oracle import circuits as C
+from oracle import tfhe
+
+
+def test_plain_definitions_by_hand():
+    # 200>>1 - 7>>0 + 255>>7 = 100 - 7 + 1
+    assert C.plain_shift_acc([[200, 7, 255]], [[1, -1, 1]], [[-1, 0, -7]], 16).tolist() == [94]
+    assert C.plain_shift_acc([[1, 255]], [[-1, -1]], [[0, 0]], 16).tolist() == [-256]
+    assert C.plain_shift_acc([[255] * 4], [[1] * 4], [[0] * 4], 8).tolist() == [1020 - 1024]      # wraps at acc_bits
+    assert C.plain_relu([-3, 0, 5]).tolist() == [0, 0, 5]
+    x = np.arange(16).reshape(4, 4, 1) * np.array([1, -1, 1, -1]).reshape(1, 4, 1)
+    assert C.plain_maxpool2x2(x)[:, :, 0].tolist() == [[4, 6], [12, 14]]
+    assert C.from_bits(C.to_bits(np.array([-5, 7, -32768]), 16), True).tolist() == [-5, 7, -32768]
+
+
+@pytest.mark.parametrize("w", [1, 2, 3, 4])
+def test_adder_exhaustive(w):
+    for cap in (w, w + 1, 16):
+        nl = C.Netlist(2 * w)
+        out = C.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), cap)
+        assert len(out) == min(w + 1, cap)
+        if w > 1:
+            assert len(nl.gtype) == (5 * w - 3 if cap > w else 5 * w - 6)
+        for a, b in itertools.product(range(1 << w), repeat=2):
+            bits = np.concatenate([C.to_bits(np.array(a), w), C.to_bits(np.array(b), w)])
+            val = nl.run_plain(bits)
+            got = int(C.from_bits(val[out], False))
+            assert got == (a + b) % (1 << len(out))
+
+
+@pytest.mark.parametrize("w", [2, 3, 4])
+def test_subtractor_exhaustive(w):
+    nl = C.Netlist(2 * w)
+    out = C.sub_wrapped(nl, list(range(w)), list(range(w, 2 * w)))
+    assert len(nl.gtype) == 5 * w - 3
+    for a, b in itertools.product(range(1 << w), repeat=2):
+        bits = np.concatenate([C.to_bits(np.array(a), w), C.to_bits(np.array(b), w)])
+        assert int(C.from_bits(nl.run_plain(bits)[out], False)) == (a - b) % (1 << w)
+
+
+def test_adder_cost_is_linear_in_width():
+    # Section 3.3: an 8-bit adder costs about twice a 4-bit adder
+    def cost(w):
+        nl = C.Netlist(2 * w)
+        C.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), 99)
+        return len(nl.gtype)
+    assert cost(4) == 17 and cost(8) == 37 and cost(16) == 77
+
+
+def test_shift_has_no_gates_and_drops_low_bits():
+    nl = C.Netlist(8)
+    t = C.shifted_term(nl, list(range(8)), -3)
+    assert t == [3, 4, 5, 6, 7, nl.ZERO, nl.ZERO, nl.ZERO] and not nl.gtype
+    assert C.shifted_term(nl, list(range(8)), 0) == list(range(8))
+    assert C.shifted_term(nl, list(range(8)), -7) == [7] + [nl.ZERO] * 7
+
+
+def _run_shift_acc(units, terms, in_bits, acc_bits, rng, x=None, sign=None, exp=None):
+    x = rng.integers(0, 1 << in_bits, (units, terms)) if x is None else np.asarray(x)
+    sign = rng.choice([-1, 1], (units, terms)) if sign is None else np.asarray(sign)
+    exp = -rng.integers(0, in_bits, (units, terms)) if exp is None else np.asarray(exp)
+    nl, outs = C.build_shift_acc(units, terms, in_bits, sign, exp, acc_bits)
+    val = nl.run_plain(C.to_bits(x, in_bits))
+    got = C.from_bits(val[np.array(outs)], True)
+    assert np.array_equal(got, C.plain_shift_acc(x, sign, exp, acc_bits)), (x, sign, exp)
+    return nl
+
+
+def test_shift_acc_netlist_equals_integer_sum():
+    rng = np.random.default_rng(0)
+    for terms in (1, 2, 3, 5, 9, 16, 33):
+        _run_shift_acc(3, terms, 8, 16, rng)
+    _run_shift_acc(2, 7, 4, 6, rng)                       # accumulator narrower than the full sum: wraps
+    _run_shift_acc(1, 9, 8, 16, rng, x=[[255] * 9], sign=[[1] * 9], exp=[[0] * 9])
+    _run_shift_acc(1, 9, 8, 16, rng, x=[[255] * 9], sign=[[-1] * 9], exp=[[0] * 9])
+    _run_shift_acc(1, 9, 8, 16, rng, x=[[0] * 9])
+    _run_shift_acc(1, 300, 8, 16, rng, x=[[255] * 300], sign=[[1] * 300], exp=[[0] * 300])     # overflow past 2^16
+
+
+def test_shift_acc_gate_counts():
+    # 576 terms of one sign, 8 -> 16 bits: closed form of the mixed-width tree
+    want = 288 * 37 + 144 * 42 + 72 * 47 + 36 * 52 + 18 * 57 + 9 * 62 + 4 * 67 + 2 * 72 + 74 + 74
+    nl, _ = C.build_shift_acc(1, 576, 8, np.ones((1, 576)), np.zeros((1, 576)), 16)
+    assert len(nl.gtype) == want == 24104
+    # a final subtraction costs 5*16-3 gates
+    s = np.ones((1, 4)); s[0, 3] = -1
+    nl2, _ = C.build_shift_acc(1, 4, 8, s, np.zeros((1, 4)), 16)
+    nl3, _ = C.build_shift_acc(1, 3, 8, np.ones((1, 3)), np.zeros((1, 3)), 16)
+    assert len(nl2.gtype) - len(nl3.gtype) == 77
+
+
+def test_relu_netlist():
+    rng = np.random.default_rng(1)
+    x = np.concatenate([rng.integers(-32768, 32768, 200), [0, -1, 1, -32768, 32767]])
+    nl, outs = C.build_relu(x.size, 16)
+    assert len(nl.gtype) == x.size * 15 and set(nl.levels().tolist()) == {1}
+    got = C.from_bits(nl.run_plain(C.to_bits(x, 16))[np.array(outs)], True)
+    assert np.array_equal(got, C.plain_relu(x))
+
+
+def test_max_netlist_exhaustive_4bit_and_random_16bit():
+    nl = C.Netlist(8)
+    out = C.max_signed(nl, [0, 1, 2, 3], [4, 5, 6, 7])
+    assert len(nl.gtype) == 4 + 3 * 4 + 3 * 4
+    for a, b in itertools.product(range(-8, 8), repeat=2):
+        bits = np.concatenate([C.to_bits(np.array(a), 4), C.to_bits(np.array(b), 4)])
+        assert int(C.from_bits(nl.run_plain(bits)[out], True)) == max(a, b)
+    rng = np.random.default_rng(2)
+    nl = C.Netlist(32)
+    out = C.max_signed(nl, list(range(16)), list(range(16, 32)))
+    assert len(nl.gtype) == 112
+    pairs = rng.integers(-32768, 32768, (300, 2)).tolist() + [[5, 5], [-32768, 32767], [32767, -32768], [-1, 0],
+                                                               [0, -1], [-2, -1], [100, 101]]
+    for a, b in pairs:
+        bits = np.concatenate([C.to_bits(np.array(a), 16), C.to_bits(np.array(b), 16)])
+        assert int(C.from_bits(nl.run_plain(bits)[out], True)) == max(a, b)
+
+
+def test_maxpool_netlist():
+    rng = np.random.default_rng(3)
+    H, W, Cn, bits = 5, 4, 3, 8
+    x = rng.integers(-128, 128, (H, W, Cn))
+    nl, outs = C.build_maxpool(H, W, Cn, bits)
+    per_max = bits + 3 * bits + 3 * bits
+    assert len(nl.gtype) == (H // 2) * (W // 2) * Cn * 3 * per_max
+    got = C.from_bits(nl.run_plain(C.to_bits(x, bits))[np.array(outs)], True).reshape(H // 2, W // 2, Cn)
+    assert np.array_equal(got, C.plain_maxpool2x2(x))
+
+
+def test_levels_are_a_topological_schedule():
+    nl, _ = C.build_shift_acc(1, 9, 8, np.ones((1, 9)), np.zeros((1, 9)), 16)
+    lev = nl.levels()
+    wire_level = {o: l for o, l in zip(nl.out, lev)}
+    for a, b, o in zip(nl.in0, nl.in1, nl.out):
+        assert wire_level[o] > max(wire_level.get(a, 0), wire_level.get(b, 0))
+    assert lev.min() == 1
+
+
+def test_small_circuits_on_ciphertexts(toy_keys):
+    K = toy_keys
+    rng = np.random.default_rng(4)
+    # 3 terms of 3 bits, mixed signs, 5-bit accumulator
+    x = np.array([[5, 7, 2]]); sign = np.array([[1, -1, 1]]); exp = np.array([[0, -1, 0]])
+    nl, outs = C.build_shift_acc(1, 3, 3, sign, exp, 5)
+    cts = tfhe.encrypt_bits(K, C.to_bits(x, 3).ravel(), 77)
+    pool = nl.run_encrypted(K, cts, threads=8)
+    got = C.from_bits(tfhe.decrypt_bits(K, pool[np.array(outs).ravel()]).reshape(1, 5), True)
+    assert got.tolist() == C.plain_shift_acc(x, sign, exp, 5).tolist() == [4]
+    # the level-parallel schedule gives the same ciphertexts as list order
+    pool1 = nl.run_encrypted(K, cts, threads=1)
+    assert np.array_equal(pool, pool1)
+    # max of two 3-bit values then relu
+    nl, out = C.Netlist(6), None
+    out = C.max_signed(nl, [0, 1, 2], [3, 4, 5])
+    for a, b in ((-3, 2), (1, -4)):
+        cts = tfhe.encrypt_bits(K, np.concatenate([C.to_bits(np.array(a), 3), C.to_bits(np.array(b), 3)]), 5)
+        pool = nl.run_encrypted(K, cts, threads=8)
+        assert int(C.from_bits(tfhe.decrypt_bits(K, pool[out]), True)) == max(a, b)

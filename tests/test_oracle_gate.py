@@ -1,0 +1,370 @@
+"""Pins for the oracle's samples, external product, blind rotation, extraction,
+key switch and whole gates (CPU only).  Nothing here compares the oracle with
+itself: expected values come from plaintext logic, phase algebra done in Python
+integers, and the analytic noise bound."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import tfhe
+
+M32 = 0xFFFFFFFF
+EIGHTH = 1 << 29
+
+
+def centred(x):
+    """torus word(s) -> signed distance from 0 in units of 2^-32"""
+    return ((np.asarray(x, np.int64) + (1 << 31)) & M32) - (1 << 31)
+
+
+def py_ring_phase(ring_key, acc):
+    """B - A*s' in Z[X]/(X^N+1) with python integers (independent of the oracle's product)."""
+    N = acc.shape[1]
+    out = [int(v) for v in acc[1]]
+    for i in range(N):
+        if not ring_key[i]:
+            continue
+        for j in range(N):
+            e = i + j
+            if e < N:
+                out[e] -= int(acc[0][j])
+            else:
+                out[e - N] += int(acc[0][j])
+    return np.array([v & M32 for v in out], np.int64)
+
+
+TINY = tfhe.Params(n=4, N=8, lwe_std=0.0, bk_std=0.0)
+SMALL0 = tfhe.Params(n=16, N=32, lwe_std=0.0, bk_std=0.0)
+
+
+# ----------------------------------------------------------------- keys
+def test_key_bits_and_sizes(toy_keys):
+    K = toy_keys
+    assert set(np.unique(K.lwe_key)) <= {0, 1} and set(np.unique(K.ring_key)) <= {0, 1}
+    assert 40 < K.lwe_key.sum() < 88 and 100 < K.ring_key.sum() < 156
+    assert K.bk.shape == (128, 2, 3, 2, 256) and K.ks.shape == (256, 8, 3, 129)
+
+
+def test_keygen_does_not_depend_on_anything_but_the_seed():
+    a = tfhe.keygen(TINY, 5)
+    b = tfhe.keygen(TINY, 5)
+    c = tfhe.keygen(TINY, 6)
+    assert np.array_equal(a.bk, b.bk) and np.array_equal(a.ks, b.ks)
+    assert not np.array_equal(a.bk, c.bk)
+
+
+def test_bk_rows_are_trlwe_of_zero_plus_gadget(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    bound = 6 * P.bk_std * 2 ** 32 + 1
+    errs = []
+    for i in (0, 1, 2, 63, 127):
+        for c in range(2):
+            for p in range(P.l):
+                ph = py_ring_phase(K.ring_key, K.bk[i, c, p])
+                g = int(K.lwe_key[i]) << (32 - (p + 1) * P.bg_bit)
+                if c == 1:                                     # gadget on the body: phase = E + g
+                    want = np.zeros(P.N, np.int64); want[0] = g
+                else:                                          # gadget on the mask: phase = E - g*s'
+                    want = (-g * K.ring_key.astype(np.int64))
+                e = centred(ph - want)
+                assert np.abs(e).max() < bound, (i, c, p)
+                errs.append(e)
+    errs = np.concatenate(errs)
+    assert abs(errs.std() / (P.bk_std * 2 ** 32) - 1) < 0.05
+
+
+def test_ks_rows_encrypt_scaled_key_bits(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    bound = 6 * P.lwe_std * 2 ** 32
+    errs = []
+    for i in (0, 5, 255):
+        for j in range(P.ks_t):
+            for v in (1, 2, 3):
+                ph = tfhe.lwe_phase(K.lwe_key, K.ks[i, j, v - 1])
+                want = (int(K.ring_key[i]) * v << (32 - (j + 1) * P.ks_basebit)) & M32
+                e = int(centred(ph - want))
+                assert abs(e) < bound
+                errs.append(e)
+    assert 0.7 < np.std(errs) / (P.lwe_std * 2 ** 32) < 1.3
+
+
+def test_fresh_encryptions_decrypt_and_have_the_stated_noise(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    rng = np.random.default_rng(1)
+    bits = rng.integers(0, 2, 400).astype(np.uint8)
+    cts = tfhe.encrypt_bits(K, bits, 99)
+    assert np.array_equal(tfhe.decrypt_bits(K, cts), bits)
+    ph = np.array([tfhe.lwe_phase(K.lwe_key, c) for c in cts], np.int64)
+    want = np.where(bits == 1, EIGHTH, -EIGHTH)
+    e = centred(ph - want)
+    assert abs(e.std() / (P.lwe_std * 2 ** 32) - 1) < 0.15
+    # same seed, same ciphertexts; mask words are uniform
+    assert np.array_equal(cts, tfhe.encrypt_bits(K, bits, 99))
+    assert not np.array_equal(cts[:, :-1], tfhe.encrypt_bits(K, bits, 100)[:, :-1])
+    assert abs(cts[:, :-1].astype(np.float64).mean() / 2 ** 32 - 0.5) < 0.01
+
+
+# ----------------------------------------------------------------- linear combination
+def test_lincomb_phases_in_eighths():
+    # noiseless trivial inputs: phase in units of 1/8 must have the gate's sign pattern
+    table = {"AND": [-3, -1, -1, 1], "NAND": [3, 1, 1, -1], "OR": [-1, 1, 1, 3], "NOR": [1, -1, -1, -3],
+             "XOR": [-2, 2, 2, -2], "XNOR": [2, -2, -2, 2], "ANDNY": [-1, 1, -3, -1], "ANDYN": [-1, -3, 1, -1],
+             "ORNY": [1, 3, -1, 1], "ORYN": [1, -1, 3, 1]}
+    n = 5
+    for name, want in table.items():
+        got = []
+        for a in (0, 1):
+            for b in (0, 1):
+                ca = np.zeros(n + 1, np.uint32); ca[n] = (EIGHTH if a else -EIGHTH) & M32
+                cb = np.zeros(n + 1, np.uint32); cb[n] = (EIGHTH if b else -EIGHTH) & M32
+                out = tfhe.gate_lincomb(tfhe.GATES[name], ca, cb)
+                assert not out[:n].any()
+                got.append(int(centred(out[n])) // EIGHTH)
+        # 6/8 and -6/8 wrap to -2/8 and 2/8
+        got = [g - 8 if g > 4 else g + 8 if g < -4 else g for g in got]
+        assert got == want, name
+
+
+def test_lincomb_acts_on_masks_too():
+    rng = np.random.default_rng(2)
+    ca = rng.integers(0, 1 << 32, 9, dtype=np.uint64).astype(np.uint32)
+    cb = rng.integers(0, 1 << 32, 9, dtype=np.uint64).astype(np.uint32)
+    out = tfhe.gate_lincomb(tfhe.GATES["ANDNY"], ca, cb).astype(np.int64)
+    assert np.array_equal(out[:8], (cb[:8].astype(np.int64) - ca[:8]) & M32)
+    out = tfhe.gate_lincomb(tfhe.GATES["XNOR"], ca, cb).astype(np.int64)
+    assert np.array_equal(out[:8], (-2 * (cb[:8].astype(np.int64) + ca[:8])) & M32)
+
+
+# ----------------------------------------------------------------- external product / CMux
+def test_external_product_multiplies_the_phase_by_the_key_bit(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    rng = np.random.default_rng(4)
+    D = np.zeros((2, P.N), np.uint32)
+    D[0] = rng.integers(0, 1 << 32, P.N, dtype=np.uint64).astype(np.uint32)
+    msg = rng.integers(0, 1 << 32, P.N, dtype=np.uint64).astype(np.uint32)
+    D[1] = (py_ring_phase(K.ring_key, np.stack([D[0], np.zeros(P.N, np.uint32)])) * -1 + msg) & M32  # B = A*s' + msg
+    assert np.array_equal(py_ring_phase(K.ring_key, D), msg.astype(np.int64))
+    # worst-case bound: 2lN digits of size <= Bg/2 times 6 sigma, plus rounding (1+N) * 2^10
+    bound = 2 * P.l * P.N * 64 * 6 * P.bk_std * 2 ** 32 + (1 + P.N) * 1024
+    seen = set()
+    for i in range(12):
+        out = tfhe.external_product(P, K.bk[i], D)
+        ph = py_ring_phase(K.ring_key, out)
+        want = msg.astype(np.int64) * int(K.lwe_key[i])
+        assert np.abs(centred(ph - want)).max() < bound, i
+        seen.add(int(K.lwe_key[i]))
+    assert seen == {0, 1}
+
+
+def test_external_product_is_linear_in_rows_brute_force():
+    # tiny ring: recompute sum_rows digit(X) * row with python integers
+    P = tfhe.Params(n=1, N=4, lwe_std=0.0, bk_std=0.0)
+    rng = np.random.default_rng(8)
+    G = rng.integers(0, 1 << 32, (2, P.l, 2, P.N), dtype=np.uint64).astype(np.uint32)
+    D = rng.integers(0, 1 << 32, (2, P.N), dtype=np.uint64).astype(np.uint32)
+    out = tfhe.external_product(P, G, D)
+    want = np.zeros((2, P.N), object)
+    for c in range(2):
+        digs = np.array([tfhe.gadget_decompose(P, int(x)) for x in D[c]])       # [N][l]
+        for p in range(P.l):
+            for comp in range(2):
+                for i in range(P.N):
+                    for j in range(P.N):
+                        e = i + j
+                        term = int(digs[i, p]) * int(G[c, p, comp, j])
+                        if e < P.N:
+                            want[comp, e] += term
+                        else:
+                            want[comp, e - P.N] -= term
+    assert np.array_equal(out.astype(np.int64), np.vectorize(lambda v: v & M32)(want).astype(np.int64))
+
+
+def expected_rotation(N, phibar, mu=EIGHTH):
+    """X^(-phibar) * (mu + mu X + ...): coefficient j is +mu iff (j + phibar) mod 2N < N"""
+    j = np.arange(N)
+    return np.where(((j + phibar) % (2 * N)) < N, mu, -mu).astype(np.int64)
+
+
+def test_blind_rotation_with_noiseless_keys_rotates_by_the_phase_tiny_ring():
+    P = TINY
+    rng = np.random.default_rng(12)
+    for seed in range(6):
+        K = tfhe.keygen(P, seed)
+        cases = [(rng.integers(0, 2 * P.N, P.n), int(rng.integers(0, 2 * P.N))) for _ in range(300)]
+        cases += [(np.zeros(P.n, np.int64), b) for b in range(2 * P.N)]
+        cases += [(np.full(P.n, a), 0) for a in range(2 * P.N)]
+        for abar, bbar in cases:
+            acc = tfhe.blind_rotate(P, K.bk, abar, bbar)
+            ph = py_ring_phase(K.ring_key, acc)
+            phibar = (bbar - int(np.dot(abar, K.lwe_key))) % (2 * P.N)
+            err = centred(ph - expected_rotation(P.N, phibar))
+            # only gadget rounding remains: each step adds at most (1+N) * 2^10
+            assert np.abs(err).max() <= P.n * (1 + P.N) * 1024, (seed, abar, bbar)
+
+
+def test_blind_rotation_toy_params_noiseless():
+    P = tfhe.Params(n=128, N=256, lwe_std=0.0, bk_std=0.0)
+    K = tfhe.keygen(P, 77)
+    rng = np.random.default_rng(5)
+    for _ in range(2):
+        abar = rng.integers(0, 2 * P.N, P.n)
+        bbar = int(rng.integers(0, 2 * P.N))
+        acc = tfhe.blind_rotate(P, K.bk, abar, bbar)
+        ph = py_ring_phase(K.ring_key, acc)
+        phibar = (bbar - int(np.dot(abar, K.lwe_key))) % (2 * P.N)
+        err = centred(ph - expected_rotation(P.N, phibar))
+        assert np.abs(err).max() <= P.n * (1 + P.N) * 1024
+        # and statistically far below the worst case
+        assert err.std() < math.sqrt(P.n * (1 + P.N / 2) / 12.0) * 2048 * 1.5
+
+
+def test_blind_rotation_zero_mask_is_a_plain_rotation():
+    P = SMALL0
+    K = tfhe.keygen(P, 3)
+    for bbar in (0, 1, 31, 32, 33, 63):
+        acc = tfhe.blind_rotate(P, K.bk, np.zeros(P.n, np.int64), bbar)
+        assert not acc[0].any()
+        assert np.array_equal(centred(acc[1]), expected_rotation(P.N, bbar))
+
+
+# ----------------------------------------------------------------- extraction, key switch
+def test_sample_extract_phase_is_constant_coefficient_of_ring_phase(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    rng = np.random.default_rng(9)
+    for _ in range(5):
+        acc = rng.integers(0, 1 << 32, (2, P.N), dtype=np.uint64).astype(np.uint32)
+        ext = tfhe.sample_extract(acc)
+        assert tfhe.lwe_phase(K.ring_key, ext) == int(py_ring_phase(K.ring_key, acc)[0])
+
+
+def test_key_switch_keeps_the_phase(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    rng = np.random.default_rng(10)
+    errs = []
+    # rounding: N terms of at most 2^(32-17); noise: at most N*t rows
+    bound = P.N * 2 ** 15 + 6 * P.lwe_std * 2 ** 32 * math.sqrt(P.N * P.ks_t)
+    for _ in range(20):
+        ext = rng.integers(0, 1 << 32, P.N + 1, dtype=np.uint64).astype(np.uint32)
+        out = tfhe.key_switch(P, K.ks, ext)
+        e = int(centred(tfhe.lwe_phase(K.lwe_key, out) - tfhe.lwe_phase(K.ring_key, ext)))
+        assert abs(e) < bound
+        errs.append(e)
+    v_ks = P.N * P.ks_t * P.lwe_std ** 2 + P.N * 2.0 ** (-2 * (P.ks_t * P.ks_basebit + 1)) / 3
+    assert np.std(errs) / 2 ** 32 < 1.6 * math.sqrt(v_ks)
+
+
+def test_key_switch_of_zero_mask_is_trivial(toy_keys):
+    K, P = toy_keys, toy_keys.params
+    ext = np.zeros(P.N + 1, np.uint32); ext[P.N] = 12345
+    out = tfhe.key_switch(P, K.ks, ext)
+    assert not out[:P.n].any() and out[P.n] == 12345
+    # mask words below the rounding threshold do not select any row either
+    ext[:P.N] = (1 << 15) - 1
+    out = tfhe.key_switch(P, K.ks, ext)
+    assert not out[:P.n].any() and out[P.n] == 12345
+
+
+# ----------------------------------------------------------------- whole gates
+def _truth_table_run(K, reps, threads=8):
+    P = K.params
+    names = list(tfhe.GATES)
+    rng = np.random.default_rng(21)
+    combos = [(a, b) for a in (0, 1) for b in (0, 1)]
+    in_bits = np.array([ab for _ in range(reps) for ab in combos], np.uint8).ravel()          # [reps*4*2]
+    fresh = tfhe.encrypt_bits(K, in_bits, 4242)
+    n_in = fresh.shape[0]
+    gt, i0, i1 = [], [], []
+    for gi, name in enumerate(names):
+        for r in range(reps * 4):
+            gt.append(tfhe.GATES[name]); i0.append(2 * r); i1.append(2 * r + 1)
+    out = np.arange(n_in, n_in + len(gt))
+    pool = np.zeros((n_in + len(gt), P.n + 1), np.uint32)
+    pool[:n_in] = fresh
+    tfhe.eval_gates(K, pool, gt, i0, i1, out, threads)
+    return names, in_bits.reshape(-1, 2), np.array(gt), np.array(i0) // 2, pool[n_in:]
+
+
+PLAIN = {"NAND": lambda a, b: 1 - (a & b), "AND": lambda a, b: a & b, "OR": lambda a, b: a | b,
+         "XOR": lambda a, b: a ^ b, "XNOR": lambda a, b: 1 - (a ^ b), "NOR": lambda a, b: 1 - (a | b),
+         "ANDNY": lambda a, b: (1 - a) & b, "ANDYN": lambda a, b: a & (1 - b),
+         "ORNY": lambda a, b: (1 - a) | b, "ORYN": lambda a, b: a | (1 - b)}
+
+
+def _check_gates(K, reps, std_bound):
+    names, pairs, gt, pair_idx, outs = _truth_table_run(K, reps)
+    code_to_name = {v: k for k, v in tfhe.GATES.items()}
+    errs = []
+    for g in range(len(gt)):
+        a, b = (int(v) for v in pairs[pair_idx[g]])
+        want = PLAIN[code_to_name[int(gt[g])]](a, b)
+        ph = tfhe.lwe_phase(K.lwe_key, outs[g])
+        assert (int(centred(ph)) > 0) == bool(want), (code_to_name[int(gt[g])], a, b)
+        errs.append(int(centred(ph - (EIGHTH if want else -EIGHTH))))
+    errs = np.array(errs, np.float64) / 2 ** 32
+    assert np.abs(errs).max() < 1 / 16
+    assert errs.std() < std_bound, errs.std()
+    return errs
+
+
+def noise_std_bound(P, worst_digits=True):
+    beta = (1 << P.bg_bit) ** 2 / (4.0 if worst_digits else 12.0)
+    eps = 2.0 ** -(P.l * P.bg_bit + 1)
+    v_br = P.n * 2 * P.l * P.N * beta * P.bk_std ** 2 + P.n * (1 + P.N) * eps ** 2
+    v_ks = P.N * P.ks_t * P.lwe_std ** 2 + P.N * 2.0 ** (-2 * (P.ks_t * P.ks_basebit + 1)) / 3
+    return math.sqrt(v_br + v_ks)
+
+
+def test_gate_truth_tables_toy(toy_keys):
+    errs = _check_gates(toy_keys, reps=4, std_bound=noise_std_bound(toy_keys.params))
+    # the bound is not vacuous: measured noise is within a factor 3 of the average-case formula
+    assert errs.std() > noise_std_bound(toy_keys.params, worst_digits=False) / 3
+
+
+def test_gate_truth_tables_real(real_keys):
+    _check_gates(real_keys, reps=1, std_bound=noise_std_bound(real_keys.params))
+
+
+def test_real_noise_bound_value():
+    # value derived for n=630, N=1024: std below 2^-7.8 of the torus
+    assert noise_std_bound(tfhe.REAL) < 2.0 ** -7.8 * 1.05
+    assert noise_std_bound(tfhe.REAL, worst_digits=False) < 2.0 ** -8.1
+
+
+def test_gates_compose_over_depth_32_chain(toy_keys):
+    # bootstrapped outputs feed further gates: XOR doubles its input noise, the worst case
+    K = toy_keys
+    bits = np.array([1, 0, 1, 1], np.uint8)
+    cts = tfhe.encrypt_bits(K, bits, 31)
+    acc_ct, acc_bit = cts[0], 1
+    other = [(cts[1], 0), (cts[2], 1), (cts[3], 1)]
+    for d in range(32):
+        c, b = other[d % 3]
+        name = ("XOR", "NAND", "XNOR", "ORNY")[d % 4]
+        acc_ct = tfhe.gate(K, tfhe.GATES[name], acc_ct, c)
+        acc_bit = PLAIN[name](acc_bit, b)
+        assert int(tfhe.decrypt_bits(K, acc_ct)[0]) == acc_bit, d
+    ph = tfhe.lwe_phase(K.lwe_key, acc_ct)
+    assert abs(int(centred(ph - (EIGHTH if acc_bit else -EIGHTH)))) < 2 ** 32 / 16
+
+
+def test_bootstrap_output_is_independent_of_input_noise_sign(toy_keys):
+    # bootstrapping a fresh ciphertext returns +-1/8 according to the sign of its phase only
+    K = toy_keys
+    cts = tfhe.encrypt_bits(K, np.array([0, 1], np.uint8), 55)
+    for c, bit in zip(cts, (0, 1)):
+        out = tfhe.bootstrap(K, c)
+        assert int(tfhe.decrypt_bits(K, out)[0]) == bit
+
+
+def test_oracle_digests_are_frozen():
+    # not a correctness pin (the paper prints no ciphertexts): guards against accidental drift
+    import importlib.util
+    import json
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    with open(os.path.join(here, "oracle_digests.json")) as f:
+        assert mod.compute() == json.load(f)
