@@ -1,0 +1,176 @@
+/*
+ * she.h - C ABI of the MI355X library for SHE's encrypted-inference hot path:
+ * batched bootstrapped TFHE binary gates and the layer operators that lower to them.
+ *
+ * Citations are to "SHE: A Fast and Accurate Deep Neural Network for Encrypted
+ * Data" (arXiv 1906.00148).  The paper states the problem (client encrypts bit by
+ * bit, server evaluates 2-input homomorphic gates, shifts, accumulations, ReLU and
+ * max pooling on ciphertexts, client decrypts) and cites the TFHE gate
+ * bootstrapping without restating it; the encodings and rounding rules this library
+ * fixes where the paper is silent are stated with the calls below.
+ *
+ * Conventions that hold for every call:
+ *  - All pointer arguments are HOST pointers unless a comment says "device".  They
+ *    are caller-owned and not retained after the call returns.
+ *  - Ciphertexts live in a device-resident pool of `pool_capacity` TLWE slots owned
+ *    by the context and addressed by a 32-bit id in [0, pool_capacity).  The caller
+ *    decides which id holds what.  A slot is n+1 Torus32 words (a_0..a_{n-1}, b).
+ *    Temporaries of the layer operators live in a separate internal buffer.
+ *  - Torus32: a uint32_t t stands for t / 2^32 in R/Z; arithmetic is modulo 2^32.
+ *    Bit 1 is encoded as +2^29 (+1/8), bit 0 as -2^29; decryption takes the sign of
+ *    the phase.  Integers are vectors of bit ids, least significant bit first,
+ *    two's complement where signed (Section 3.2: data are encrypted bit by bit and
+ *    keep the order of the plaintext bits).
+ *  - Return value: SHE_OK (0) or a negative code; she_last_error() gives the text.
+ *    Nothing is thrown across this boundary.  On error the pool contents that the
+ *    failing call was going to write are unspecified; inputs are untouched.
+ *  - Calls run on the context's HIP stream and return after the work has finished
+ *    (they synchronise that stream), unless stated otherwise.  A context is not
+ *    thread-safe.  One GPU: the context uses the HIP device current at she_keygen.
+ *  - There is no CPU fallback: without a usable GPU every call that computes
+ *    returns SHE_EDEVICE.
+ */
+#ifndef SHE_H
+#define SHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct she_ctx she_ctx; /* opaque: keys (secret ones too), device buffers, stream */
+
+/* TFHE parameter set (Section 4, "TFHE setting", names the three sample levels; the
+ * gate-bootstrapping values used by the benchmarks are n=630, N=1024, k=1, bg_bit=7,
+ * l=3, ks_t=8, ks_basebit=2, lwe_std=2^-15, bk_std=2^-25).  Supported: k = 1;
+ * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8;
+ * ks_t*ks_basebit <= 16 with ks_basebit <= 4. */
+typedef struct {
+    uint32_t n;          /* TLWE dimension */
+    uint32_t N;          /* ring degree of TRLWE / TRGSW samples */
+    uint32_t k;          /* number of TRLWE mask polynomials */
+    uint32_t bg_bit;     /* log2 of the gadget base Bg */
+    uint32_t l;          /* gadget length */
+    uint32_t ks_t;       /* key-switch digits per coefficient */
+    uint32_t ks_basebit; /* log2 of the key-switch base */
+    double lwe_std;      /* noise of fresh TLWE samples and key-switch rows (fraction of the torus) */
+    double bk_std;       /* noise of bootstrapping-key rows */
+} she_params;
+
+enum { SHE_OK = 0, SHE_EINVAL = -1, SHE_ENOMEM = -2, SHE_EDEVICE = -3, SHE_ERANGE = -4 };
+
+/* Gate codes of she_eval_gates (Section 3.1: any 2-input binary homomorphic operation).
+ * ANDNY = (not a) and b, ANDYN = a and (not b), ORNY = (not a) or b, ORYN = a or (not b).
+ * NOT, copies and constants are not gates: the layer operators realise them as
+ * re-wiring or as noiseless trivial ciphertexts (Section 3.2: a shift costs no gate). */
+enum { SHE_NAND = 0, SHE_AND, SHE_OR, SHE_XOR, SHE_XNOR, SHE_NOR, SHE_ANDNY, SHE_ANDYN, SHE_ORNY, SHE_ORYN,
+       SHE_NUM_GATES };
+
+/* Section 2 ("Homomorphic Encryption": key pair of the client).  Generates the TLWE key,
+ * the ring key, the bootstrapping key BK_i = TRGSW(s_i) and the key-switching key from
+ * `seed`, uploads them, transforms BK to the kernels' spectral layout and allocates the
+ * pool.  *out receives a new context; release it with she_free.  Errors: SHE_EINVAL
+ * (unsupported parameters, null pointers), SHE_ENOMEM (host or device allocation),
+ * SHE_EDEVICE (no GPU / HIP failure). */
+int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, she_ctx **out);
+
+/* Frees every host and device resource of the context.  NULL is allowed. */
+void she_free(she_ctx *ctx);
+
+/* Section 2 (encryption function) / Section 3.2 (bit-by-bit encryption).  Encrypts
+ * bits[0..nbits) (each 0 or 1) as fresh TLWE samples; sample k uses the noise stream
+ * (enc_seed, k) and is stored in slot dst_ids[k].  Errors: SHE_ERANGE for an id outside
+ * the pool, SHE_EINVAL for a bit other than 0/1 or null pointers. */
+int she_encrypt_bits(she_ctx *ctx, const uint8_t *bits, size_t nbits, uint64_t enc_seed, const uint32_t *dst_ids);
+
+/* Section 2 (decryption function).  bits_out[k] = 1 iff the phase of slot ids[k] is
+ * positive.  Uses the secret key held by the context. */
+int she_decrypt(she_ctx *ctx, const uint32_t *ids, size_t count, uint8_t *bits_out);
+
+/* Section 3.1 (2-input homomorphic gates), Section 2 (bootstrapping keeps the noise in
+ * check).  Evaluates ONE circuit level: ngates mutually independent bootstrapped gates,
+ * slot out[g] <- type[g](slot in0[g], slot in1[g]).  Per gate: TLWE linear combination,
+ * modulus switch, blind rotation (n CMux external products), sample extraction, key
+ * switch.  All four arrays have ngates entries.  No out id may equal an in id of the
+ * same call or another out id (SHE_EINVAL); ids outside the pool give SHE_ERANGE; a
+ * type >= SHE_NUM_GATES gives SHE_EINVAL.  ngates = 0 is a no-op. */
+int she_eval_gates(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1,
+                   const uint32_t *out, size_t ngates);
+
+/* Section 3.2 (logarithmic quantization: sum_i binaryshift(input_i, weightQ_i)) and
+ * Section 3.3 (mixed-bitwidth accumulator).  For each of `units` output neurons:
+ *   out = sum_t w_sign[t] * (x_t >> -w_exp[t])   modulo 2^acc_bits (two's complement),
+ * x_t unsigned in_bits-bit inputs.  Shifts re-wire ids (dropped low bits, trivial zeros on
+ * top); positive and negative terms are summed by separate adder trees whose level j uses
+ * min(in_bits+j, acc_bits)-bit ripple-carry adders, followed by one subtraction.
+ *   x_ids   [units][terms][in_bits]  pool ids, LSB first
+ *   w_sign  [units][terms]           +1 or -1
+ *   w_exp   [units][terms]           in [-(in_bits-1), 0]
+ *   out_ids [units][acc_bits]        pool ids that receive the result bits
+ * Requires 1 <= in_bits <= acc_bits <= 32.  All units are levelized together and each
+ * level is one batched gate evaluation.  *gates_out (may be NULL) receives the number of
+ * bootstrapped gates evaluated.  out ids must not overlap x ids. */
+int she_shift_acc(she_ctx *ctx, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
+                  const int8_t *w_sign, const int8_t *w_exp, uint32_t acc_bits, const uint32_t *out_ids,
+                  uint64_t *gates_out);
+
+/* Section 3.1 (ReLU(x) = max(x, 0) from Boolean gates).  x_ids [count][bits] two's
+ * complement, out_ids [count][bits]; every lower bit is masked by the sign bit, the
+ * result's sign bit is a trivial zero.  bits >= 2.  One level of count*(bits-1) gates. */
+int she_relu(she_ctx *ctx, const uint32_t *x_ids, uint32_t count, uint32_t bits, const uint32_t *out_ids,
+             uint64_t *gates_out);
+
+/* Section 3.1 (max pooling unit).  2x2 window, stride 2 over x_ids [H][W][C][bits]
+ * (two's complement); out_ids [H/2][W/2][C][bits].  A ragged last row or column is
+ * dropped.  Each max is a ripple comparator plus one MUX per bit; MUX(s,u,v) is lowered
+ * to OR(AND(s,u), ANDNY(s,v)). */
+int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
+                const uint32_t *out_ids, uint64_t *gates_out);
+
+/* ---- diagnostics and plumbing (not part of the paper's problem statement) ---- */
+
+/* Copies slot `id` to dst[0..n] (a_0..a_{n-1}, b) / overwrites it from src. */
+int she_read_ct(she_ctx *ctx, uint32_t id, uint32_t *dst);
+int she_write_ct(she_ctx *ctx, uint32_t id, const uint32_t *src);
+
+/* Copies the generated keys to caller buffers (any may be NULL): lwe_key[n] and
+ * ring_key[N] bits, bk[n][2][l][2][N] and ks[N][ks_t][2^ks_basebit-1][n+1] Torus32
+ * words in the logical layout used for generation (not the device layout). */
+int she_export_keys(she_ctx *ctx, uint8_t *lwe_key, uint8_t *ring_key, uint32_t *bk, uint32_t *ks);
+
+/* Work of later calls is enqueued on `hip_stream` (a hipStream_t; NULL = default stream). */
+int she_set_stream(she_ctx *ctx, void *hip_stream);
+
+/* Replaces the pool by caller-owned DEVICE memory of at least she_pool_bytes(ctx) bytes
+ * (256-byte aligned); the old pool's contents are not copied.  The caller keeps ownership
+ * and must keep it alive until she_free or the next she_bind_pool. */
+int she_bind_pool(she_ctx *ctx, void *dev_ptr, size_t bytes);
+size_t she_pool_bytes(const she_ctx *ctx);
+
+/* Enqueues one level like she_eval_gates but takes DEVICE arrays, validates nothing but
+ * ngates, and does not synchronise: for timing loops and callers that keep netlists on
+ * the device.  The arrays must stay valid until the stream has finished. */
+int she_eval_gates_device(she_ctx *ctx, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                          const uint32_t *d_out, size_t ngates);
+
+/* Largest distance from an integer seen by the blind rotation's rounding of inverse
+ * transform outputs since the last reset (0 <= value <= 0.5); only recorded while
+ * tracking is on (slower kernel).  Exact integer results need this to stay well below 0.5. */
+int she_set_round_tracking(she_ctx *ctx, int on);
+int she_get_round_error(she_ctx *ctx, double *max_abs_frac, int reset);
+
+/* Milliseconds spent by the last she_eval_gates / layer-operator call in each kernel
+ * family, measured with HIP events on the context's stream: ms[0] linear combination,
+ * ms[1] blind rotation + extraction, ms[2] key switch, ms[3] number of levels launched. */
+int she_last_timing(const she_ctx *ctx, double ms[4]);
+
+/* Text of the last error of this context ("" if none).  ctx may be NULL: then the text
+ * of the last failed she_keygen of the calling thread. */
+const char *she_last_error(const she_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SHE_H */

@@ -1,0 +1,7 @@
+"""MI355X-native batched bootstrapped TFHE gates and SHE layer operators (arXiv 1906.00148).
+
+Thin ctypes binding over the C ABI in include/she.h.  Every step of the path runs in the HIP
+library; this package only marshals arguments.  PyTorch is used for the pool's device memory
+and for the stream the kernels run on.
+"""
+from .binding import (GATES, REAL, TOY, Context, Params, SheError, lib_path, load_library)  # noqa: F401

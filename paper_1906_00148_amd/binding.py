@@ -1,0 +1,241 @@
+"""ctypes binding with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+GATES = {"NAND": 0, "AND": 1, "OR": 2, "XOR": 3, "XNOR": 4, "NOR": 5, "ANDNY": 6, "ANDYN": 7, "ORNY": 8, "ORYN": 9}
+
+
+class SheError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"she error {code}: {text}")
+        self.code = code
+
+
+class _CParams(C.Structure):
+    _fields_ = [
+        ("n", C.c_uint32), ("N", C.c_uint32), ("k", C.c_uint32), ("bg_bit", C.c_uint32), ("l", C.c_uint32),
+        ("ks_t", C.c_uint32), ("ks_basebit", C.c_uint32), ("lwe_std", C.c_double), ("bk_std", C.c_double),
+    ]
+
+
+@dataclass(frozen=True)
+class Params:
+    n: int
+    N: int
+    k: int = 1
+    bg_bit: int = 7
+    l: int = 3
+    ks_t: int = 8
+    ks_basebit: int = 2
+    lwe_std: float = 2.0 ** -15
+    bk_std: float = 2.0 ** -25
+
+
+TOY = Params(n=128, N=256)
+REAL = Params(n=630, N=1024)
+
+_lib = None
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libshe_hip.so")
+
+
+def load_library() -> C.CDLL:
+    """Loads the built HIP library; builds it first only if no built library exists.
+    There is no fallback: a missing or unloadable library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    L = C.CDLL(path)
+    u8p, u32p, i8p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint32), C.POINTER(C.c_int8)
+    ctx, u64p = C.c_void_p, C.POINTER(C.c_uint64)
+    sigs = {
+        "she_keygen": (C.c_int, [C.POINTER(_CParams), C.c_uint64, C.c_uint32, C.POINTER(C.c_void_p)]),
+        "she_free": (None, [ctx]),
+        "she_encrypt_bits": (C.c_int, [ctx, u8p, C.c_size_t, C.c_uint64, u32p]),
+        "she_decrypt": (C.c_int, [ctx, u32p, C.c_size_t, u8p]),
+        "she_eval_gates": (C.c_int, [ctx, u8p, u32p, u32p, u32p, C.c_size_t]),
+        "she_shift_acc": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, u32p, u64p]),
+        "she_relu": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, u32p, u64p]),
+        "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
+        "she_read_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
+        "she_write_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
+        "she_export_keys": (C.c_int, [ctx, u8p, u8p, u32p, u32p]),
+        "she_set_stream": (C.c_int, [ctx, C.c_void_p]),
+        "she_bind_pool": (C.c_int, [ctx, C.c_void_p, C.c_size_t]),
+        "she_pool_bytes": (C.c_size_t, [ctx]),
+        "she_eval_gates_device": (C.c_int, [ctx, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+        "she_set_round_tracking": (C.c_int, [ctx, C.c_int]),
+        "she_get_round_error": (C.c_int, [ctx, C.POINTER(C.c_double), C.c_int]),
+        "she_last_timing": (C.c_int, [ctx, C.POINTER(C.c_double)]),
+        "she_last_error": (C.c_char_p, [ctx]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _u8(a):
+    return np.ascontiguousarray(a, dtype=np.uint8)
+
+
+def _u32(a):
+    return np.ascontiguousarray(a, dtype=np.uint32)
+
+
+def _i8(a):
+    return np.ascontiguousarray(a, dtype=np.int8)
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(C.POINTER(ty))
+
+
+class Context:
+    """Owns one she_ctx.  Method names mirror the C calls (she_ prefix dropped)."""
+
+    def __init__(self, params: Params, seed: int, pool_capacity: int, use_torch_pool: bool = True):
+        self._L = load_library()
+        self.params = params
+        self.capacity = int(pool_capacity)
+        cp = _CParams(params.n, params.N, params.k, params.bg_bit, params.l, params.ks_t, params.ks_basebit,
+                      params.lwe_std, params.bk_std)
+        h = C.c_void_p()
+        rc = self._L.she_keygen(C.byref(cp), seed, self.capacity, C.byref(h))
+        if rc:
+            raise SheError(rc, (self._L.she_last_error(None) or b"").decode())
+        self._h = h
+        self._pool_tensor = None
+        if use_torch_pool:
+            import torch
+            nbytes = self._L.she_pool_bytes(self._h)
+            self._pool_tensor = torch.zeros(nbytes // 4, dtype=torch.int32, device="cuda")
+            self._check(self._L.she_bind_pool(self._h, C.c_void_p(self._pool_tensor.data_ptr()), nbytes))
+            self.set_stream(torch.cuda.current_stream().cuda_stream)
+
+    # ---- plumbing
+    def _check(self, rc: int):
+        if rc:
+            raise SheError(rc, (self._L.she_last_error(self._h) or b"").decode())
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.she_free(self._h)
+            self._h = None
+            self._pool_tensor = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def set_stream(self, hip_stream: int):
+        self._check(self._L.she_set_stream(self._h, C.c_void_p(hip_stream)))
+
+    # ---- the paper's problem statement
+    def encrypt_bits(self, bits, enc_seed: int, dst_ids):
+        bits, dst_ids = _u8(bits).ravel(), _u32(dst_ids).ravel()
+        assert bits.size == dst_ids.size
+        self._check(self._L.she_encrypt_bits(self._h, _p(bits, C.c_uint8), bits.size, enc_seed, _p(dst_ids, C.c_uint32)))
+
+    def decrypt(self, ids) -> np.ndarray:
+        ids = _u32(ids)
+        out = np.zeros(ids.size, np.uint8)
+        self._check(self._L.she_decrypt(self._h, _p(ids.ravel(), C.c_uint32), ids.size, _p(out, C.c_uint8)))
+        return out.reshape(ids.shape)
+
+    def eval_gates(self, gtype, in0, in1, out):
+        gtype, in0, in1, out = _u8(gtype).ravel(), _u32(in0).ravel(), _u32(in1).ravel(), _u32(out).ravel()
+        assert gtype.size == in0.size == in1.size == out.size
+        self._check(self._L.she_eval_gates(self._h, _p(gtype, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
+                                           _p(out, C.c_uint32), gtype.size))
+
+    def shift_acc(self, x_ids, w_sign, w_exp, acc_bits: int, out_ids) -> int:
+        x_ids = _u32(x_ids)
+        units, terms, in_bits = x_ids.shape
+        w_sign, w_exp, out_ids = _i8(w_sign), _i8(w_exp), _u32(out_ids)
+        assert w_sign.shape == (units, terms) == w_exp.shape and out_ids.shape == (units, acc_bits)
+        gates = C.c_uint64(0)
+        self._check(self._L.she_shift_acc(self._h, _p(x_ids, C.c_uint32), units, terms, in_bits, _p(w_sign, C.c_int8),
+                                          _p(w_exp, C.c_int8), acc_bits, _p(out_ids, C.c_uint32), C.byref(gates)))
+        return gates.value
+
+    def relu(self, x_ids, out_ids) -> int:
+        x_ids, out_ids = _u32(x_ids), _u32(out_ids)
+        bits = x_ids.shape[-1]
+        count = x_ids.size // bits
+        assert out_ids.shape == x_ids.shape
+        gates = C.c_uint64(0)
+        self._check(self._L.she_relu(self._h, _p(x_ids, C.c_uint32), count, bits, _p(out_ids, C.c_uint32), C.byref(gates)))
+        return gates.value
+
+    def maxpool(self, x_ids, out_ids) -> int:
+        x_ids, out_ids = _u32(x_ids), _u32(out_ids)
+        H, W, Cn, bits = x_ids.shape
+        assert out_ids.shape == (H // 2, W // 2, Cn, bits)
+        gates = C.c_uint64(0)
+        self._check(self._L.she_maxpool(self._h, _p(x_ids, C.c_uint32), H, W, Cn, bits, _p(out_ids, C.c_uint32),
+                                        C.byref(gates)))
+        return gates.value
+
+    # ---- diagnostics
+    def read_ct(self, idx: int) -> np.ndarray:
+        out = np.zeros(self.params.n + 1, np.uint32)
+        self._check(self._L.she_read_ct(self._h, idx, _p(out, C.c_uint32)))
+        return out
+
+    def write_ct(self, idx: int, ct):
+        ct = _u32(ct)
+        assert ct.size == self.params.n + 1
+        self._check(self._L.she_write_ct(self._h, idx, _p(ct, C.c_uint32)))
+
+    def read_cts(self, ids) -> np.ndarray:
+        return np.stack([self.read_ct(int(i)) for i in np.asarray(ids).ravel()])
+
+    def export_keys(self):
+        P = self.params
+        lwe, ring = np.zeros(P.n, np.uint8), np.zeros(P.N, np.uint8)
+        bk = np.zeros((P.n, 2, P.l, 2, P.N), np.uint32)
+        ks = np.zeros((P.N, P.ks_t, (1 << P.ks_basebit) - 1, P.n + 1), np.uint32)
+        self._check(self._L.she_export_keys(self._h, _p(lwe, C.c_uint8), _p(ring, C.c_uint8), _p(bk, C.c_uint32),
+                                            _p(ks, C.c_uint32)))
+        return lwe, ring, bk, ks
+
+    def eval_gates_device(self, d_type, d_in0, d_in1, d_out, ngates: int):
+        """Device pointers (ints); enqueues without validation or synchronisation."""
+        self._check(self._L.she_eval_gates_device(self._h, C.c_void_p(d_type), C.c_void_p(d_in0), C.c_void_p(d_in1),
+                                                  C.c_void_p(d_out), ngates))
+
+    def set_round_tracking(self, on: bool):
+        self._check(self._L.she_set_round_tracking(self._h, int(on)))
+
+    def get_round_error(self, reset: bool = True) -> float:
+        v = C.c_double(0)
+        self._check(self._L.she_get_round_error(self._h, C.byref(v), int(reset)))
+        return v.value
+
+    def last_timing(self) -> dict:
+        ms = (C.c_double * 4)()
+        self._check(self._L.she_last_timing(self._h, ms))
+        return {"lincomb_ms": ms[0], "blind_rotate_ms": ms[1], "key_switch_ms": ms[2], "levels": int(ms[3])}

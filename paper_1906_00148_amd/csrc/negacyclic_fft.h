@@ -1,0 +1,236 @@
+// In-register negacyclic transform for gfx950 wavefronts.
+//
+// A real polynomial a(X) of degree < N in R[X]/(X^N+1) is folded to M = N/2 complex
+// numbers u_j = a_j + i*a_{j+M}, twisted by psi^j (psi = exp(i*pi/N)) and sent through an
+// M-point complex DFT with kernel exp(+2*pi*i*jk/M).  The result is a(X) evaluated at the
+// M roots psi^(4k+1) of X^N+1 (the other M roots are their conjugates), so a product in
+// the ring is a pointwise complex product there.
+//
+// Mapping: M = P^K.  One transform is spread over L = M/P lanes of a wavefront, each lane
+// holding P complex points in registers; 64/L transforms run side by side in one
+// wavefront.  The forward transform is K decimation-in-frequency passes of radix P with
+// K-1 transpositions through a wave-private LDS buffer; its output order is digit-reversed
+// and is never undone: the inverse transform is the exact mirror (decimation in time), so
+// it takes that order as input and returns coefficients to the lane and register they
+// were read from.  The twist and the first pass share one per-lane twiddle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <cmath>
+
+namespace she {
+
+// cos(pi*k/64), k = 0..32
+__host__ __device__ constexpr double cos_pi64_q(int k)
+{
+    constexpr double t[33] = {
+        1.0, 0.9987954562051724, 0.9951847266721969, 0.989176509964781, 0.9807852804032304, 0.970031253194544,
+        0.9569403357322088, 0.9415440651830208, 0.9238795325112867, 0.9039892931234433, 0.881921264348355,
+        0.8577286100002721, 0.8314696123025452, 0.8032075314806449, 0.773010453362737, 0.7409511253549591,
+        0.7071067811865476, 0.6715589548470183, 0.6343932841636455, 0.5956993044924335, 0.5555702330196023,
+        0.5141027441932217, 0.4713967368259978, 0.4275550934302822, 0.38268343236508984, 0.33688985339222005,
+        0.29028467725446233, 0.24298017990326398, 0.19509032201612833, 0.14673047445536175, 0.09801714032956077,
+        0.049067674327418126, 0.0};
+    return t[k];
+}
+// cos / sin of pi*a/64 for any integer a
+__host__ __device__ constexpr double cos_pi64(int a)
+{
+    a = ((a % 128) + 128) % 128;
+    if (a > 64) a = 128 - a;                     // cos is even about pi
+    return a <= 32 ? cos_pi64_q(a) : -cos_pi64_q(64 - a);
+}
+__host__ __device__ constexpr double sin_pi64(int a) { return cos_pi64(a - 32); }
+
+constexpr int ipow(int b, int e) { return e == 0 ? 1 : b * ipow(b, e - 1); }
+constexpr int brev(int v, int bits) { int r = 0; for (int i = 0; i < bits; i++) r |= ((v >> i) & 1) << (bits - 1 - i); return r; }
+
+template <int LOGP_, int K_> struct Plan {
+    static constexpr int LOGP = LOGP_;
+    static constexpr int K = K_;                      // passes
+    static constexpr int P = 1 << LOGP;               // points per lane, radix of every pass
+    static constexpr int M = ipow(P, K);              // complex length
+    static constexpr int N = 2 * M;                   // ring degree
+    static constexpr int L = M / P;                   // lanes per transform
+    static constexpr int GPW = 64 / L;                // transforms (gates) per wavefront
+    static constexpr int XROW = L + 1;                // padded row of the exchange buffer (16-byte slots)
+    static constexpr int XSLOTS = P * XROW;           // exchange slots per transform
+    static constexpr int NTW = (K - 1) * P;           // per-lane twiddles
+    static_assert(L >= 1 && L <= 64 && 64 % L == 0, "one transform must fit a wavefront");
+};
+
+// ---- radix-P DFT on registers ------------------------------------------------------------
+// y_k = sum_m x_m exp(SIGN*2*pi*i*k*m/P), decimation in frequency; y_k is left at position
+// brev(k) and handed back in natural order by a compile-time register renaming.
+template <int P, int SIGN> __device__ __forceinline__ void dft_regs(double (&xr)[P], double (&xi)[P])
+{
+    constexpr int LOGP = __builtin_ctz(P);
+#pragma unroll
+    for (int len = P; len >= 2; len >>= 1) {
+        const int half = len >> 1;
+#pragma unroll
+        for (int base = 0; base < P; base += len) {
+#pragma unroll
+            for (int j = 0; j < half; j++) {
+                const int a = base + j, b = a + half;
+                const double tr = xr[a] - xr[b], ti = xi[a] - xi[b];
+                xr[a] += xr[b];
+                xi[a] += xi[b];
+                if (j == 0) {
+                    xr[b] = tr; xi[b] = ti;
+                } else if (4 * j == len) {                       // multiply by SIGN*i
+                    xr[b] = -SIGN * ti; xi[b] = SIGN * tr;
+                } else if (8 * j == len) {                       // (1 + SIGN*i)/sqrt2
+                    const double h = 0.7071067811865476;
+                    xr[b] = (tr - SIGN * ti) * h; xi[b] = (ti + SIGN * tr) * h;
+                } else if (8 * j == 3 * len) {                   // (-1 + SIGN*i)/sqrt2
+                    const double h = 0.7071067811865476;
+                    xr[b] = (-tr - SIGN * ti) * h; xi[b] = (SIGN * tr - ti) * h;
+                } else {
+                    const double wr = cos_pi64(128 * j / len), wi = SIGN * sin_pi64(128 * j / len);
+                    xr[b] = tr * wr - ti * wi; xi[b] = tr * wi + ti * wr;
+                }
+            }
+        }
+    }
+    double yr[P], yi[P];
+#pragma unroll
+    for (int k = 0; k < P; k++) { yr[k] = xr[brev(k, LOGP)]; yi[k] = xi[brev(k, LOGP)]; }
+#pragma unroll
+    for (int k = 0; k < P; k++) { xr[k] = yr[k]; xi[k] = yi[k]; }
+}
+
+// Orders LDS traffic of one wavefront: a wave's LDS operations complete in issue order,
+// so only the compiler has to be kept from moving them across this point.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Per-lane constants of a transform: twiddles in registers and exchange addresses.
+template <class PL> struct LaneCtx {
+    double twr[PL::NTW > 0 ? PL::NTW : 1], twi[PL::NTW > 0 ? PL::NTW : 1];   // [pass s-1][k]
+    int rd_base[PL::K > 1 ? PL::K - 1 : 1];   // slot read by this lane after pass s (register m adds m*T_{s+1})
+    int t;                                     // lane within the transform
+    double2 *xch;                              // this transform's exchange buffer (XSLOTS slots)
+
+    // tw_table: [K-1][P][L] complex, device memory, filled by make_twiddles() on the host
+    __device__ __forceinline__ void init(int lane_in_transform, double2 *xbuf, const double2 *tw_table)
+    {
+        t = lane_in_transform;
+        xch = xbuf;
+#pragma unroll
+        for (int s = 0; s < PL::K - 1; s++) {
+#pragma unroll
+            for (int k = 0; k < PL::P; k++) {
+                const double2 w = tw_table[(s * PL::P + k) * PL::L + t];
+                twr[s * PL::P + k] = w.x;
+                twi[s * PL::P + k] = w.y;
+            }
+            const int Ts = ipow(PL::P, PL::K - 1 - s);       // sub-transform length after pass s+1 (1-based s+1)
+            const int Tn = Ts / PL::P;
+            const int q = t / Tn, tn = t % Tn, ks = q % PL::P, kap = q / PL::P;
+            rd_base[s] = ks * PL::XROW + tn + Ts * kap;
+        }
+    }
+};
+
+// Host side of LaneCtx::init: twiddle of pass s (1-based), output k, lane t.
+//   s = 1: exp(i*pi*t*(1+4k)/N)   (twist psi^t merged with the first pass)
+//   s > 1: exp(2*pi*i*k*(t mod T_s)/T_{s-1}),  T_s = P^(K-s)
+template <class PL> inline void make_twiddles(double *out /* [K-1][P][L][2] */)
+{
+    for (int s = 1; s < PL::K; s++)
+        for (int k = 0; k < PL::P; k++)
+            for (int t = 0; t < PL::L; t++) {
+                long double ang;
+                if (s == 1) {
+                    ang = 3.14159265358979323846264338327950288L * (long double)t * (1 + 4 * k) / (long double)PL::N;
+                } else {
+                    const int Ts = ipow(PL::P, PL::K - s), Tp = Ts * PL::P;
+                    ang = 2.0L * 3.14159265358979323846264338327950288L * (long double)k * (t % Ts) / (long double)Tp;
+                }
+                double *o = out + 2 * (((size_t)(s - 1) * PL::P + k) * PL::L + t);
+                o[0] = (double)cosl(ang);
+                o[1] = (double)sinl(ang);
+            }
+}
+
+// Forward transform.  In: xr/xi[m] = u_{t + L*m} (folded, not yet twisted).  Out: spectrum in
+// the lane/register order that inverse() and the pointwise products share.
+template <class PL> __device__ __forceinline__ void forward(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+{
+    constexpr int P = PL::P, K = PL::K;
+    // register-dependent part of the twist: psi^(L*m) = exp(i*pi*m/(2P))
+#pragma unroll
+    for (int m = 1; m < P; m++) {
+        const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
+        const double r = xr[m], i = xi[m];
+        xr[m] = r * cr - i * ci;
+        xi[m] = r * ci + i * cr;
+    }
+#pragma unroll
+    for (int s = 0; s < K; s++) {
+        dft_regs<P, +1>(xr, xi);
+        if (s == K - 1) break;
+#pragma unroll
+        for (int k = (s == 0 ? 0 : 1); k < P; k++) {
+            const double wr = lc.twr[s * P + k], wi = lc.twi[s * P + k];
+            const double r = xr[k], i = xi[k];
+            xr[k] = r * wr - i * wi;
+            xi[k] = r * wi + i * wr;
+        }
+        wave_lds_fence();
+#pragma unroll
+        for (int k = 0; k < P; k++) lc.xch[k * PL::XROW + lc.t] = make_double2(xr[k], xi[k]);
+        wave_lds_fence();
+        const int Tn = ipow(P, K - 2 - s);
+#pragma unroll
+        for (int m = 0; m < P; m++) {
+            const double2 v = lc.xch[lc.rd_base[s] + m * Tn];
+            xr[m] = v.x; xi[m] = v.y;
+        }
+    }
+}
+
+// Inverse transform, unnormalised mirror of forward(); the caller's scale folds in 1/M.
+// Out: xr/xi[m] = M * u_{t + L*m}.
+template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+{
+    constexpr int P = PL::P, K = PL::K;
+#pragma unroll
+    for (int s = K - 1; s >= 0; s--) {
+        if (s < K - 1) {
+            // undo the transposition that followed pass s+1
+            const int Tn = ipow(P, K - 2 - s);
+            wave_lds_fence();
+#pragma unroll
+            for (int m = 0; m < P; m++) lc.xch[lc.rd_base[s] + m * Tn] = make_double2(xr[m], xi[m]);
+            wave_lds_fence();
+#pragma unroll
+            for (int k = 0; k < P; k++) {
+                const double2 v = lc.xch[k * PL::XROW + lc.t];
+                xr[k] = v.x; xi[k] = v.y;
+            }
+#pragma unroll
+            for (int k = (s == 0 ? 0 : 1); k < P; k++) {            // conjugate twiddle
+                const double wr = lc.twr[s * P + k], wi = lc.twi[s * P + k];
+                const double r = xr[k], i = xi[k];
+                xr[k] = r * wr + i * wi;
+                xi[k] = i * wr - r * wi;
+            }
+        }
+        dft_regs<P, -1>(xr, xi);
+    }
+#pragma unroll
+    for (int m = 1; m < P; m++) {                                    // conjugate of psi^(L*m)
+        const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
+        const double r = xr[m], i = xi[m];
+        xr[m] = r * cr + i * ci;
+        xi[m] = i * cr - r * ci;
+    }
+}
+
+}  // namespace she

@@ -1,0 +1,580 @@
+// C ABI of the library (declared in include/she.h): context, pool, level scheduler.
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <new>
+
+#include "she_internal.h"
+
+using namespace she;
+
+struct she_ctx {
+    she_params P{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    HostKeys hk;
+    DeviceKeys dk;
+    uint32_t cap = 0, stride = 0;
+    uint32_t *pool = nullptr;
+    bool pool_owned = true;
+    uint32_t *temp = nullptr;            // internal slots: 0 = trivial 0, 1 = trivial 1, then temporaries
+    size_t temp_slots = 0;
+    LevelWork work;
+    // device staging for host-array calls (grown on demand)
+    uint8_t *d_type = nullptr;
+    uint32_t *d_in0 = nullptr, *d_in1 = nullptr, *d_out = nullptr;
+    size_t d_gate_cap = 0;
+    uint32_t *d_stage = nullptr;         // ciphertext staging [slots][n+1] and id lists
+    size_t d_stage_words = 0;
+    unsigned *d_round_err = nullptr;
+    bool track_round = false;
+    double last_ms[4] = {0, 0, 0, 0};
+    std::string err;
+};
+
+namespace {
+
+thread_local std::string g_keygen_error;
+
+int fail(she_ctx *c, int code, const std::string &msg)
+{
+    if (c) c->err = msg; else g_keygen_error = msg;
+    return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? SHE_ENOMEM : SHE_EDEVICE,                \
+                        std::string(#expr) + ": " + hipGetErrorString(e_));                       \
+    } while (0)
+
+CtSpace space(const she_ctx *c) { return CtSpace{c->pool, c->temp, c->cap, c->stride}; }
+
+int ensure_temp(she_ctx *c, size_t slots)
+{
+    if (slots <= c->temp_slots) return SHE_OK;
+    if (c->temp) { HIP_TRY(c, hipStreamSynchronize(c->stream)); HIP_TRY(c, hipFree(c->temp)); c->temp = nullptr; c->temp_slots = 0; }
+    slots = std::max<size_t>(slots + slots / 8, 1024);
+    HIP_TRY(c, hipMalloc((void **)&c->temp, slots * c->stride * sizeof(uint32_t)));
+    c->temp_slots = slots;
+    // trivial ciphertexts of 0 and 1: zero mask, body -1/8 and +1/8
+    std::vector<uint32_t> consts(2 * (size_t)c->stride, 0u);
+    consts[c->P.n] = 0u - (1u << 29);
+    consts[c->stride + c->P.n] = 1u << 29;
+    HIP_TRY(c, hipMemcpyAsync(c->temp, consts.data(), consts.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return SHE_OK;
+}
+
+int ensure_work(she_ctx *c, size_t gates)
+{
+    if (gates <= c->work.gates) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->work.bar) { hipFree(c->work.bar); hipFree(c->work.ext_b); hipFree(c->work.ksd); c->work = LevelWork{}; }
+    const size_t groups = (gates + KS_GROUP - 1) / KS_GROUP;
+    c->work.bar_stride = round_up(c->P.n + 1, 2);
+    HIP_TRY(c, hipMalloc((void **)&c->work.bar, gates * c->work.bar_stride * sizeof(uint16_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->work.ext_b, gates * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->work.ksd, groups * c->P.N * KS_GROUP * sizeof(uint16_t)));
+    HIP_TRY(c, hipMemset(c->work.ksd, 0, groups * c->P.N * KS_GROUP * sizeof(uint16_t)));
+    c->work.gates = gates;
+    return SHE_OK;
+}
+
+int ensure_gate_arrays(she_ctx *c, size_t gates)
+{
+    if (gates <= c->d_gate_cap) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->d_type) { hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out); }
+    c->d_type = nullptr; c->d_gate_cap = 0;
+    gates += gates / 4;
+    HIP_TRY(c, hipMalloc((void **)&c->d_type, gates));
+    HIP_TRY(c, hipMalloc((void **)&c->d_in0, gates * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->d_in1, gates * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->d_out, gates * sizeof(uint32_t)));
+    c->d_gate_cap = gates;
+    return SHE_OK;
+}
+
+int ensure_stage(she_ctx *c, size_t words)
+{
+    if (words <= c->d_stage_words) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->d_stage) hipFree(c->d_stage);
+    c->d_stage = nullptr; c->d_stage_words = 0;
+    HIP_TRY(c, hipMalloc((void **)&c->d_stage, words * sizeof(uint32_t)));
+    c->d_stage_words = words;
+    return SHE_OK;
+}
+
+struct LevelTimer {           // events around the three kernel families of every chunk
+    std::vector<hipEvent_t> ev;
+    ~LevelTimer() { for (auto e : ev) hipEventDestroy(e); }
+    hipError_t mark(hipStream_t st)
+    {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return rc;
+        ev.push_back(e);
+        return hipEventRecord(e, st);
+    }
+};
+
+// Enqueues one level (device arrays), cut into chunks of at most MAX_LEVEL_CHUNK gates.
+int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                  const uint32_t *d_out, size_t gates, LevelTimer *timer)
+{
+    const CtSpace cs = space(c);
+    for (size_t off = 0; off < gates; off += MAX_LEVEL_CHUNK) {
+        const size_t cnt = std::min<size_t>(MAX_LEVEL_CHUNK, gates - off);
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, cnt, c->work, c->stream));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+    }
+    return SHE_OK;
+}
+
+int finish_timing(she_ctx *c, LevelTimer &timer, size_t levels)
+{
+    double ms[3] = {0, 0, 0};
+    for (size_t q = 0; q + 3 < timer.ev.size(); q += 4)
+        for (int f = 0; f < 3; f++) {
+            float t = 0;
+            HIP_TRY(c, hipEventElapsedTime(&t, timer.ev[q + f], timer.ev[q + f + 1]));
+            ms[f] += t;
+        }
+    c->last_ms[0] = ms[0]; c->last_ms[1] = ms[1]; c->last_ms[2] = ms[2]; c->last_ms[3] = (double)levels;
+    return SHE_OK;
+}
+
+bool params_supported(const she_params &P, std::string &why)
+{
+    if (P.k != 1) { why = "k must be 1"; return false; }
+    if (!plan_supported(P.N)) { why = "N must be 256, 512 or 1024"; return false; }
+    if (P.n < 1 || P.n > 4096) { why = "n must be in [1, 4096]"; return false; }
+    if (P.l < 1 || P.l > 8 || P.bg_bit < 1 || P.l * P.bg_bit > 31) { why = "need 1 <= l <= 8 and l*bg_bit <= 31"; return false; }
+    if (P.ks_t < 1 || P.ks_basebit < 1 || P.ks_basebit > 4 || P.ks_t * P.ks_basebit > 16) {
+        why = "need ks_basebit <= 4 and ks_t*ks_basebit <= 16"; return false;
+    }
+    if (!(P.lwe_std >= 0) || !(P.bk_std >= 0)) { why = "noise deviations must be >= 0"; return false; }
+    return true;
+}
+
+// Runs a finished netlist: levelize, bind outputs, upload, one enqueue per level, copies, sync.
+int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires, const uint32_t *out_ids,
+                uint64_t *gates_out)
+{
+    const std::vector<size_t> bounds = nl.levelize();
+    nl.bind_outputs(out_wires, out_ids);
+    const size_t G = nl.type.size();
+    if (gates_out) *gates_out = G;
+    int rc = ensure_temp(c, (size_t)nl.next_temp - nl.cap);
+    if (rc) return rc;
+    size_t widest = 0;
+    for (size_t lv = 0; lv + 1 < bounds.size(); lv++) widest = std::max(widest, bounds[lv + 1] - bounds[lv]);
+    if ((rc = ensure_work(c, std::min<size_t>(widest, MAX_LEVEL_CHUNK)))) return rc;
+    if ((rc = ensure_gate_arrays(c, std::max(G, nl.copy_src.size())))) return rc;
+    LevelTimer timer;
+    if (G) {
+        HIP_TRY(c, hipMemcpyAsync(c->d_type, nl.type.data(), G, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_in0, nl.in0.data(), G * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_in1, nl.in1.data(), G * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_out, nl.out.data(), G * 4, hipMemcpyHostToDevice, c->stream));
+        for (size_t lv = 0; lv + 1 < bounds.size(); lv++) {
+            const size_t a = bounds[lv], b = bounds[lv + 1];
+            if ((rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, b - a, &timer))) return rc;
+        }
+    }
+    if (!nl.copy_src.empty()) {
+        // the gate arrays are free again once the levels are enqueued in stream order
+        const size_t n_copy = nl.copy_src.size();
+        HIP_TRY(c, hipMemcpyAsync(c->d_in0, nl.copy_src.data(), n_copy * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_in1, nl.copy_dst.data(), n_copy * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, launch_copy_ct(space(c), c->d_in0, c->d_in1, n_copy, c->P.n, c->stream));
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return finish_timing(c, timer, bounds.empty() ? 0 : bounds.size() - 1);
+}
+
+// ids must be inside the pool; marks them in `seen` (if given) and reports duplicates
+int check_ids(she_ctx *c, const uint32_t *ids, size_t count, const char *what)
+{
+    for (size_t k = 0; k < count; k++)
+        if (ids[k] >= c->cap) return fail(c, SHE_ERANGE, std::string(what) + ": id outside the pool");
+    return SHE_OK;
+}
+
+int check_disjoint(she_ctx *c, const uint32_t *ins, size_t n_in, const uint32_t *ins2, size_t n_in2,
+                   const uint32_t *outs, size_t n_out)
+{
+    std::vector<uint8_t> mark(c->cap, 0);
+    for (size_t k = 0; k < n_in; k++) mark[ins[k]] = 1;
+    for (size_t k = 0; k < n_in2; k++) mark[ins2[k]] = 1;
+    for (size_t k = 0; k < n_out; k++) {
+        if (mark[outs[k]] == 1) return fail(c, SHE_EINVAL, "an output id is also an input id");
+        if (mark[outs[k]] == 2) return fail(c, SHE_EINVAL, "an output id appears twice");
+        mark[outs[k]] = 2;
+    }
+    return SHE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, she_ctx **out)
+{
+    if (!params || !out) return fail(nullptr, SHE_EINVAL, "null argument");
+    *out = nullptr;
+    std::string why;
+    if (!params_supported(*params, why)) return fail(nullptr, SHE_EINVAL, "unsupported parameters: " + why);
+    if (pool_capacity == 0 || pool_capacity > 0x7FFFFFF0u) return fail(nullptr, SHE_EINVAL, "bad pool capacity");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, SHE_EDEVICE, "no HIP device");
+
+    std::unique_ptr<she_ctx> c(new (std::nothrow) she_ctx);
+    if (!c) return fail(nullptr, SHE_ENOMEM, "host allocation");
+    c->P = *params;
+    c->cap = pool_capacity;
+    c->stride = round_up(params->n + 1, 32);
+    auto bail = [&](int code) { g_keygen_error = c->err; she_free(c.release()); return code; };
+    if (hipGetDevice(&c->device) != hipSuccess) return bail(fail(c.get(), SHE_EDEVICE, "hipGetDevice"));
+
+    try {
+        generate_keys(c->P, seed, c->hk);
+    } catch (const std::bad_alloc &) {
+        return bail(fail(c.get(), SHE_ENOMEM, "host allocation for keys"));
+    }
+
+    auto body = [&]() -> int {
+        she_ctx *cc = c.get();
+        const she_params &P = cc->P;
+        // twiddles
+        std::vector<double> tw(twiddle_doubles(P.N));
+        fill_twiddles(P.N, tw.data());
+        HIP_TRY(cc, hipMalloc((void **)&cc->dk.twiddles, std::max<size_t>(tw.size(), 2) * sizeof(double)));
+        HIP_TRY(cc, hipMemcpy(cc->dk.twiddles, tw.data(), tw.size() * sizeof(double), hipMemcpyHostToDevice));
+        // bootstrapping key: upload integers, transform on the device, drop the integers
+        uint32_t *d_bk_int = nullptr;
+        HIP_TRY(cc, hipMalloc((void **)&d_bk_int, cc->hk.bk.size() * sizeof(uint32_t)));
+        hipError_t e = hipMemcpy(d_bk_int, cc->hk.bk.data(), cc->hk.bk.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMalloc((void **)&cc->dk.bk_hat, bk_hat_elems(P) * sizeof(double2));
+        if (e == hipSuccess) e = launch_bk_transform(P, d_bk_int, cc->dk, nullptr);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        hipFree(d_bk_int);
+        HIP_TRY(cc, e);
+        // key-switching key, rows padded to the slot stride
+        const uint32_t rows = P.N * P.ks_t * ((1u << P.ks_basebit) - 1);
+        cc->dk.ks_stride = cc->stride;
+        HIP_TRY(cc, hipMalloc((void **)&cc->dk.ks, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
+        HIP_TRY(cc, hipMemset(cc->dk.ks, 0, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
+        HIP_TRY(cc, hipMemcpy2D(cc->dk.ks, cc->dk.ks_stride * sizeof(uint32_t), cc->hk.ks.data(), (P.n + 1) * sizeof(uint32_t),
+                                (P.n + 1) * sizeof(uint32_t), rows, hipMemcpyHostToDevice));
+        // pool and internal slots
+        HIP_TRY(cc, hipMalloc((void **)&cc->pool, (size_t)cc->cap * cc->stride * sizeof(uint32_t)));
+        HIP_TRY(cc, hipMemset(cc->pool, 0, (size_t)cc->cap * cc->stride * sizeof(uint32_t)));
+        HIP_TRY(cc, hipMalloc((void **)&cc->d_round_err, sizeof(unsigned)));
+        HIP_TRY(cc, hipMemset(cc->d_round_err, 0, sizeof(unsigned)));
+        int rc = ensure_temp(cc, 2);
+        if (rc) return rc;
+        return SHE_OK;
+    };
+    int rc = body();
+    if (rc) return bail(rc);
+    *out = c.release();
+    return SHE_OK;
+}
+
+void she_free(she_ctx *c)
+{
+    if (!c) return;
+    if (c->stream) hipStreamSynchronize(c->stream); else hipDeviceSynchronize();
+    hipFree(c->dk.bk_hat); hipFree(c->dk.ks); hipFree(c->dk.twiddles);
+    if (c->pool_owned) hipFree(c->pool);
+    hipFree(c->temp);
+    hipFree(c->work.bar); hipFree(c->work.ext_b); hipFree(c->work.ksd);
+    hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out);
+    hipFree(c->d_stage); hipFree(c->d_round_err);
+    delete c;
+}
+
+int she_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t nbits, uint64_t enc_seed, const uint32_t *dst_ids)
+{
+    if (!c) return SHE_EINVAL;
+    if (nbits == 0) return SHE_OK;
+    if (!bits || !dst_ids) return fail(c, SHE_EINVAL, "null argument");
+    for (size_t k = 0; k < nbits; k++)
+        if (bits[k] > 1) return fail(c, SHE_EINVAL, "bits must be 0 or 1");
+    int rc = check_ids(c, dst_ids, nbits, "she_encrypt_bits");
+    if (rc) return rc;
+    const size_t w = c->P.n + 1;
+    std::vector<uint32_t> host;
+    try { host.resize(nbits * w); } catch (const std::bad_alloc &) { return fail(c, SHE_ENOMEM, "host staging"); }
+    fresh_samples(c->P, c->hk.lwe_key, bits, nbits, enc_seed, host.data());
+    if ((rc = ensure_stage(c, nbits * w + nbits))) return rc;
+    uint32_t *d_ids = c->d_stage + nbits * w;
+    HIP_TRY(c, hipMemcpyAsync(c->d_stage, host.data(), nbits * w * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(d_ids, dst_ids, nbits * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, launch_scatter(space(c), c->d_stage, d_ids, nbits, c->P.n, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return SHE_OK;
+}
+
+static int fetch(she_ctx *c, const uint32_t *ids, size_t count, std::vector<uint32_t> &host)
+{
+    const size_t w = c->P.n + 1;
+    try { host.resize(count * w); } catch (const std::bad_alloc &) { return fail(c, SHE_ENOMEM, "host staging"); }
+    int rc = ensure_stage(c, count * w + count);
+    if (rc) return rc;
+    uint32_t *d_ids = c->d_stage + count * w;
+    HIP_TRY(c, hipMemcpyAsync(d_ids, ids, count * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, launch_gather(space(c), c->d_stage, d_ids, count, c->P.n, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(host.data(), c->d_stage, count * w * 4, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return SHE_OK;
+}
+
+int she_decrypt(she_ctx *c, const uint32_t *ids, size_t count, uint8_t *bits_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (count == 0) return SHE_OK;
+    if (!ids || !bits_out) return fail(c, SHE_EINVAL, "null argument");
+    int rc = check_ids(c, ids, count, "she_decrypt");
+    if (rc) return rc;
+    std::vector<uint32_t> host;
+    if ((rc = fetch(c, ids, count, host))) return rc;
+    phases_to_bits(c->P, c->hk.lwe_key, host.data(), count, bits_out);
+    return SHE_OK;
+}
+
+int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *out,
+                   size_t ngates)
+{
+    if (!c) return SHE_EINVAL;
+    if (ngates == 0) return SHE_OK;
+    if (!type || !in0 || !in1 || !out) return fail(c, SHE_EINVAL, "null argument");
+    for (size_t g = 0; g < ngates; g++)
+        if (type[g] >= SHE_NUM_GATES) return fail(c, SHE_EINVAL, "unknown gate code");
+    int rc;
+    if ((rc = check_ids(c, in0, ngates, "she_eval_gates in0"))) return rc;
+    if ((rc = check_ids(c, in1, ngates, "she_eval_gates in1"))) return rc;
+    if ((rc = check_ids(c, out, ngates, "she_eval_gates out"))) return rc;
+    if ((rc = check_disjoint(c, in0, ngates, in1, ngates, out, ngates))) return rc;
+    if ((rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK)))) return rc;
+    if ((rc = ensure_gate_arrays(c, ngates))) return rc;
+    HIP_TRY(c, hipMemcpyAsync(c->d_type, type, ngates, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_in0, in0, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_in1, in1, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_out, out, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    LevelTimer timer;
+    if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates, &timer))) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return finish_timing(c, timer, 1);
+}
+
+int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                          const uint32_t *d_out, size_t ngates)
+{
+    if (!c) return SHE_EINVAL;
+    if (ngates == 0) return SHE_OK;
+    if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
+    int rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK));
+    if (rc) return rc;
+    return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates, nullptr);
+}
+
+int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
+                  const int8_t *w_sign, const int8_t *w_exp, uint32_t acc_bits, const uint32_t *out_ids,
+                  uint64_t *gates_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (gates_out) *gates_out = 0;
+    if (units == 0) return SHE_OK;
+    if (!out_ids || (terms && (!x_ids || !w_sign || !w_exp))) return fail(c, SHE_EINVAL, "null argument");
+    if (in_bits < 1 || in_bits > acc_bits || acc_bits > 32) return fail(c, SHE_EINVAL, "need 1 <= in_bits <= acc_bits <= 32");
+    const size_t n_in = (size_t)units * terms * in_bits, n_out = (size_t)units * acc_bits;
+    int rc;
+    if ((rc = check_ids(c, x_ids, n_in, "she_shift_acc x_ids"))) return rc;
+    if ((rc = check_ids(c, out_ids, n_out, "she_shift_acc out_ids"))) return rc;
+    if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
+    for (size_t k = 0; k < (size_t)units * terms; k++) {
+        if (w_sign[k] != 1 && w_sign[k] != -1) return fail(c, SHE_EINVAL, "w_sign must be +1 or -1");
+        if (w_exp[k] > 0 || -(int)w_exp[k] >= (int)in_bits) return fail(c, SHE_EINVAL, "w_exp must be in [-(in_bits-1), 0]");
+    }
+    try {
+        Netlist nl(c->cap);
+        std::vector<uint32_t> wires;
+        wires.reserve(n_out);
+        for (uint32_t u = 0; u < units; u++) {
+            std::vector<std::vector<uint32_t>> pos, neg;
+            for (uint32_t t = 0; t < terms; t++) {
+                const size_t k = (size_t)u * terms + t;
+                const uint32_t drop = (uint32_t)(-(int)w_exp[k]);
+                // x >> drop: the low `drop` wires fall away, trivial zeros refill the top
+                std::vector<uint32_t> term(x_ids + k * in_bits + drop, x_ids + (k + 1) * in_bits);
+                term.resize(in_bits, nl.zero());
+                (w_sign[k] > 0 ? pos : neg).push_back(std::move(term));
+            }
+            const bool has_neg = !neg.empty();
+            std::vector<uint32_t> total = nl_tree(nl, std::move(pos), in_bits, acc_bits);
+            if (has_neg) total = nl_sub(nl, total, nl_tree(nl, std::move(neg), in_bits, acc_bits));
+            wires.insert(wires.end(), total.begin(), total.end());
+        }
+        return run_netlist(c, nl, wires, out_ids, gates_out);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
+int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, const uint32_t *out_ids,
+             uint64_t *gates_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (gates_out) *gates_out = 0;
+    if (count == 0) return SHE_OK;
+    if (!x_ids || !out_ids) return fail(c, SHE_EINVAL, "null argument");
+    if (bits < 2 || bits > 64) return fail(c, SHE_EINVAL, "need 2 <= bits <= 64");
+    const size_t total = (size_t)count * bits;
+    int rc;
+    if ((rc = check_ids(c, x_ids, total, "she_relu x_ids"))) return rc;
+    if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
+    if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
+    try {
+        Netlist nl(c->cap);
+        std::vector<uint32_t> wires;
+        wires.reserve(total);
+        for (uint32_t v = 0; v < count; v++) {
+            const uint32_t *x = x_ids + (size_t)v * bits;
+            for (uint32_t i = 0; i + 1 < bits; i++) wires.push_back(nl.gate(SHE_ANDNY, x[bits - 1], x[i]));
+            wires.push_back(nl.zero());
+        }
+        return run_netlist(c, nl, wires, out_ids, gates_out);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
+int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
+                const uint32_t *out_ids, uint64_t *gates_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (gates_out) *gates_out = 0;
+    const uint32_t Ho = H / 2, Wo = W / 2;
+    if (Ho == 0 || Wo == 0 || C == 0) return SHE_OK;
+    if (!x_ids || !out_ids) return fail(c, SHE_EINVAL, "null argument");
+    if (bits < 2 || bits > 64) return fail(c, SHE_EINVAL, "need 2 <= bits <= 64");
+    const size_t n_in = (size_t)H * W * C * bits, n_out = (size_t)Ho * Wo * C * bits;
+    int rc;
+    if ((rc = check_ids(c, x_ids, n_in, "she_maxpool x_ids"))) return rc;
+    if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
+    if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
+    try {
+        Netlist nl(c->cap);
+        std::vector<uint32_t> wires;
+        wires.reserve(n_out);
+        auto pixel = [&](uint32_t h, uint32_t w, uint32_t ch) {
+            const uint32_t *p = x_ids + (((size_t)h * W + w) * C + ch) * bits;
+            return std::vector<uint32_t>(p, p + bits);
+        };
+        for (uint32_t h = 0; h < Ho; h++)
+            for (uint32_t w = 0; w < Wo; w++)
+                for (uint32_t ch = 0; ch < C; ch++) {
+                    const auto top = nl_max(nl, pixel(2 * h, 2 * w, ch), pixel(2 * h, 2 * w + 1, ch));
+                    const auto bot = nl_max(nl, pixel(2 * h + 1, 2 * w, ch), pixel(2 * h + 1, 2 * w + 1, ch));
+                    const auto best = nl_max(nl, top, bot);
+                    wires.insert(wires.end(), best.begin(), best.end());
+                }
+        return run_netlist(c, nl, wires, out_ids, gates_out);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
+int she_read_ct(she_ctx *c, uint32_t id, uint32_t *dst)
+{
+    if (!c) return SHE_EINVAL;
+    if (!dst) return fail(c, SHE_EINVAL, "null argument");
+    if (id >= c->cap) return fail(c, SHE_ERANGE, "she_read_ct: id outside the pool");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(dst, c->pool + (size_t)id * c->stride, (c->P.n + 1) * 4, hipMemcpyDeviceToHost));
+    return SHE_OK;
+}
+
+int she_write_ct(she_ctx *c, uint32_t id, const uint32_t *src)
+{
+    if (!c) return SHE_EINVAL;
+    if (!src) return fail(c, SHE_EINVAL, "null argument");
+    if (id >= c->cap) return fail(c, SHE_ERANGE, "she_write_ct: id outside the pool");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(c->pool + (size_t)id * c->stride, src, (c->P.n + 1) * 4, hipMemcpyHostToDevice));
+    return SHE_OK;
+}
+
+int she_export_keys(she_ctx *c, uint8_t *lwe_key, uint8_t *ring_key, uint32_t *bk, uint32_t *ks)
+{
+    if (!c) return SHE_EINVAL;
+    if (lwe_key) std::memcpy(lwe_key, c->hk.lwe_key.data(), c->hk.lwe_key.size());
+    if (ring_key) std::memcpy(ring_key, c->hk.ring_key.data(), c->hk.ring_key.size());
+    if (bk) std::memcpy(bk, c->hk.bk.data(), c->hk.bk.size() * 4);
+    if (ks) std::memcpy(ks, c->hk.ks.data(), c->hk.ks.size() * 4);
+    return SHE_OK;
+}
+
+int she_set_stream(she_ctx *c, void *hip_stream)
+{
+    if (!c) return SHE_EINVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->stream = (hipStream_t)hip_stream;
+    return SHE_OK;
+}
+
+size_t she_pool_bytes(const she_ctx *c) { return c ? (size_t)c->cap * c->stride * sizeof(uint32_t) : 0; }
+
+int she_bind_pool(she_ctx *c, void *dev_ptr, size_t bytes)
+{
+    if (!c) return SHE_EINVAL;
+    if (!dev_ptr || bytes < she_pool_bytes(c) || ((uintptr_t)dev_ptr & 255)) return fail(c, SHE_EINVAL, "bad pool memory");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->pool_owned) hipFree(c->pool);
+    c->pool = (uint32_t *)dev_ptr;
+    c->pool_owned = false;
+    return SHE_OK;
+}
+
+int she_set_round_tracking(she_ctx *c, int on)
+{
+    if (!c) return SHE_EINVAL;
+    c->track_round = on != 0;
+    return SHE_OK;
+}
+
+int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
+{
+    if (!c) return SHE_EINVAL;
+    if (!max_abs_frac) return fail(c, SHE_EINVAL, "null argument");
+    unsigned raw = 0;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(&raw, c->d_round_err, sizeof(raw), hipMemcpyDeviceToHost));
+    float f;
+    std::memcpy(&f, &raw, sizeof(f));
+    *max_abs_frac = f;
+    if (reset) HIP_TRY(c, hipMemset(c->d_round_err, 0, sizeof(unsigned)));
+    return SHE_OK;
+}
+
+int she_last_timing(const she_ctx *c, double ms[4])
+{
+    if (!c || !ms) return SHE_EINVAL;
+    for (int i = 0; i < 4; i++) ms[i] = c->last_ms[i];
+    return SHE_OK;
+}
+
+const char *she_last_error(const she_ctx *c) { return c ? c->err.c_str() : g_keygen_error.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,156 @@
+// Netlists of SHE's layer operators and the level scheduler (host code).
+// (SHE, arXiv 1906.00148: Section 3.1 builds ReLU and max-pooling units from 2-input gates,
+// Section 3.2 turns multiplications by power-of-two weights into shifts that only re-wire
+// encrypted bits, Section 3.3 sums the shifted terms with a mixed-bitwidth adder tree.)
+#include <algorithm>
+
+#include "she_internal.h"
+
+namespace she {
+
+uint32_t Netlist::gate(int code, uint32_t a, uint32_t b)
+{
+    const uint32_t w = next_temp++;
+    type.push_back((uint8_t)code);
+    in0.push_back(a);
+    in1.push_back(b);
+    out.push_back(w);
+    return w;
+}
+
+// s ? u : v with three 2-input gates
+uint32_t Netlist::mux(uint32_t s, uint32_t u, uint32_t v)
+{
+    const uint32_t taken = gate(SHE_AND, s, u);
+    const uint32_t other = gate(SHE_ANDNY, s, v);
+    return gate(SHE_OR, taken, other);
+}
+
+void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst)
+{
+    const uint32_t first_temp = cap + 2, unbound = 0xFFFFFFFFu;
+    std::vector<uint32_t> rename(next_temp - first_temp, unbound);     // temporary wire -> caller id
+    for (size_t k = 0; k < wires.size(); k++) {
+        const uint32_t w = wires[k];
+        if (w >= first_temp && rename[w - first_temp] == unbound) {
+            rename[w - first_temp] = dst[k];
+        } else {                                          // input, constant, or a wire already bound
+            copy_src.push_back(w);
+            copy_dst.push_back(dst[k]);
+        }
+    }
+    auto fix = [&](uint32_t &w) {
+        if (w >= first_temp && rename[w - first_temp] != unbound) w = rename[w - first_temp];
+    };
+    for (size_t g = 0; g < type.size(); g++) { fix(in0[g]); fix(in1[g]); fix(out[g]); }
+    for (auto &w : copy_src) fix(w);
+}
+
+// Must run before bind_outputs (every gate output is still a temporary wire).
+std::vector<size_t> Netlist::levelize()
+{
+    // depth of a wire = 0 for inputs and constants, else 1 + deepest operand; gates were
+    // appended in topological order, so one pass suffices
+    const uint32_t first_temp = cap + 2;
+    std::vector<uint32_t> depth(next_temp - first_temp, 0);
+    std::vector<uint32_t> lev(type.size());
+    uint32_t deepest = 0;
+    for (size_t g = 0; g < type.size(); g++) {
+        uint32_t d = 0;
+        if (in0[g] >= first_temp) d = depth[in0[g] - first_temp];
+        if (in1[g] >= first_temp) d = std::max(d, depth[in1[g] - first_temp]);
+        lev[g] = d + 1;
+        depth[out[g] - first_temp] = d + 1;
+        deepest = std::max(deepest, d + 1);
+    }
+    std::vector<size_t> start(deepest + 2, 0);
+    for (uint32_t v : lev) start[v + 1]++;
+    for (size_t i = 1; i < start.size(); i++) start[i] += start[i - 1];
+    std::vector<size_t> cursor(start.begin(), start.end() - 1);
+    std::vector<uint8_t> t2(type.size());
+    std::vector<uint32_t> a2(type.size()), b2(type.size()), o2(type.size());
+    for (size_t g = 0; g < type.size(); g++) {
+        const size_t pos = cursor[lev[g]]++;
+        t2[pos] = type[g]; a2[pos] = in0[g]; b2[pos] = in1[g]; o2[pos] = out[g];
+    }
+    type.swap(t2); in0.swap(a2); in1.swap(b2); out.swap(o2);
+    // start[1..deepest+1] are the level boundaries (level 0 holds no gates)
+    return std::vector<size_t>(start.begin() + 1, start.end());
+}
+
+// a + b for equally wide unsigned vectors; one more bit than the operands unless that
+// would exceed cap_bits (then the last carry is not formed and the sum wraps).
+std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const std::vector<uint32_t> &b, uint32_t cap_bits)
+{
+    const size_t w = a.size();
+    std::vector<uint32_t> sum;
+    sum.push_back(nl.gate(SHE_XOR, a[0], b[0]));
+    if (w == 1 && cap_bits == 1) return sum;
+    uint32_t carry = nl.gate(SHE_AND, a[0], b[0]);
+    for (size_t i = 1; i < w; i++) {
+        const uint32_t half = nl.gate(SHE_XOR, a[i], b[i]);
+        sum.push_back(nl.gate(SHE_XOR, half, carry));
+        if (i + 1 == w && w >= cap_bits) return sum;
+        const uint32_t gen = nl.gate(SHE_AND, a[i], b[i]);
+        const uint32_t prop = nl.gate(SHE_AND, half, carry);
+        carry = nl.gate(SHE_OR, gen, prop);
+    }
+    sum.push_back(carry);
+    return sum;
+}
+
+// p - q modulo 2^w = p + not(q) + 1; the complement sits in the gate types, the chain starts at trivial 1
+std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const std::vector<uint32_t> &q)
+{
+    const size_t w = p.size();
+    std::vector<uint32_t> diff;
+    uint32_t carry = nl.one();
+    for (size_t i = 0; i < w; i++) {
+        const uint32_t half = nl.gate(SHE_XNOR, p[i], q[i]);
+        diff.push_back(nl.gate(SHE_XOR, half, carry));
+        if (i + 1 == w) break;
+        const uint32_t gen = nl.gate(SHE_ANDYN, p[i], q[i]);
+        const uint32_t prop = nl.gate(SHE_AND, half, carry);
+        carry = nl.gate(SHE_OR, gen, prop);
+    }
+    return diff;
+}
+
+// Mixed-bitwidth accumulator: tree level j adds neighbours with min(in_bits+j, acc_bits)-bit adders,
+// an unpaired last vector moves up zero-extended; the result is zero-extended to acc_bits.
+std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> terms, uint32_t in_bits, uint32_t acc_bits)
+{
+    uint32_t width = in_bits;
+    while (terms.size() > 1) {
+        const uint32_t next_width = std::min(width + 1, acc_bits);
+        std::vector<std::vector<uint32_t>> next;
+        for (size_t m = 0; m + 1 < terms.size(); m += 2) next.push_back(nl_add(nl, terms[m], terms[m + 1], acc_bits));
+        if (terms.size() & 1) {
+            std::vector<uint32_t> last = terms.back();
+            last.resize(next_width, nl.zero());
+            next.push_back(std::move(last));
+        }
+        terms.swap(next);
+        width = next_width;
+    }
+    std::vector<uint32_t> total = terms.empty() ? std::vector<uint32_t>() : terms[0];
+    total.resize(acc_bits, nl.zero());
+    return total;
+}
+
+// max of two two's-complement vectors: equality bits, a ripple "x > y so far" from the least
+// significant bit up, the sign position decided the other way round, then one MUX per bit
+std::vector<uint32_t> nl_max(Netlist &nl, const std::vector<uint32_t> &x, const std::vector<uint32_t> &y)
+{
+    const size_t w = x.size();
+    std::vector<uint32_t> eq(w);
+    for (size_t i = 0; i < w; i++) eq[i] = nl.gate(SHE_XNOR, x[i], y[i]);
+    uint32_t gt = nl.zero();
+    for (size_t i = 0; i + 1 < w; i++) gt = nl.mux(eq[i], gt, x[i]);
+    gt = nl.mux(eq[w - 1], gt, y[w - 1]);
+    std::vector<uint32_t> z(w);
+    for (size_t i = 0; i < w; i++) z[i] = nl.mux(gt, x[i], y[i]);
+    return z;
+}
+
+}  // namespace she

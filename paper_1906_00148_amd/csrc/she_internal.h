@@ -1,0 +1,98 @@
+// Internal declarations shared by the host files and the kernel file of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/she.h"
+
+namespace she {
+
+constexpr int KS_GROUP = 32;        // gates whose key-switch digits are stored together / share one key-switch block
+constexpr int MAX_LEVEL_CHUNK = 32768;  // gates per kernel launch; larger levels are cut into chunks
+
+inline uint32_t round_up(uint32_t v, uint32_t m) { return (v + m - 1) / m * m; }
+
+// Everything a kernel needs to find ciphertexts: ids below `cap` are pool slots, ids from
+// `cap` on are slots of the internal temporary buffer (slot 0 = trivial 0, slot 1 = trivial 1).
+struct CtSpace {
+    uint32_t *pool;
+    uint32_t *temp;
+    uint32_t cap;
+    uint32_t stride;   // words per slot (n+1 rounded up to 32)
+};
+
+struct DeviceKeys {
+    double2 *bk_hat = nullptr;    // [n][2l][2][P][L] spectra of the bootstrapping key
+    uint32_t *ks = nullptr;       // [N][t][base-1][ks_stride]
+    double2 *twiddles = nullptr;  // [K-1][P][L]
+    uint32_t ks_stride = 0;
+};
+
+struct LevelWork {                // scratch of one level launch, sized for `gates` gates
+    uint16_t *bar = nullptr;      // [gates][bar_stride]: abar_0..abar_{n-1}, bbar
+    uint32_t *ext_b = nullptr;    // [gates] body of the extracted sample
+    uint16_t *ksd = nullptr;      // [gates/KS_GROUP][N][KS_GROUP] rounded top bits of the extracted mask
+    uint32_t bar_stride = 0;
+    size_t gates = 0;
+};
+
+// ---- kernel launchers (she_kernels.hip); each returns a hipError_t and never synchronises ----
+bool plan_supported(uint32_t N);
+size_t twiddle_doubles(uint32_t N);
+void fill_twiddles(uint32_t N, double *host_out);
+size_t bk_hat_elems(const she_params &P);   // number of double2 in DeviceKeys::bk_hat
+
+hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st);
+hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
+                          const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
+hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
+                               unsigned *d_round_err /* nullptr = no tracking */, hipStream_t st);
+hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                             size_t gates, const LevelWork &W, hipStream_t st);
+hipError_t launch_scatter(const CtSpace &cs, const uint32_t *d_src /* [count][n+1] */, const uint32_t *d_ids,
+                          size_t count, uint32_t n, hipStream_t st);
+hipError_t launch_gather(const CtSpace &cs, uint32_t *d_dst /* [count][n+1] */, const uint32_t *d_ids, size_t count,
+                         uint32_t n, hipStream_t st);
+hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const uint32_t *d_dst_ids, size_t count,
+                          uint32_t n, hipStream_t st);
+
+// ---- host-side key material and samples (she_host.cpp) ----
+struct HostKeys {
+    std::vector<uint8_t> lwe_key, ring_key;
+    std::vector<uint32_t> bk;    // [n][2][l][2][N]
+    std::vector<uint32_t> ks;    // [N][t][base-1][n+1]
+};
+void generate_keys(const she_params &P, uint64_t seed, HostKeys &out);
+void fresh_samples(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint8_t *bits, size_t nbits,
+                   uint64_t enc_seed, uint32_t *out /* [nbits][n+1] */);
+void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint32_t *cts, size_t count,
+                    uint8_t *bits);
+
+// ---- netlists of the layer operators (she_circuits.cpp) ----
+struct Netlist {
+    // wire ids: [0, cap) pool slots, cap = trivial 0, cap+1 = trivial 1, cap+2.. temporaries
+    uint32_t cap = 0;
+    uint32_t next_temp = 0;
+    std::vector<uint8_t> type;
+    std::vector<uint32_t> in0, in1, out;
+    std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates
+
+    explicit Netlist(uint32_t capacity) : cap(capacity), next_temp(capacity + 2) {}
+    uint32_t zero() const { return cap; }
+    uint32_t one() const { return cap + 1; }
+    uint32_t gate(int code, uint32_t a, uint32_t b);
+    uint32_t mux(uint32_t s, uint32_t u, uint32_t v);
+    // route the wires in `wires` to the caller's ids `dst`: gate outputs are renamed,
+    // anything else (inputs, constants, a wire used twice) is copied at the end
+    void bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst);
+    // stable sort of the gates by depth; returns the first gate index of each level (+ end)
+    std::vector<size_t> levelize();
+};
+std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const std::vector<uint32_t> &b, uint32_t cap_bits);
+std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const std::vector<uint32_t> &q);
+std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> terms, uint32_t in_bits, uint32_t acc_bits);
+std::vector<uint32_t> nl_max(Netlist &nl, const std::vector<uint32_t> &x, const std::vector<uint32_t> &y);
+
+}  // namespace she

@@ -1,0 +1,411 @@
+// HIP kernels of the bootstrapped-gate path for gfx950 (MI355X).
+//
+// One circuit level of G independent gates runs as three launches:
+//   k_lincomb       gate-specific TLWE linear combination + modulus switch to Z_2N
+//   k_blind_rotate  n CMux steps per gate (decompose, forward transforms, pointwise
+//                   products with the streamed spectral bootstrapping key, inverse
+//                   transforms), then sample extraction and key-switch digit rounding
+//   k_key_switch    subtraction of the selected key-switching rows
+// (SHE, arXiv 1906.00148: Section 3.1 for the gates, Section 2 for bootstrapping; the
+// construction itself is the cited TFHE gate bootstrapping.)
+#include "negacyclic_fft.h"
+#include "she_internal.h"
+
+namespace she {
+
+__device__ __forceinline__ uint32_t *ct_ptr(const CtSpace &cs, uint32_t id)
+{
+    return id < cs.cap ? cs.pool + (size_t)id * cs.stride : cs.temp + (size_t)(id - cs.cap) * cs.stride;
+}
+
+// ------------------------------------------------------------------------------------------
+// Linear combination and modulus switch.  One block per gate.
+// Pre-bootstrap sample = (0, off) + sa*ca + sb*cb, doubled for XOR/XNOR; every word is then
+// rounded to the nearest multiple of 1/2N.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void k_lincomb(CtSpace cs, const uint8_t *__restrict__ type,
+                                                 const uint32_t *__restrict__ in0, const uint32_t *__restrict__ in1,
+                                                 uint32_t n, uint32_t log2_2N, uint16_t *__restrict__ bar,
+                                                 uint32_t bar_stride)
+{
+    const uint32_t g = blockIdx.x;
+    const uint32_t ty = type[g];
+    const uint32_t e = 1u << 29;
+    // sign of ca, sign of cb, offset, doubling
+    uint32_t off = e; bool na = false, nb = false, dbl = false;
+    switch (ty) {
+    case SHE_AND:   off = 0u - e; break;
+    case SHE_NAND:  off = e; na = nb = true; break;
+    case SHE_OR:    off = e; break;
+    case SHE_NOR:   off = 0u - e; na = nb = true; break;
+    case SHE_XOR:   off = 2 * e; dbl = true; break;
+    case SHE_XNOR:  off = 0u - 2 * e; na = nb = true; dbl = true; break;
+    case SHE_ANDNY: off = 0u - e; na = true; break;
+    case SHE_ANDYN: off = 0u - e; nb = true; break;
+    case SHE_ORNY:  off = e; na = true; break;
+    default:        off = e; nb = true; break;     // SHE_ORYN
+    }
+    const uint32_t *ca = ct_ptr(cs, in0[g]);
+    const uint32_t *cb = ct_ptr(cs, in1[g]);
+    uint16_t *dst = bar + (size_t)g * bar_stride;
+    const uint32_t rnd = 1u << (31 - log2_2N), sh = 32 - log2_2N;
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) {
+        uint32_t a = ca[i], b = cb[i];
+        uint32_t x = (na ? 0u - a : a) + (nb ? 0u - b : b);
+        if (dbl) x += x;
+        if (i == n) x += off;
+        dst[i] = (uint16_t)((x + rnd) >> sh);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Blind rotation.  One gate per L lanes; a wavefront never talks to another one.
+// ------------------------------------------------------------------------------------------
+constexpr int BR_WAVES = 4;
+
+template <class PL, bool TRACK>
+__global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
+    const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
+    const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
+    uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err)
+{
+    constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
+    __shared__ uint32_t s_acc[BR_WAVES * GPW][2][N];
+    __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sub = lane / L, t = lane % L;
+    const int slot = wave * GPW + sub;
+    const uint32_t g_raw = (blockIdx.x * BR_WAVES + wave) * GPW + sub;
+    if ((blockIdx.x * BR_WAVES + wave) * GPW >= gates) return;          // whole wavefront idle
+    const bool live = g_raw < gates;
+    const uint32_t g = live ? g_raw : gates - 1;                          // idle lanes shadow the last gate
+
+    LaneCtx<PL> lc;
+    lc.init(t, s_xch[slot], tw_table);
+    uint32_t(*acc)[N] = s_acc[slot];
+    const uint16_t *mybar = bar + (size_t)g * bar_stride;
+
+    // ACC = (0, X^(-bbar) * testv), testv = 1/8 on every coefficient
+    {
+        const uint32_t bbar = mybar[n];
+        for (int j = t; j < N; j += L) {
+            acc[0][j] = 0;
+            acc[1][j] = (((uint32_t)j + bbar) & N) ? 0u - (1u << 29) : (1u << 29);
+        }
+    }
+    wave_lds_fence();
+
+    const uint32_t Bg = 1u << bg_bit, half_bg = Bg >> 1;
+    uint32_t dec_off = 1u << (31 - l * bg_bit);
+    for (uint32_t p = 1; p <= l; p++) dec_off += half_bg << (32 - p * bg_bit);
+    const double inv_m = 1.0 / (double)M;
+    float worst = 0.f;
+
+    uint32_t abar_next = mybar[0];
+    for (uint32_t i = 0; i < n; i++) {
+        const uint32_t abar = abar_next;
+        abar_next = mybar[i + 1];                                          // i+1 == n reads bbar: harmless
+        const double2 *bki = bk_hat + (size_t)i * (2 * l) * 2 * P * L;
+
+        double sr[2][P], si[2][P];                                         // spectra of the two output components
+#pragma unroll
+        for (int k = 0; k < P; k++) { sr[0][k] = si[0][k] = sr[1][k] = si[1][k] = 0.0; }
+
+        for (int c = 0; c < 2; c++) {
+            // D_c = X^abar * ACC_c - ACC_c at this lane's 2P coefficients
+            uint32_t dlo[P], dhi[P];
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                const uint32_t j0 = t + L * m, j1 = j0 + M;
+                const uint32_t s0 = (j0 - abar) & (2 * N - 1), s1 = (j1 - abar) & (2 * N - 1);
+                uint32_t v0 = acc[c][s0 & (N - 1)], v1 = acc[c][s1 & (N - 1)];
+                v0 = (s0 & N) ? 0u - v0 : v0;
+                v1 = (s1 & N) ? 0u - v1 : v1;
+                dlo[m] = v0 - acc[c][j0] + dec_off;
+                dhi[m] = v1 - acc[c][j1] + dec_off;
+            }
+            for (uint32_t p = 0; p < l; p++) {
+                const uint32_t sh = 32 - (p + 1) * bg_bit;
+                const double2 *row = bki + (size_t)(c * l + p) * 2 * P * L + t;
+                double xr[P], xi[P];
+#pragma unroll
+                for (int m = 0; m < P; m++) {
+                    xr[m] = (double)((int)((dlo[m] >> sh) & (Bg - 1)) - (int)half_bg);
+                    xi[m] = (double)((int)((dhi[m] >> sh) & (Bg - 1)) - (int)half_bg);
+                }
+                forward<PL>(lc, xr, xi);
+#pragma unroll
+                for (int o = 0; o < 2; o++) {
+#pragma unroll
+                    for (int k = 0; k < P; k++) {
+                        const double2 b = row[(o * P + k) * L];
+                        sr[o][k] += xr[k] * b.x - xi[k] * b.y;
+                        si[o][k] += xr[k] * b.y + xi[k] * b.x;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int o = 0; o < 2; o++) {
+            inverse<PL>(lc, sr[o], si[o]);
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                const double vr = sr[o][m] * inv_m, vi = si[o][m] * inv_m;
+                if (TRACK) {
+                    worst = fmaxf(worst, (float)fabs(vr - rint(vr)));
+                    worst = fmaxf(worst, (float)fabs(vi - rint(vi)));
+                }
+                // |v| < 2^51: adding 1.5*2^52 leaves round(v) mod 2^32 in the low word
+                const uint32_t ir = (uint32_t)__double2loint(vr + 6755399441055744.0);
+                const uint32_t ii = (uint32_t)__double2loint(vi + 6755399441055744.0);
+                acc[o][t + L * m] += ir;
+                acc[o][t + L * m + M] += ii;
+            }
+        }
+        wave_lds_fence();
+    }
+
+    if (TRACK && round_err) atomicMax(round_err, __float_as_uint(worst));
+
+    // sample extraction: a''_0 = A_0, a''_j = -A_{N-j}, b'' = B_0; keep the top ks_bits of each a'' rounded
+    if (live) {
+        const uint32_t rnd = 1u << (31 - ks_bits), sh = 32 - ks_bits;
+        uint16_t *dst = ksd + ((size_t)(g / KS_GROUP) * N) * KS_GROUP + (g % KS_GROUP);
+        for (int j = t; j < N; j += L) {
+            const uint32_t a = (j == 0) ? acc[0][0] : 0u - acc[0][N - j];
+            dst[(size_t)j * KS_GROUP] = (uint16_t)((a + rnd) >> sh);
+        }
+        if (t == 0) ext_b[g] = acc[1][0];
+    }
+}
+
+// Spectra of the bootstrapping key: one transform per (i, row, component) polynomial.
+template <class PL>
+__global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *__restrict__ bk_int,
+                                                                const double2 *__restrict__ tw_table,
+                                                                double2 *__restrict__ bk_hat, uint32_t polys)
+{
+    constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
+    __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sub = lane / L, t = lane % L;
+    const uint32_t first = (blockIdx.x * BR_WAVES + wave) * GPW;
+    if (first >= polys) return;
+    const bool live = first + sub < polys;
+    const uint32_t q = live ? first + sub : polys - 1;
+    LaneCtx<PL> lc;
+    lc.init(t, s_xch[wave * GPW + sub], tw_table);
+    const uint32_t *src = bk_int + (size_t)q * N;
+    double xr[P], xi[P];
+#pragma unroll
+    for (int m = 0; m < P; m++) {
+        xr[m] = (double)(int)src[t + L * m];                 // torus words taken as signed: centred, |x| <= 2^31
+        xi[m] = (double)(int)src[t + L * m + M];
+    }
+    forward<PL>(lc, xr, xi);
+    if (live) {
+        double2 *dst = bk_hat + (size_t)q * P * L + t;
+#pragma unroll
+        for (int k = 0; k < P; k++) dst[k * L] = make_double2(xr[k], xi[k]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Key switch.  Block = KS_GROUP gates x KS_COLS output words; every thread owns one output
+// word of all the gates, so each key row that is loaded serves KS_GROUP gates.
+// ------------------------------------------------------------------------------------------
+constexpr int KS_COLS = 128;
+
+__global__ __launch_bounds__(KS_COLS) void k_key_switch(CtSpace cs, const uint32_t *__restrict__ ks,
+                                                        uint32_t ks_stride, const uint16_t *__restrict__ ksd,
+                                                        const uint32_t *__restrict__ ext_b,
+                                                        const uint32_t *__restrict__ out_ids, uint32_t N, uint32_t t,
+                                                        uint32_t bb, uint32_t n, uint32_t gates)
+{
+    const uint32_t grp = blockIdx.x;
+    const uint32_t col = blockIdx.y * KS_COLS + threadIdx.x;
+    const uint32_t colc = col <= n ? col : n;
+    const uint32_t nrows = (1u << bb) - 1;
+    uint32_t acc[KS_GROUP];
+#pragma unroll
+    for (int g = 0; g < KS_GROUP; g++) acc[g] = 0;
+
+    const uint32_t *dg = (const uint32_t *)(ksd + (size_t)grp * N * KS_GROUP);
+    for (uint32_t i = 0; i < N; i++) {
+        uint32_t yw[KS_GROUP / 2];
+#pragma unroll
+        for (int q = 0; q < KS_GROUP / 2; q++) yw[q] = dg[(size_t)i * (KS_GROUP / 2) + q];
+        for (uint32_t j = 0; j < t; j++) {
+            const uint32_t sh = (t - 1 - j) * bb;
+            const uint32_t *rows = ks + ((size_t)(i * t + j) * nrows) * ks_stride + colc;
+            for (uint32_t v = 1; v <= nrows; v++) {
+                const uint32_t r = rows[(size_t)(v - 1) * ks_stride];
+#pragma unroll
+                for (int g = 0; g < KS_GROUP; g++) {
+                    const uint32_t y = (yw[g >> 1] >> (16 * (g & 1))) & 0xffffu;
+                    const uint32_t d = (y >> sh) & nrows;
+                    acc[g] -= (d == v) ? r : 0u;
+                }
+            }
+        }
+    }
+    if (col > n) return;
+#pragma unroll
+    for (int g = 0; g < KS_GROUP; g++) {
+        const uint32_t gi = grp * KS_GROUP + g;
+        if (gi < gates) {
+            uint32_t v = acc[g];
+            if (col == n) v += ext_b[gi];
+            ct_ptr(cs, out_ids[gi])[col] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Pool plumbing
+// ------------------------------------------------------------------------------------------
+__global__ void k_scatter(CtSpace cs, const uint32_t *__restrict__ src, const uint32_t *__restrict__ ids, uint32_t n)
+{
+    uint32_t *dst = ct_ptr(cs, ids[blockIdx.x]);
+    const uint32_t *s = src + (size_t)blockIdx.x * (n + 1);
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) dst[i] = s[i];
+}
+__global__ void k_gather(CtSpace cs, uint32_t *__restrict__ dst, const uint32_t *__restrict__ ids, uint32_t n)
+{
+    const uint32_t *s = ct_ptr(cs, ids[blockIdx.x]);
+    uint32_t *d = dst + (size_t)blockIdx.x * (n + 1);
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) d[i] = s[i];
+}
+__global__ void k_copy_ct(CtSpace cs, const uint32_t *__restrict__ src_ids, const uint32_t *__restrict__ dst_ids,
+                          uint32_t n)
+{
+    const uint32_t *s = ct_ptr(cs, src_ids[blockIdx.x]);
+    uint32_t *d = ct_ptr(cs, dst_ids[blockIdx.x]);
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) d[i] = s[i];
+}
+
+// ------------------------------------------------------------------------------------------
+// Host launchers
+// ------------------------------------------------------------------------------------------
+using Plan256 = Plan<1, 7>;
+using Plan512 = Plan<2, 4>;
+using Plan1024 = Plan<3, 3>;
+
+bool plan_supported(uint32_t N) { return N == 256 || N == 512 || N == 1024; }
+
+template <class PL> static size_t tw_doubles() { return (size_t)2 * (PL::K - 1) * PL::P * PL::L; }
+
+size_t twiddle_doubles(uint32_t N)
+{
+    switch (N) {
+    case 256: return tw_doubles<Plan256>();
+    case 512: return tw_doubles<Plan512>();
+    case 1024: return tw_doubles<Plan1024>();
+    }
+    return 0;
+}
+
+void fill_twiddles(uint32_t N, double *out)
+{
+    switch (N) {
+    case 256: make_twiddles<Plan256>(out); break;
+    case 512: make_twiddles<Plan512>(out); break;
+    case 1024: make_twiddles<Plan1024>(out); break;
+    }
+}
+
+size_t bk_hat_elems(const she_params &P) { return (size_t)P.n * 2 * P.l * 2 * (P.N / 2); }
+
+template <class PL>
+static hipError_t bk_transform_t(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st)
+{
+    const uint32_t polys = P.n * 2 * P.l * 2;
+    const uint32_t per_block = BR_WAVES * PL::GPW;
+    hipLaunchKernelGGL((k_bk_transform<PL>), dim3((polys + per_block - 1) / per_block), dim3(64 * BR_WAVES), 0, st,
+                       d_bk_int, K.twiddles, K.bk_hat, polys);
+    return hipGetLastError();
+}
+
+hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st)
+{
+    switch (P.N) {
+    case 256: return bk_transform_t<Plan256>(P, d_bk_int, K, st);
+    case 512: return bk_transform_t<Plan512>(P, d_bk_int, K, st);
+    case 1024: return bk_transform_t<Plan1024>(P, d_bk_int, K, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+static uint32_t ilog2(uint32_t v) { uint32_t r = 0; while ((1u << r) < v) r++; return r; }
+
+hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
+                          const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st)
+{
+    if (!gates) return hipSuccess;
+    hipLaunchKernelGGL(k_lincomb, dim3((unsigned)gates), dim3(128), 0, st, cs, d_type, d_in0, d_in1, P.n,
+                       ilog2(2 * P.N), W.bar, W.bar_stride);
+    return hipGetLastError();
+}
+
+template <class PL>
+static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
+                                 unsigned *d_round_err, hipStream_t st)
+{
+    const uint32_t per_block = BR_WAVES * PL::GPW;
+    const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
+    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
+    if (d_round_err)
+        hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err);
+    else
+        hipLaunchKernelGGL((k_blind_rotate<PL, false>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err);
+    return hipGetLastError();
+}
+
+hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
+                               unsigned *d_round_err, hipStream_t st)
+{
+    if (!gates) return hipSuccess;
+    switch (P.N) {
+    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, st);
+    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, st);
+    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                             size_t gates, const LevelWork &W, hipStream_t st)
+{
+    if (!gates) return hipSuccess;
+    const dim3 grid((unsigned)((gates + KS_GROUP - 1) / KS_GROUP), (P.n + 1 + KS_COLS - 1) / KS_COLS);
+    hipLaunchKernelGGL(k_key_switch, grid, dim3(KS_COLS), 0, st, cs, K.ks, K.ks_stride, W.ksd, W.ext_b, d_out, P.N,
+                       P.ks_t, P.ks_basebit, P.n, (uint32_t)gates);
+    return hipGetLastError();
+}
+
+hipError_t launch_scatter(const CtSpace &cs, const uint32_t *d_src, const uint32_t *d_ids, size_t count, uint32_t n,
+                          hipStream_t st)
+{
+    if (!count) return hipSuccess;
+    hipLaunchKernelGGL(k_scatter, dim3((unsigned)count), dim3(128), 0, st, cs, d_src, d_ids, n);
+    return hipGetLastError();
+}
+hipError_t launch_gather(const CtSpace &cs, uint32_t *d_dst, const uint32_t *d_ids, size_t count, uint32_t n,
+                         hipStream_t st)
+{
+    if (!count) return hipSuccess;
+    hipLaunchKernelGGL(k_gather, dim3((unsigned)count), dim3(128), 0, st, cs, d_dst, d_ids, n);
+    return hipGetLastError();
+}
+hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const uint32_t *d_dst_ids, size_t count,
+                          uint32_t n, hipStream_t st)
+{
+    if (!count) return hipSuccess;
+    hipLaunchKernelGGL(k_copy_ct, dim3((unsigned)count), dim3(128), 0, st, cs, d_src_ids, d_dst_ids, n);
+    return hipGetLastError();
+}
+
+}  // namespace she

@@ -1,0 +1,70 @@
+"""Seeded synthetic inputs shaped like the paper's workloads (arXiv 1906.00148, Section 4:
+MNIST-shaped 28x28 images, 3x3 kernels, 2x2 pooling, 16-bit accumulators, power-of-two
+weights).  Used by tests, the smoke check and the benchmark to feed the oracle and the GPU
+library the same values.  Holds none of the method's arithmetic: only random draws.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+KEY_SEED = 190600148
+GATE_NAMES_4 = ("NAND", "AND", "OR", "XOR")
+GATE_NAMES_5 = ("NAND", "AND", "OR", "XOR", "XNOR")
+GATE_CODE = {"NAND": 0, "AND": 1, "OR": 2, "XOR": 3, "XNOR": 4, "NOR": 5, "ANDNY": 6, "ANDYN": 7, "ORNY": 8, "ORYN": 9}
+
+
+def data_seed(cfg: int) -> int:
+    return 1000 + cfg
+
+
+def gate_level(ngates: int, names, seed: int):
+    """One level of independent gates: gate g reads fresh bits 2g and 2g+1.
+    Returns (input bits [2*ngates], gate codes [ngates])."""
+    rng = np.random.default_rng(seed)
+    bits = rng.integers(0, 2, 2 * ngates).astype(np.uint8)
+    codes = np.array([GATE_CODE[n] for n in names], np.uint8)[rng.integers(0, len(names), ngates)]
+    return bits, codes
+
+
+def cfg1_toy_level():
+    return gate_level(128, GATE_NAMES_4, data_seed(1))
+
+
+def cfg2_real_level(ngates: int = 4096):
+    return gate_level(ngates, GATE_NAMES_5, data_seed(2))
+
+
+def log_weights(shape, rng, max_shift: int = 7):
+    """sign in {+1,-1}, exponent uniform in [-max_shift, 0]"""
+    sign = rng.choice(np.array([-1, 1], np.int8), shape).astype(np.int8)
+    exp = (-rng.integers(0, max_shift + 1, shape)).astype(np.int8)
+    return sign, exp
+
+
+def cfg3_neuron(terms: int = 576, in_bits: int = 8, seed: int | None = None):
+    """One output neuron: `terms` unsigned activations and their log-quantized weights."""
+    rng = np.random.default_rng(data_seed(3) if seed is None else seed)
+    x = rng.integers(0, 1 << in_bits, (1, terms)).astype(np.int64)
+    sign, exp = log_weights((1, terms), rng, in_bits - 1)
+    return x, sign, exp
+
+
+def cfg4_feature_map(H: int = 32, W: int = 32, C: int = 16, seed: int | None = None):
+    """16-bit two's-complement feature map, normal(0, 2^10) rounded and clipped."""
+    rng = np.random.default_rng(data_seed(4) if seed is None else seed)
+    v = np.rint(rng.normal(0.0, 1024.0, (H, W, C)))
+    return np.clip(v, -32768, 32767).astype(np.int64)
+
+
+def cfg5_conv_layer(H: int = 28, W: int = 28, out_ch: int = 8, ksize: int = 3, seed: int | None = None):
+    """Grayscale-shaped 8-bit image and out_ch 3x3 log-quantized kernels."""
+    rng = np.random.default_rng(data_seed(5) if seed is None else seed)
+    img = rng.integers(0, 256, (H, W)).astype(np.int64)
+    sign, exp = log_weights((out_ch, ksize, ksize), rng, 7)
+    return img, sign, exp
+
+
+def subset(total: int, count: int, seed: int) -> np.ndarray:
+    """Sorted seeded sample of `count` indices out of `total` (for spot checks)."""
+    rng = np.random.default_rng(seed)
+    return np.sort(rng.choice(total, size=min(count, total), replace=False))

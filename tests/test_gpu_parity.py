@@ -1,0 +1,261 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle on the
+same seeded inputs.  Integer work throughout, so the bar is bit-exact ciphertext words and
+bit-exact decrypted bits.  Run with:  python -u -m pytest tests -m gpu -x -v --timeout 300
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import circuits as OC
+from oracle import tfhe as O
+
+pytestmark = pytest.mark.gpu
+
+
+def she():
+    import paper_1906_00148_amd as pkg
+    return pkg
+
+
+@pytest.fixture(scope="module")
+def toy_ctx():
+    pkg = she()
+    ctx = pkg.Context(pkg.TOY, S.KEY_SEED, 4096)
+    yield ctx
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def real_ctx():
+    pkg = she()
+    ctx = pkg.Context(pkg.REAL, S.KEY_SEED, 3 * 4096 + 64)
+    yield ctx
+    ctx.close()
+
+
+def plain(code, a, b):
+    return OC.plain_gate(int(code), int(a), int(b))
+
+
+# ------------------------------------------------------------------ keys and client side
+def test_keys_match_the_oracle_bit_for_bit(toy_ctx, toy_keys):
+    lwe, ring, bk, ks = toy_ctx.export_keys()
+    assert np.array_equal(lwe, toy_keys.lwe_key) and np.array_equal(ring, toy_keys.ring_key)
+    assert np.array_equal(bk, toy_keys.bk)
+    assert np.array_equal(ks, toy_keys.ks)
+
+
+def test_real_keys_match_the_oracle(real_ctx, real_keys):
+    lwe, ring, bk, ks = real_ctx.export_keys()
+    assert np.array_equal(lwe, real_keys.lwe_key) and np.array_equal(ring, real_keys.ring_key)
+    assert np.array_equal(bk, real_keys.bk) and np.array_equal(ks, real_keys.ks)
+
+
+def test_fresh_encryptions_and_decrypt(toy_ctx, toy_keys):
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 2, 300).astype(np.uint8)
+    ids = rng.permutation(4096)[:300].astype(np.uint32)
+    toy_ctx.encrypt_bits(bits, 31337, ids)
+    want = O.encrypt_bits(toy_keys, bits, 31337)
+    got = toy_ctx.read_cts(ids[:40])
+    assert np.array_equal(got, want[:40])
+    assert np.array_equal(toy_ctx.decrypt(ids), bits)
+    assert np.array_equal(O.decrypt_bits(toy_keys, got), bits[:40])
+
+
+def test_write_then_read_roundtrip(toy_ctx):
+    ct = np.arange(129, dtype=np.uint32) * 2654435761 % (1 << 32)
+    toy_ctx.write_ct(7, ct)
+    assert np.array_equal(toy_ctx.read_ct(7), ct.astype(np.uint32))
+
+
+# ------------------------------------------------------------------ config 1: toy level, every word
+def test_cfg1_toy_level_bit_exact(toy_ctx, toy_keys):
+    bits, codes = S.cfg1_toy_level()
+    G = codes.size
+    in_ids = np.arange(2 * G, dtype=np.uint32)
+    out_ids = np.arange(2 * G, 3 * G, dtype=np.uint32)
+    toy_ctx.encrypt_bits(bits, S.data_seed(1), in_ids)
+    toy_ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+    got = toy_ctx.read_cts(out_ids)
+    pool = np.zeros((3 * G, toy_keys.params.n + 1), np.uint32)
+    pool[: 2 * G] = O.encrypt_bits(toy_keys, bits, S.data_seed(1))
+    O.eval_gates(toy_keys, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
+    assert np.array_equal(got, pool[2 * G:])
+    dec = toy_ctx.decrypt(out_ids)
+    assert np.array_equal(dec, [plain(c, bits[2 * g], bits[2 * g + 1]) for g, c in enumerate(codes)])
+    # deterministic: a second run of the same level gives the same words
+    toy_ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+    assert np.array_equal(toy_ctx.read_cts(out_ids), got)
+
+
+def test_every_gate_type_and_ragged_batch_sizes_toy(toy_ctx, toy_keys):
+    # 10 gate types x 4 input combinations = 40 gates, then batch sizes that leave idle lanes and wavefronts
+    combos = np.array([[a, b] for a in (0, 1) for b in (0, 1)], np.uint8)
+    bits = np.tile(combos.ravel(), 10)
+    in_ids = np.arange(80, dtype=np.uint32)
+    toy_ctx.encrypt_bits(bits, 77, in_ids)
+    codes = np.repeat(np.arange(10, dtype=np.uint8), 4)
+    out_ids = np.arange(100, 140, dtype=np.uint32)
+    fresh = O.encrypt_bits(toy_keys, bits, 77)
+    for count in (40, 1, 3, 5, 33):
+        toy_ctx.eval_gates(codes[:count], in_ids[0:2 * count:2], in_ids[1:2 * count:2], out_ids[:count])
+        got = toy_ctx.read_cts(out_ids[:count])
+        for g in range(count):
+            want = O.gate(toy_keys, int(codes[g]), fresh[2 * g], fresh[2 * g + 1])
+            assert np.array_equal(got[g], want), (count, g)
+        dec = toy_ctx.decrypt(out_ids[:count])
+        assert dec.tolist() == [plain(codes[g], bits[2 * g], bits[2 * g + 1]) for g in range(count)]
+
+
+def test_gates_on_bootstrapped_inputs_chain_toy(toy_ctx, toy_keys):
+    bits = np.array([1, 0, 1], np.uint8)
+    toy_ctx.encrypt_bits(bits, 9, np.array([0, 1, 2], np.uint32))
+    fresh = O.encrypt_bits(toy_keys, bits, 9)
+    cur_o, cur_bit, cur_id = fresh[0], 1, 0
+    names = ("XOR", "NAND", "XNOR", "ORNY", "ANDYN", "NOR")
+    for d in range(6):
+        code = O.GATES[names[d]]
+        other = 1 + d % 2
+        nid = 10 + d
+        toy_ctx.eval_gates([code], [cur_id], [other], [nid])
+        cur_o = O.gate(toy_keys, code, cur_o, fresh[other])
+        cur_bit = plain(code, cur_bit, bits[other])
+        assert np.array_equal(toy_ctx.read_ct(nid), cur_o), d
+        assert int(toy_ctx.decrypt([nid])[0]) == cur_bit
+        cur_id = nid
+
+
+# ------------------------------------------------------------------ config 2: real parameters
+def test_cfg2_real_level(real_ctx, real_keys):
+    G = 4096
+    bits, codes = S.cfg2_real_level(G)
+    in_ids = np.arange(2 * G, dtype=np.uint32)
+    out_ids = np.arange(2 * G, 3 * G, dtype=np.uint32)
+    real_ctx.encrypt_bits(bits, S.data_seed(2), in_ids)
+    real_ctx.set_round_tracking(True)
+    real_ctx.get_round_error(reset=True)
+    real_ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+    worst = real_ctx.get_round_error()
+    real_ctx.set_round_tracking(False)
+    # every one of 4096*630*2048 rounded inverse-transform outputs sat this close to an integer
+    print(f"\nmax distance from an integer before rounding: {worst:.4f}")
+    assert worst < 0.2
+    dec = real_ctx.decrypt(out_ids)
+    want_bits = np.array([plain(c, bits[2 * g], bits[2 * g + 1]) for g, c in enumerate(codes)], np.uint8)
+    assert np.array_equal(dec, want_bits)
+    # seeded 32-gate subset, every ciphertext word, against the oracle
+    sub = S.subset(G, 32, 2)
+    fresh_sub = O.encrypt_bits(real_keys, bits, S.data_seed(2))
+    pool = np.zeros((3 * G, real_keys.params.n + 1), np.uint32)
+    pool[: 2 * G] = fresh_sub
+    O.eval_gates(real_keys, pool, codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub], threads=16)
+    got = real_ctx.read_cts(out_ids[sub])
+    assert np.array_equal(got, pool[out_ids[sub]])
+    # the production kernel (tracking off) gives the same words
+    real_ctx.eval_gates(codes[:64], in_ids[0:128:2], in_ids[1:128:2], out_ids[:64])
+    again = real_ctx.read_cts(out_ids[sub[sub < 64]])
+    assert np.array_equal(again, pool[out_ids[sub[sub < 64]]])
+
+
+# ------------------------------------------------------------------ layer operators, toy parameters, ciphertext level
+def _encrypt_values(ctx, keys, values, bits, seed, first_id):
+    b = OC.to_bits(np.asarray(values), bits).ravel()
+    ids = np.arange(first_id, first_id + b.size, dtype=np.uint32)
+    ctx.encrypt_bits(b, seed, ids)
+    return ids, O.encrypt_bits(keys, b, seed)
+
+
+def test_shift_acc_small_matches_oracle_netlist_toy(toy_ctx, toy_keys):
+    x = np.array([[5, 7, 2, 6, 1], [3, 3, 0, 7, 4]])
+    sign = np.array([[1, -1, 1, 1, -1], [1, 1, 1, 1, 1]], np.int8)
+    exp = np.array([[0, -1, 0, -2, 0], [0, 0, -1, -2, 0]], np.int8)
+    in_bits, acc_bits = 3, 6
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 41, 0)
+    out_ids = np.arange(1000, 1000 + 2 * acc_bits, dtype=np.uint32).reshape(2, acc_bits)
+    gates = toy_ctx.shift_acc(ids.reshape(2, 5, in_bits), sign, exp, acc_bits, out_ids)
+    nl, outs = OC.build_shift_acc(2, 5, in_bits, sign, exp, acc_bits)
+    assert gates == len(nl.gtype)
+    pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+    got = toy_ctx.read_cts(out_ids)
+    assert np.array_equal(got, pool[np.array(outs).ravel()])
+    dec = OC.from_bits(toy_ctx.decrypt(out_ids), True)
+    assert np.array_equal(dec, OC.plain_shift_acc(x, sign, exp, acc_bits))
+
+
+def test_relu_and_maxpool_small_match_oracle_netlist_toy(toy_ctx, toy_keys):
+    vals = np.array([[[-3], [2]], [[1], [-4]]])                       # H=2, W=2, C=1, 4-bit
+    bits = 4
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, vals, bits, 43, 0)
+    relu_ids = np.arange(2000, 2000 + ids.size, dtype=np.uint32)
+    g1 = toy_ctx.relu(ids.reshape(4, bits), relu_ids.reshape(4, bits))
+    nl, outs = OC.build_relu(4, bits)
+    assert g1 == len(nl.gtype) == 12
+    pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+    relu_want = pool[np.array(outs).ravel()]
+    assert np.array_equal(toy_ctx.read_cts(relu_ids), relu_want)
+    assert OC.from_bits(toy_ctx.decrypt(relu_ids.reshape(4, bits)), True).tolist() == [0, 2, 1, 0]
+    # pooling of the ReLU outputs (bootstrapped and trivial ciphertexts as inputs)
+    pool_ids = np.arange(3000, 3000 + bits, dtype=np.uint32)
+    g2 = toy_ctx.maxpool(relu_ids.reshape(2, 2, 1, bits), pool_ids.reshape(1, 1, 1, bits))
+    nl2, outs2 = OC.build_maxpool(2, 2, 1, bits)
+    assert g2 == len(nl2.gtype) == 3 * (bits + 6 * bits)
+    pool2 = nl2.run_encrypted(toy_keys, relu_want, threads=8)
+    assert np.array_equal(toy_ctx.read_cts(pool_ids), pool2[np.array(outs2).ravel()])
+    assert int(OC.from_bits(toy_ctx.decrypt(pool_ids), True)) == 2
+
+
+def test_shift_acc_edge_cases_toy(toy_ctx, toy_keys):
+    # single positive term (pure re-wiring, no gate), all-negative terms, no terms at all
+    x = np.array([[6]])
+    ids, _ = _encrypt_values(toy_ctx, toy_keys, x, 3, 47, 0)
+    out = np.arange(500, 505, dtype=np.uint32).reshape(1, 5)
+    assert toy_ctx.shift_acc(ids.reshape(1, 1, 3), [[1]], [[-1]], 5, out) == 0
+    assert int(OC.from_bits(toy_ctx.decrypt(out), True)[0]) == 3
+    x = np.array([[6, 5]])
+    ids, _ = _encrypt_values(toy_ctx, toy_keys, x, 3, 48, 0)
+    toy_ctx.shift_acc(ids.reshape(1, 2, 3), [[-1, -1]], [[0, 0]], 5, out)
+    assert int(OC.from_bits(toy_ctx.decrypt(out), True)[0]) == -11
+    assert toy_ctx.shift_acc(np.zeros((1, 0, 3), np.uint32), np.zeros((1, 0), np.int8), np.zeros((1, 0), np.int8), 5, out) == 0
+    assert int(OC.from_bits(toy_ctx.decrypt(out), True)[0]) == 0
+
+
+# ------------------------------------------------------------------ error paths (host-side checks, no kernel runs)
+def test_error_codes(toy_ctx):
+    pkg = she()
+    toy_ctx.eval_gates([], [], [], [])                                             # empty level is a no-op
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates([0], [0], [1], [4096])
+    assert e.value.code == -4
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates([10], [0], [1], [2])
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates([0], [0], [1], [1])                                     # output overwrites an input
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates([0, 0], [0, 0], [1, 1], [2, 2])                         # same output twice
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.encrypt_bits([2], 1, [0])
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.decrypt([99999])
+    assert e.value.code == -4
+
+
+# ------------------------------------------------------------------ another ring degree
+def test_ring_degree_512(toy_keys):
+    pkg = she()
+    P = pkg.Params(n=96, N=512)
+    K = O.keygen(O.Params(n=96, N=512), 321)
+    with pkg.Context(P, 321, 256) as ctx:
+        bits, codes = S.gate_level(24, S.GATE_NAMES_5, 9)
+        in_ids = np.arange(48, dtype=np.uint32)
+        out_ids = np.arange(48, 72, dtype=np.uint32)
+        ctx.encrypt_bits(bits, 11, in_ids)
+        ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+        pool = np.zeros((72, 97), np.uint32)
+        pool[:48] = O.encrypt_bits(K, bits, 11)
+        O.eval_gates(K, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
+        assert np.array_equal(ctx.read_cts(out_ids), pool[48:])
