@@ -58,6 +58,9 @@ def load_library() -> C.CDLL:
     if not os.path.exists(path):
         from . import build as _build
         _build.build()
+    # PyTorch ships its own HIP runtime under the same soname; load it first so that this
+    # process holds one runtime only (two runtimes do not share the device).
+    import torch  # noqa: F401
     L = C.CDLL(path)
     u8p, u32p, i8p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint32), C.POINTER(C.c_int8)
     ctx, u64p = C.c_void_p, C.POINTER(C.c_uint64)
