@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the bootstrapped-gate hot path on one MI355X.
+
+A step = one pass of the whole path (linear combination + modulus switch, blind rotation,
+sample extraction, key switch) over one circuit level of 4096 independent gates at
+n=630, N=1024 (the workload the metric is quoted on), with keys, input ciphertexts and the
+gate arrays already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--conv-layer]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+GATES_PER_LEVEL = 4096
+# Algorithmic FP64 work of the blind rotation per gate at n=630, N=1024, l=3 (FFT route):
+# per CMux 6 forward + 2 inverse 512-point complex transforms (5*512*9 butterfly flops plus
+# the 6*512 twist each = 26.1 KFLOP) and 12*512 complex multiply-adds (8 flops each = 49.2 KFLOP),
+# i.e. 0.258 MFLOP per CMux, times 630 CMux.
+FLOP_PER_CMUX = 8 * (5 * 512 * 9 + 6 * 512) + 12 * 512 * 8
+FLOP_PER_GATE = 630 * FLOP_PER_CMUX
+FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop/FMA x 2.4 GHz
+# HBM bytes per blind-rotation launch from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE runs, scaled by
+# a copy kernel of known size); None until measured for the current kernel.  See profiles/.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def cpu_baseline(sample_gates: int):
+    """The oracle, as it stands, on this machine's host cores, on the first gates of the same workload."""
+    import numpy as np
+
+    import synth_inputs as S
+    from oracle import tfhe as O
+
+    threads = max(1, min(os.cpu_count() or 1, 16))
+    bits, codes = S.cfg2_real_level(GATES_PER_LEVEL)
+    K = O.keygen(O.REAL, S.KEY_SEED)
+    g = sample_gates
+    fresh = O.encrypt_bits(K, bits[: 2 * g], S.data_seed(2))
+    pool = np.zeros((3 * g, K.params.n + 1), np.uint32)
+    pool[: 2 * g] = fresh
+    ids = np.arange(2 * g, dtype=np.uint32)
+    t0 = time.perf_counter()
+    O.eval_gates(K, pool, codes[:g], ids[0::2], ids[1::2], np.arange(2 * g, 3 * g, dtype=np.uint32), threads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": g / dt, "unit": "gates/s", "cores": min(threads, g), "kind": "oracle",
+            "sample": f"first {g} gates of the 4096-gate level, schoolbook negacyclic products, "
+                      f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
+
+
+def conv_layer(ctx_factory):
+    """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
+    accumulators), ReLU, 2x2 max pool; returns latency and gate counts."""
+    import numpy as np
+
+    import synth_inputs as S
+
+    img, sign, exp = S.cfg5_conv_layer()
+    H, W = img.shape
+    oc, k = sign.shape[0], sign.shape[1]
+    oh, ow = H - k + 1, W - k + 1
+    n_in = H * W * 8
+    conv_ids = n_in + np.arange(oh * ow * oc * 16, dtype=np.uint32)
+    relu_ids = conv_ids[-1] + 1 + np.arange(oh * ow * oc * 16, dtype=np.uint32)
+    pool_ids = relu_ids[-1] + 1 + np.arange((oh // 2) * (ow // 2) * oc * 16, dtype=np.uint32)
+    ctx = ctx_factory(int(pool_ids[-1]) + 1)
+    bits = ((img[..., None] >> np.arange(8)) & 1).astype(np.uint8)
+    in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, 8)
+    ctx.encrypt_bits(bits.ravel(), S.data_seed(5), in_ids.ravel())
+    # receptive fields: unit (y, x, c) reads the k*k pixels under it
+    x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)
+    for dy in range(k):
+        for dx in range(k):
+            x_ids[:, :, :, dy * k + dx, :] = in_ids[dy:dy + oh, dx:dx + ow, None, :]
+    w_sign = np.broadcast_to(sign.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
+    w_exp = np.broadcast_to(exp.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
+    t0 = time.perf_counter()
+    g1 = ctx.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, 16, conv_ids.reshape(-1, 16))
+    t1 = time.perf_counter()
+    g2 = ctx.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+    t2 = time.perf_counter()
+    g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
+    t3 = time.perf_counter()
+    ctx.close()
+    total = g1 + g2 + g3
+    return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
+            "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
+            "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
+            "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-gates", type=int, default=16)
+    ap.add_argument("--conv-layer", action="store_true", help="also time config 5 (one conv layer, ~2.8M gates)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; gates of a level would be sharded across GPUs "
+              "with replicated keys, which is not built. Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1906_00148_amd as she
+    import synth_inputs as S
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
+    torch.cuda.set_device(0)
+    G = GATES_PER_LEVEL
+    bits, codes = S.cfg2_real_level(G)
+    ctx = she.Context(she.REAL, S.KEY_SEED, 3 * G)
+    in_ids = np.arange(2 * G, dtype=np.uint32)
+    ctx.encrypt_bits(bits, S.data_seed(2), in_ids)
+    d_type = torch.from_numpy(codes.copy()).cuda()
+    d_in0 = torch.from_numpy(in_ids[0::2].astype(np.int32)).cuda()
+    d_in1 = torch.from_numpy(in_ids[1::2].astype(np.int32)).cuda()
+    d_out = torch.arange(2 * G, 3 * G, dtype=torch.int32, device="cuda")
+
+    def step():
+        ctx.eval_gates_device(d_type.data_ptr(), d_in0.data_ptr(), d_in1.data_ptr(), d_out.data_ptr(), G)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.last_timing()                       # drop the warm-up's events
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    tim = ctx.last_timing()                 # HIP events on the kernels' stream, summed over the timed steps
+    # correctness of what was timed: every output decrypts to the plain gate
+    dec = ctx.decrypt(np.arange(2 * G, 3 * G, dtype=np.uint32))
+    table = {0: lambda a, b: 1 - (a & b), 1: lambda a, b: a & b, 2: lambda a, b: a | b, 3: lambda a, b: a ^ b,
+             4: lambda a, b: 1 - (a ^ b)}
+    want = np.array([table[int(c)](int(bits[2 * g]), int(bits[2 * g + 1])) for g, c in enumerate(codes)], np.uint8)
+    assert np.array_equal(dec, want), "timed level decrypts wrongly"
+
+    ms_per_step = dt / args.steps * 1e3
+    br_ms = tim["blind_rotate_ms"] / args.steps
+    achieved = FLOP_PER_GATE * G / (br_ms * 1e-3) / 1e12
+    out = {
+        "metric": "bootstrapped TFHE gates/sec at n=630,N=1024 on 1 MI355X; conv-layer latency",
+        "value": G * args.steps / dt, "unit": "gates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": "one level of 4096 independent bootstrapped gates (NAND/AND/OR/XOR/XNOR uniform) on "
+                               "fresh encryptions of uniform bits, n=630 N=1024 k=1 Bgbit=7 l=3 ks t=8 base 4",
+                   "gates_per_step": G, "seed": S.KEY_SEED},
+        "kernels_ms_per_step": {"lincomb": tim["lincomb_ms"] / args.steps, "blind_rotate": br_ms,
+                                "key_switch": tim["key_switch_ms"] / args.steps},
+        "roofline": {"bound": "alu", "kernel": "k_blind_rotate", "achieved": achieved,
+                     "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES},
+        "paper_context": {"value": 77, "unit": "gates/s", "note": "implied by the paper's projected fully-homomorphic "
+                          "latency / gate count (about 13 ms per gate), Xeon E7-4850, different parameter set"},
+    }
+    ctx.close()
+    if args.conv_layer:
+        out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -161,10 +161,13 @@ int she_eval_gates_device(she_ctx *ctx, const uint8_t *d_type, const uint32_t *d
 int she_set_round_tracking(she_ctx *ctx, int on);
 int she_get_round_error(she_ctx *ctx, double *max_abs_frac, int reset);
 
-/* Milliseconds spent by the last she_eval_gates / layer-operator call in each kernel
- * family, measured with HIP events on the context's stream: ms[0] linear combination,
- * ms[1] blind rotation + extraction, ms[2] key switch, ms[3] number of levels launched. */
-int she_last_timing(const she_ctx *ctx, double ms[4]);
+/* Kernel timing with HIP events on the context's stream (on by default; she_set_timing(ctx, 0)
+ * removes the events).  she_last_timing gives the milliseconds spent in each kernel family by
+ * the last she_eval_gates / layer-operator call, or summed over all she_eval_gates_device
+ * calls since the previous she_last_timing (it then waits for the stream): ms[0] linear
+ * combination, ms[1] blind rotation + extraction, ms[2] key switch, ms[3] levels launched. */
+int she_set_timing(she_ctx *ctx, int on);
+int she_last_timing(she_ctx *ctx, double ms[4]);
 
 /* Text of the last error of this context ("" if none).  ctx may be NULL: then the text
  * of the last failed she_keygen of the calling thread. */

@@ -8,6 +8,22 @@
 
 using namespace she;
 
+namespace {
+struct LevelTimer {           // events around the three kernel families of every chunk
+    std::vector<hipEvent_t> ev;
+    ~LevelTimer() { clear(); }
+    void clear() { for (auto e : ev) hipEventDestroy(e); ev.clear(); }
+    hipError_t mark(hipStream_t st)
+    {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return rc;
+        ev.push_back(e);
+        return hipEventRecord(e, st);
+    }
+};
+}  // namespace
+
 struct she_ctx {
     she_params P{};
     int device = 0;
@@ -28,6 +44,9 @@ struct she_ctx {
     size_t d_stage_words = 0;
     unsigned *d_round_err = nullptr;
     bool track_round = false;
+    bool timing = true;                  // record HIP events around every kernel
+    LevelTimer timer;                    // events not yet folded into last_ms
+    size_t timer_levels = 0;
     double last_ms[4] = {0, 0, 0, 0};
     std::string err;
 };
@@ -109,24 +128,13 @@ int ensure_stage(she_ctx *c, size_t words)
     return SHE_OK;
 }
 
-struct LevelTimer {           // events around the three kernel families of every chunk
-    std::vector<hipEvent_t> ev;
-    ~LevelTimer() { for (auto e : ev) hipEventDestroy(e); }
-    hipError_t mark(hipStream_t st)
-    {
-        hipEvent_t e;
-        hipError_t rc = hipEventCreate(&e);
-        if (rc != hipSuccess) return rc;
-        ev.push_back(e);
-        return hipEventRecord(e, st);
-    }
-};
-
 // Enqueues one level (device arrays), cut into chunks of at most MAX_LEVEL_CHUNK gates.
 int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
-                  const uint32_t *d_out, size_t gates, LevelTimer *timer)
+                  const uint32_t *d_out, size_t gates)
 {
     const CtSpace cs = space(c);
+    LevelTimer *timer = c->timing ? &c->timer : nullptr;
+    c->timer_levels++;
     for (size_t off = 0; off < gates; off += MAX_LEVEL_CHUNK) {
         const size_t cnt = std::min<size_t>(MAX_LEVEL_CHUNK, gates - off);
         if (timer) HIP_TRY(c, timer->mark(c->stream));
@@ -140,8 +148,12 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
     return SHE_OK;
 }
 
-int finish_timing(she_ctx *c, LevelTimer &timer, size_t levels)
+// Folds the recorded events into last_ms; the stream must have finished.
+int finish_timing(she_ctx *c)
 {
+    LevelTimer &timer = c->timer;
+    const size_t levels = c->timer_levels;
+    c->timer_levels = 0;
     double ms[3] = {0, 0, 0};
     for (size_t q = 0; q + 3 < timer.ev.size(); q += 4)
         for (int f = 0; f < 3; f++) {
@@ -149,6 +161,7 @@ int finish_timing(she_ctx *c, LevelTimer &timer, size_t levels)
             HIP_TRY(c, hipEventElapsedTime(&t, timer.ev[q + f], timer.ev[q + f + 1]));
             ms[f] += t;
         }
+    timer.clear();
     c->last_ms[0] = ms[0]; c->last_ms[1] = ms[1]; c->last_ms[2] = ms[2]; c->last_ms[3] = (double)levels;
     return SHE_OK;
 }
@@ -180,7 +193,8 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
     for (size_t lv = 0; lv + 1 < bounds.size(); lv++) widest = std::max(widest, bounds[lv + 1] - bounds[lv]);
     if ((rc = ensure_work(c, std::min<size_t>(widest, MAX_LEVEL_CHUNK)))) return rc;
     if ((rc = ensure_gate_arrays(c, std::max(G, nl.copy_src.size())))) return rc;
-    LevelTimer timer;
+    c->timer.clear();
+    c->timer_levels = 0;
     if (G) {
         HIP_TRY(c, hipMemcpyAsync(c->d_type, nl.type.data(), G, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_in0, nl.in0.data(), G * 4, hipMemcpyHostToDevice, c->stream));
@@ -188,7 +202,7 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         HIP_TRY(c, hipMemcpyAsync(c->d_out, nl.out.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         for (size_t lv = 0; lv + 1 < bounds.size(); lv++) {
             const size_t a = bounds[lv], b = bounds[lv + 1];
-            if ((rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, b - a, &timer))) return rc;
+            if ((rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, b - a))) return rc;
         }
     }
     if (!nl.copy_src.empty()) {
@@ -199,7 +213,7 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         HIP_TRY(c, launch_copy_ct(space(c), c->d_in0, c->d_in1, n_copy, c->P.n, c->stream));
     }
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return finish_timing(c, timer, bounds.empty() ? 0 : bounds.size() - 1);
+    return finish_timing(c);
 }
 
 // ids must be inside the pool; marks them in `seen` (if given) and reports duplicates
@@ -372,10 +386,11 @@ int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const u
     HIP_TRY(c, hipMemcpyAsync(c->d_in0, in0, ngates * 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->d_in1, in1, ngates * 4, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipMemcpyAsync(c->d_out, out, ngates * 4, hipMemcpyHostToDevice, c->stream));
-    LevelTimer timer;
-    if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates, &timer))) return rc;
+    c->timer.clear();
+    c->timer_levels = 0;
+    if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    return finish_timing(c, timer, 1);
+    return finish_timing(c);
 }
 
 int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
@@ -386,7 +401,7 @@ int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_i
     if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
     int rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK));
     if (rc) return rc;
-    return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates, nullptr);
+    return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates);
 }
 
 int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
@@ -568,9 +583,24 @@ int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
     return SHE_OK;
 }
 
-int she_last_timing(const she_ctx *c, double ms[4])
+int she_set_timing(she_ctx *c, int on)
+{
+    if (!c) return SHE_EINVAL;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->timer.clear();
+    c->timer_levels = 0;
+    c->timing = on != 0;
+    return SHE_OK;
+}
+
+int she_last_timing(she_ctx *c, double ms[4])
 {
     if (!c || !ms) return SHE_EINVAL;
+    if (!c->timer.ev.empty()) {          // events of she_eval_gates_device calls still pending
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        int rc = finish_timing(c);
+        if (rc) return rc;
+    }
     for (int i = 0; i < 4; i++) ms[i] = c->last_ms[i];
     return SHE_OK;
 }
