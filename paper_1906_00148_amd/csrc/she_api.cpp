@@ -140,7 +140,7 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream));
+        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
@@ -283,13 +283,21 @@ int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, 
         if (e == hipSuccess) e = hipDeviceSynchronize();
         hipFree(d_bk_int);
         HIP_TRY(cc, e);
-        // key-switching key, rows padded to the slot stride
-        const uint32_t rows = P.N * P.ks_t * ((1u << P.ks_basebit) - 1);
-        cc->dk.ks_stride = cc->stride;
-        HIP_TRY(cc, hipMalloc((void **)&cc->dk.ks, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
-        HIP_TRY(cc, hipMemset(cc->dk.ks, 0, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
-        HIP_TRY(cc, hipMemcpy2D(cc->dk.ks, cc->dk.ks_stride * sizeof(uint32_t), cc->hk.ks.data(), (P.n + 1) * sizeof(uint32_t),
-                                (P.n + 1) * sizeof(uint32_t), rows, hipMemcpyHostToDevice));
+        // key-switching key: signed byte planes for the MFMA kernel (base 4, 8 digits), else padded rows
+        if (P.ks_basebit == 2 && P.ks_t == 8) {
+            cc->dk.ks_cols = round_up(P.n + 1, 32);
+            std::vector<int8_t> packed;
+            pack_ks_bytes(P, cc->hk.ks, cc->dk.ks_cols, packed);
+            HIP_TRY(cc, hipMalloc((void **)&cc->dk.ks_bytes, packed.size()));
+            HIP_TRY(cc, hipMemcpy(cc->dk.ks_bytes, packed.data(), packed.size(), hipMemcpyHostToDevice));
+        } else {
+            const uint32_t rows = P.N * P.ks_t * ((1u << P.ks_basebit) - 1);
+            cc->dk.ks_stride = cc->stride;
+            HIP_TRY(cc, hipMalloc((void **)&cc->dk.ks, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
+            HIP_TRY(cc, hipMemset(cc->dk.ks, 0, (size_t)rows * cc->dk.ks_stride * sizeof(uint32_t)));
+            HIP_TRY(cc, hipMemcpy2D(cc->dk.ks, cc->dk.ks_stride * sizeof(uint32_t), cc->hk.ks.data(), (P.n + 1) * sizeof(uint32_t),
+                                    (P.n + 1) * sizeof(uint32_t), rows, hipMemcpyHostToDevice));
+        }
         // pool and internal slots
         HIP_TRY(cc, hipMalloc((void **)&cc->pool, (size_t)cc->cap * cc->stride * sizeof(uint32_t)));
         HIP_TRY(cc, hipMemset(cc->pool, 0, (size_t)cc->cap * cc->stride * sizeof(uint32_t)));
@@ -309,7 +317,7 @@ void she_free(she_ctx *c)
 {
     if (!c) return;
     if (c->stream) hipStreamSynchronize(c->stream); else hipDeviceSynchronize();
-    hipFree(c->dk.bk_hat); hipFree(c->dk.ks); hipFree(c->dk.twiddles);
+    hipFree(c->dk.bk_hat); hipFree(c->dk.ks); hipFree(c->dk.ks_bytes); hipFree(c->dk.twiddles);
     if (c->pool_owned) hipFree(c->pool);
     hipFree(c->temp);
     hipFree(c->work.bar); hipFree(c->work.ext_b); hipFree(c->work.ksd);

@@ -132,6 +132,27 @@ void fresh_samples(const she_params &P, const std::vector<uint8_t> &lwe_key, con
     });
 }
 
+void pack_ks_bytes(const she_params &P, const std::vector<uint32_t> &ks, uint32_t cols_p, std::vector<int8_t> &out)
+{
+    // word = s0 + 256*s1 + 256^2*s2 + 256^3*s3 (mod 2^32) with every s in [-128, 127]
+    const uint32_t n = P.n, t = P.ks_t, rows_per = (1u << P.ks_basebit) - 1, kk = t * (rows_per + 1);
+    out.assign((size_t)P.N * 4 * cols_p * kk, 0);
+    parallel_for(P.N, [&](size_t i) {
+        for (uint32_t j = 0; j < t; j++)
+            for (uint32_t v = 1; v <= rows_per; v++) {
+                const uint32_t *row = ks.data() + (((size_t)i * t + j) * rows_per + (v - 1)) * (n + 1);
+                for (uint32_t c = 0; c <= n; c++) {
+                    uint32_t w = row[c];
+                    for (uint32_t plane = 0; plane < 4; plane++) {
+                        const int8_t s = (int8_t)(w & 0xffu);
+                        w = (w - (uint32_t)(int32_t)s) >> 8;
+                        out[(((size_t)i * 4 + plane) * cols_p + c) * kk + j * (rows_per + 1) + v] = s;
+                    }
+                }
+            }
+    });
+}
+
 void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint32_t *cts, size_t count,
                     uint8_t *bits)
 {

@@ -25,7 +25,9 @@ struct CtSpace {
 
 struct DeviceKeys {
     double2 *bk_hat = nullptr;    // [n][2l][2][P][L] spectra of the bootstrapping key
-    uint32_t *ks = nullptr;       // [N][t][base-1][ks_stride]
+    uint32_t *ks = nullptr;       // [N][t][base-1][ks_stride]; only for key-switch shapes without an MFMA kernel
+    int8_t *ks_bytes = nullptr;   // [N][4 byte planes][ks_cols][32 = 8 digits x 4 values] signed bytes (base 4, t = 8)
+    uint32_t ks_cols = 0;         // n+1 rounded up to 32
     double2 *twiddles = nullptr;  // [K-1][P][L]
     uint32_t ks_stride = 0;
 };
@@ -47,8 +49,9 @@ size_t bk_hat_elems(const she_params &P);   // number of double2 in DeviceKeys::
 hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st);
 hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
                           const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
-hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
-                               unsigned *d_round_err /* nullptr = no tracking */, hipStream_t st);
+hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                               size_t gates, const LevelWork &W, unsigned *d_round_err /* nullptr = no tracking */,
+                               hipStream_t st);
 hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                              size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_scatter(const CtSpace &cs, const uint32_t *d_src /* [count][n+1] */, const uint32_t *d_ids,
@@ -67,6 +70,8 @@ struct HostKeys {
 void generate_keys(const she_params &P, uint64_t seed, HostKeys &out);
 void fresh_samples(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint8_t *bits, size_t nbits,
                    uint64_t enc_seed, uint32_t *out /* [nbits][n+1] */);
+// key-switching key as signed byte planes for the MFMA kernel: out[i][plane][col][j*4+v]
+void pack_ks_bytes(const she_params &P, const std::vector<uint32_t> &ks, uint32_t cols_p, std::vector<int8_t> &out);
 void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint32_t *cts, size_t count,
                     uint8_t *bits);
 

@@ -67,7 +67,8 @@ template <class PL, bool TRACK>
 __global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
     const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
     const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
-    uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err)
+    uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err, CtSpace cs,
+    const uint32_t *__restrict__ out_ids)
 {
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
     __shared__ uint32_t s_acc[BR_WAVES * GPW][2][N];
@@ -177,6 +178,12 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
             dst[(size_t)j * KS_GROUP] = (uint16_t)((a + rnd) >> sh);
         }
         if (t == 0) ext_b[g] = acc[1][0];
+        // the key switch subtracts its rows from (0, b''): leave that in the output slot
+        if (out_ids) {
+            uint32_t *o = ct_ptr(cs, out_ids[g]);
+            const uint32_t body = acc[1][0];
+            for (uint32_t c = t; c <= n; c += L) o[c] = (c == n) ? body : 0u;
+        }
     }
 }
 
@@ -258,6 +265,85 @@ __global__ __launch_bounds__(KS_COLS) void k_key_switch(CtSpace cs, const uint32
             uint32_t v = acc[g];
             if (col == n) v += ext_b[gi];
             ct_ptr(cs, out_ids[gi])[col] = v;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Key switch as an int8 matrix product on the MFMA units (base 4, 8 digits).
+//   out[g][c] = (0, b'')[c] - sum_{i,j} KS[i][j][d_gij][c]
+// is sum_k A[g][k] * KS[k][c] with A the one-hot encoding of the digits, k = (i, j, v).  A is
+// 0/1 and every KS word is split into four signed bytes, so four i32 += i8*i8 products
+// (|sum| <= 2^20) recombined with shifts give the exact result modulo 2^32.
+// One v_mfma_i32_32x32x32_i8 consumes the 32 k of one i (8 digits x 4 values; the v = 0
+// column of A is always 0).  A wavefront owns 64 gates x 32 output words; a block of four
+// wavefronts shares the key bytes through L1; blockIdx.z splits the i range and partial
+// sums are subtracted atomically from the slot that the blind rotation initialised.
+// ------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+constexpr int KSM_WAVES = 4, KSM_TILES = 2;
+
+__device__ __forceinline__ int onehot_byte(uint32_t d) { return (int)((1u << (d << 3)) & 0xFFFFFF00u); }
+
+__global__ __launch_bounds__(64 * KSM_WAVES) void k_key_switch_mfma(CtSpace cs, const int8_t *__restrict__ ksb,
+                                                                     uint32_t cols_p, const uint16_t *__restrict__ ksd,
+                                                                     const uint32_t *__restrict__ out_ids, uint32_t N,
+                                                                     uint32_t n, uint32_t gates, uint32_t i_per_block)
+{
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, c32 = lane & 31;
+    const uint32_t tile0 = (blockIdx.x * KSM_WAVES + wave) * KSM_TILES;          // in units of 32 gates
+    if (tile0 * 32 >= gates) return;
+    const uint32_t col = blockIdx.y * 32 + c32;
+    const uint32_t i0 = blockIdx.z * i_per_block, i1 = min(N, i0 + i_per_block);
+
+    v16i acc[KSM_TILES][4];
+#pragma unroll
+    for (int t = 0; t < KSM_TILES; t++)
+#pragma unroll
+        for (int p = 0; p < 4; p++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[t][p][r] = 0;
+
+    const uint16_t *yp[KSM_TILES];
+    bool tile_live[KSM_TILES];
+#pragma unroll
+    for (int t = 0; t < KSM_TILES; t++) {
+        tile_live[t] = (tile0 + t) * 32 < gates;
+        yp[t] = ksd + ((size_t)(tile_live[t] ? tile0 + t : tile0) * N) * KS_GROUP + c32;
+    }
+    const int8_t *bbase = ksb + ((size_t)col * 32 + 16 * half);
+    const uint32_t ysh = 8 * (1 - half);
+
+    for (uint32_t i = i0; i < i1; i++) {
+        v4i b[4];
+#pragma unroll
+        for (int p = 0; p < 4; p++) b[p] = *(const v4i *)(bbase + ((size_t)i * 4 + p) * cols_p * 32);
+#pragma unroll
+        for (int t = 0; t < KSM_TILES; t++) {
+            const uint32_t y = ((uint32_t)yp[t][(size_t)i * KS_GROUP] >> ysh) & 0xffu;   // this half's four digits
+            v4i a;
+            a.x = onehot_byte((y >> 6) & 3);
+            a.y = onehot_byte((y >> 4) & 3);
+            a.z = onehot_byte((y >> 2) & 3);
+            a.w = onehot_byte(y & 3);
+#pragma unroll
+            for (int p = 0; p < 4; p++) acc[t][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[p], acc[t][p], 0, 0, 0);
+        }
+    }
+
+    if (col > n) return;
+#pragma unroll
+    for (int t = 0; t < KSM_TILES; t++) {
+        if (!tile_live[t]) continue;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const uint32_t row = 8 * (r / 4) + 4 * half + (r % 4);       // accumulator layout of the 32x32 MFMA
+            const uint32_t g = (tile0 + t) * 32 + row;
+            if (g >= gates) continue;
+            const uint32_t v = (uint32_t)acc[t][0][r] + ((uint32_t)acc[t][1][r] << 8) + ((uint32_t)acc[t][2][r] << 16) +
+                               ((uint32_t)acc[t][3][r] << 24);
+            atomicAdd(ct_ptr(cs, out_ids[g]) + col, 0u - v);
         }
     }
 }
@@ -350,28 +436,29 @@ hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t 
 
 template <class PL>
 static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
-                                 unsigned *d_round_err, hipStream_t st)
+                                 unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st)
 {
     const uint32_t per_block = BR_WAVES * PL::GPW;
     const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
     const uint32_t ks_bits = P.ks_t * P.ks_basebit;
     if (d_round_err)
         hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err);
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out);
     else
         hipLaunchKernelGGL((k_blind_rotate<PL, false>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err);
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out);
     return hipGetLastError();
 }
 
-hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
-                               unsigned *d_round_err, hipStream_t st)
+hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                               size_t gates, const LevelWork &W, unsigned *d_round_err, hipStream_t st)
 {
     if (!gates) return hipSuccess;
+    if (!K.ks_bytes) d_out = nullptr;      // the generic key switch writes the slot itself
     switch (P.N) {
-    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, st);
-    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, st);
-    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, st);
+    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, cs, d_out, st);
+    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, cs, d_out, st);
+    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, cs, d_out, st);
     }
     return hipErrorInvalidValue;
 }
@@ -380,6 +467,17 @@ hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtS
                              size_t gates, const LevelWork &W, hipStream_t st)
 {
     if (!gates) return hipSuccess;
+    if (K.ks_bytes) {
+        const unsigned gate_blocks = (unsigned)((gates + 64 * KSM_WAVES - 1) / (64 * KSM_WAVES));
+        const unsigned col_tiles = K.ks_cols / 32;
+        // split the i range until about a thousand blocks are in flight
+        unsigned split = 1;
+        while (split < 32 && gate_blocks * col_tiles * split < 1024 && P.N / (split * 2) >= 8) split *= 2;
+        const dim3 grid(gate_blocks, col_tiles, split);
+        hipLaunchKernelGGL(k_key_switch_mfma, grid, dim3(64 * KSM_WAVES), 0, st, cs, K.ks_bytes, K.ks_cols, W.ksd, d_out,
+                           P.N, P.n, (uint32_t)gates, P.N / split);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)((gates + KS_GROUP - 1) / KS_GROUP), (P.n + 1 + KS_COLS - 1) / KS_COLS);
     hipLaunchKernelGGL(k_key_switch, grid, dim3(KS_COLS), 0, st, cs, K.ks, K.ks_stride, W.ksd, W.ext_b, d_out, P.N,
                        P.ks_t, P.ks_basebit, P.n, (uint32_t)gates);
