@@ -15,6 +15,8 @@
 // were read from.  The twist and the first pass share one per-lane twiddle.
 #pragma once
 #include <hip/hip_runtime.h>
+// device arithmetic may fuse multiply-adds (the host's key generation is compiled without fusion)
+#pragma clang fp contract(fast)
 #include <stdint.h>
 #include <cmath>
 
@@ -55,7 +57,6 @@ template <int LOGP_, int K_> struct Plan {
     static constexpr int GPW = 64 / L;                // transforms (gates) per wavefront
     static constexpr int XROW = L + 1;                // padded row of the exchange buffer (16-byte slots)
     static constexpr int XSLOTS = P * XROW;           // exchange slots per transform
-    static constexpr int NTW = (K - 1) * P;           // per-lane twiddles
     static_assert(L >= 1 && L <= 64 && 64 % L == 0, "one transform must fit a wavefront");
 };
 
@@ -109,53 +110,67 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Per-lane constants of a transform: twiddles in registers and exchange addresses.
-template <class PL> struct LaneCtx {
-    double twr[PL::NTW > 0 ? PL::NTW : 1], twi[PL::NTW > 0 ? PL::NTW : 1];   // [pass s-1][k]
-    int rd_base[PL::K > 1 ? PL::K - 1 : 1];   // slot read by this lane after pass s (register m adds m*T_{s+1})
-    int t;                                     // lane within the transform
-    double2 *xch;                              // this transform's exchange buffer (XSLOTS slots)
+// Twiddle table, shared by every transform of a workgroup (kept in LDS by the kernels).
+// Pass s (0-based, s < K-1) multiplies output k of lane t by
+//   s = 0: exp(i*pi*t*(1+4k)/N)                    (twist psi^t merged with the first pass)
+//   s > 0: exp(2*pi*i*k*(t mod T)/(P*T)), T = P^(K-1-s)
+// which depends on t only through t mod T, so pass s stores P*T entries: [k][t mod T].
+template <class PL> struct TwTable {
+    static constexpr int period(int s) { return ipow(PL::P, PL::K - 1 - s); }              // T of pass s
+    static constexpr int offset(int s) { return s == 0 ? 0 : offset(s - 1) + PL::P * period(s - 1); }
+    static constexpr int COUNT = PL::K > 1 ? offset(PL::K - 1) : 1;                          // complex entries
+};
 
-    // tw_table: [K-1][P][L] complex, device memory, filled by make_twiddles() on the host
-    __device__ __forceinline__ void init(int lane_in_transform, double2 *xbuf, const double2 *tw_table)
+template <class PL> inline void make_twiddles(double *out /* [TwTable::COUNT][2] */)
+{
+    const long double pi = 3.14159265358979323846264338327950288L;
+    for (int s = 0; s + 1 < PL::K; s++) {
+        const int T = TwTable<PL>::period(s);
+        for (int k = 0; k < PL::P; k++)
+            for (int t = 0; t < T; t++) {
+                const long double ang = s == 0 ? pi * (long double)t * (1 + 4 * k) / (long double)PL::N
+                                               : 2.0L * pi * (long double)k * t / (long double)(PL::P * T);
+                double *o = out + 2 * ((size_t)TwTable<PL>::offset(s) + (size_t)k * T + t);
+                o[0] = (double)cosl(ang);
+                o[1] = (double)sinl(ang);
+            }
+    }
+}
+
+// Per-lane view of a transform: exchange addresses and where this lane's twiddles start.
+template <class PL> struct LaneCtx {
+    static constexpr int NP = PL::K > 1 ? PL::K - 1 : 1;
+    int rd_base[NP];        // slot read by this lane after pass s (register m adds m*T_{s+1})
+    int t;                  // lane within the transform
+    double2 *xch;           // this transform's exchange buffer (XSLOTS slots)
+    const double2 *tw;      // the workgroup's twiddle table in LDS
+
+    __device__ __forceinline__ void init(int lane_in_transform, double2 *xbuf, const double2 *tw_lds)
     {
         t = lane_in_transform;
         xch = xbuf;
+        tw = tw_lds;
 #pragma unroll
         for (int s = 0; s < PL::K - 1; s++) {
-#pragma unroll
-            for (int k = 0; k < PL::P; k++) {
-                const double2 w = tw_table[(s * PL::P + k) * PL::L + t];
-                twr[s * PL::P + k] = w.x;
-                twi[s * PL::P + k] = w.y;
-            }
-            const int Ts = ipow(PL::P, PL::K - 1 - s);       // sub-transform length after pass s+1 (1-based s+1)
+            const int Ts = ipow(PL::P, PL::K - 1 - s);       // sub-transform length after pass s
             const int Tn = Ts / PL::P;
             const int q = t / Tn, tn = t % Tn, ks = q % PL::P, kap = q / PL::P;
             rd_base[s] = ks * PL::XROW + tn + Ts * kap;
         }
     }
+    // twiddle of pass s, output k
+    __device__ __forceinline__ double2 twiddle(int s, int k) const
+    {
+        const int T = TwTable<PL>::period(s);
+        return tw[TwTable<PL>::offset(s) + k * T + (t & (T - 1))];
+    }
 };
 
-// Host side of LaneCtx::init: twiddle of pass s (1-based), output k, lane t.
-//   s = 1: exp(i*pi*t*(1+4k)/N)   (twist psi^t merged with the first pass)
-//   s > 1: exp(2*pi*i*k*(t mod T_s)/T_{s-1}),  T_s = P^(K-s)
-template <class PL> inline void make_twiddles(double *out /* [K-1][P][L][2] */)
+// Copies the twiddle table from device memory to the workgroup's LDS copy (all threads, then a barrier).
+template <class PL> __device__ __forceinline__ void load_twiddles(double2 *lds, const double2 *__restrict__ global_table)
 {
-    for (int s = 1; s < PL::K; s++)
-        for (int k = 0; k < PL::P; k++)
-            for (int t = 0; t < PL::L; t++) {
-                long double ang;
-                if (s == 1) {
-                    ang = 3.14159265358979323846264338327950288L * (long double)t * (1 + 4 * k) / (long double)PL::N;
-                } else {
-                    const int Ts = ipow(PL::P, PL::K - s), Tp = Ts * PL::P;
-                    ang = 2.0L * 3.14159265358979323846264338327950288L * (long double)k * (t % Ts) / (long double)Tp;
-                }
-                double *o = out + 2 * (((size_t)(s - 1) * PL::P + k) * PL::L + t);
-                o[0] = (double)cosl(ang);
-                o[1] = (double)sinl(ang);
-            }
+    for (int e = threadIdx.x; e < TwTable<PL>::COUNT; e += blockDim.x) lds[e] = global_table[e];
+    __syncthreads();
 }
 
 // Forward transform.  In: xr/xi[m] = u_{t + L*m} (folded, not yet twisted).  Out: spectrum in
@@ -177,10 +192,10 @@ template <class PL> __device__ __forceinline__ void forward(const LaneCtx<PL> &l
         if (s == K - 1) break;
 #pragma unroll
         for (int k = (s == 0 ? 0 : 1); k < P; k++) {
-            const double wr = lc.twr[s * P + k], wi = lc.twi[s * P + k];
+            const double2 w = lc.twiddle(s, k);
             const double r = xr[k], i = xi[k];
-            xr[k] = r * wr - i * wi;
-            xi[k] = r * wi + i * wr;
+            xr[k] = r * w.x - i * w.y;
+            xi[k] = r * w.y + i * w.x;
         }
         wave_lds_fence();
 #pragma unroll
@@ -216,10 +231,10 @@ template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &l
             }
 #pragma unroll
             for (int k = (s == 0 ? 0 : 1); k < P; k++) {            // conjugate twiddle
-                const double wr = lc.twr[s * P + k], wi = lc.twi[s * P + k];
+                const double2 w = lc.twiddle(s, k);
                 const double r = xr[k], i = xi[k];
-                xr[k] = r * wr + i * wi;
-                xi[k] = i * wr - r * wi;
+                xr[k] = r * w.x + i * w.y;
+                xi[k] = i * w.x - r * w.y;
             }
         }
         dft_regs<P, -1>(xr, xi);

@@ -10,6 +10,7 @@
 // construction itself is the cited TFHE gate bootstrapping.)
 #include "negacyclic_fft.h"
 #include "she_internal.h"
+#pragma clang fp contract(fast)
 
 namespace she {
 
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(128) void k_lincomb(CtSpace cs, const uint8_t *__re
 constexpr int BR_WAVES = 4;
 
 template <class PL, bool TRACK>
-__global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
+__global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
     const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
     const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
     uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err, CtSpace cs,
@@ -73,17 +74,19 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
     __shared__ uint32_t s_acc[BR_WAVES * GPW][2][N];
     __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
+    __shared__ double2 s_tw[TwTable<PL>::COUNT];
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane / L, t = lane % L;
     const int slot = wave * GPW + sub;
     const uint32_t g_raw = (blockIdx.x * BR_WAVES + wave) * GPW + sub;
+    load_twiddles<PL>(s_tw, tw_table);                                    // the only workgroup barrier
     if ((blockIdx.x * BR_WAVES + wave) * GPW >= gates) return;          // whole wavefront idle
     const bool live = g_raw < gates;
     const uint32_t g = live ? g_raw : gates - 1;                          // idle lanes shadow the last gate
 
     LaneCtx<PL> lc;
-    lc.init(t, s_xch[slot], tw_table);
+    lc.init(t, s_xch[slot], s_tw);
     uint32_t(*acc)[N] = s_acc[slot];
     const uint16_t *mybar = bar + (size_t)g * bar_stride;
 
@@ -99,7 +102,8 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
 
     const uint32_t Bg = 1u << bg_bit, half_bg = Bg >> 1;
     uint32_t dec_off = 1u << (31 - l * bg_bit);
-    for (uint32_t p = 1; p <= l; p++) dec_off += half_bg << (32 - p * bg_bit);
+    uint32_t flip = 0;      // top bit of every digit field: field ^ top, read as signed, is field - Bg/2
+    for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
     const double inv_m = 1.0 / (double)M;
     float worst = 0.f;
 
@@ -123,24 +127,44 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_blind_rotate(
                 uint32_t v0 = acc[c][s0 & (N - 1)], v1 = acc[c][s1 & (N - 1)];
                 v0 = (s0 & N) ? 0u - v0 : v0;
                 v1 = (s1 & N) ? 0u - v1 : v1;
-                dlo[m] = v0 - acc[c][j0] + dec_off;
-                dhi[m] = v1 - acc[c][j1] + dec_off;
+                // + dec_off: rounding and digit centring; ^ flip: turns each field into its signed digit
+                dlo[m] = (v0 - acc[c][j0] + dec_off) ^ flip;
+                dhi[m] = (v1 - acc[c][j1] + dec_off) ^ flip;
             }
             for (uint32_t p = 0; p < l; p++) {
                 const uint32_t sh = 32 - (p + 1) * bg_bit;
-                const double2 *row = bki + (size_t)(c * l + p) * 2 * P * L + t;
+                const uint32_t r = c * l + p;
+                const double2 *row = bki + (size_t)r * 2 * P * L + t;
+                // the row's spectra are requested now and consumed after the transform
+                double2 bv[2][P];
+#pragma unroll
+                for (int o = 0; o < 2; o++)
+#pragma unroll
+                    for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
+                // touch the rows needed two transforms later so that they are in L2 by then
+                if (wave == 0) {
+                    const size_t q = (size_t)i * 2 * l + r + 2;
+                    if (q < (size_t)n * 2 * l) {
+                        const char *ahead = (const char *)(bk_hat + q * 2 * P * L);
+                        for (uint32_t off = lane * 128u; off < 2u * P * L * sizeof(double2); off += 64u * 128u)
+                            (void)*(const volatile uint32_t *)(ahead + off);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 double xr[P], xi[P];
 #pragma unroll
                 for (int m = 0; m < P; m++) {
-                    xr[m] = (double)((int)((dlo[m] >> sh) & (Bg - 1)) - (int)half_bg);
-                    xi[m] = (double)((int)((dhi[m] >> sh) & (Bg - 1)) - (int)half_bg);
+                    // the builtin returns unsigned: go through int so that the conversion is signed
+                    xr[m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], sh, bg_bit);
+                    xi[m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], sh, bg_bit);
                 }
                 forward<PL>(lc, xr, xi);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int o = 0; o < 2; o++) {
 #pragma unroll
                     for (int k = 0; k < P; k++) {
-                        const double2 b = row[(o * P + k) * L];
+                        const double2 b = bv[o][k];
                         sr[o][k] += xr[k] * b.x - xi[k] * b.y;
                         si[o][k] += xr[k] * b.y + xi[k] * b.x;
                     }
@@ -195,14 +219,16 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
 {
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
     __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
+    __shared__ double2 s_tw[TwTable<PL>::COUNT];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int sub = lane / L, t = lane % L;
     const uint32_t first = (blockIdx.x * BR_WAVES + wave) * GPW;
+    load_twiddles<PL>(s_tw, tw_table);
     if (first >= polys) return;
     const bool live = first + sub < polys;
     const uint32_t q = live ? first + sub : polys - 1;
     LaneCtx<PL> lc;
-    lc.init(t, s_xch[wave * GPW + sub], tw_table);
+    lc.init(t, s_xch[wave * GPW + sub], s_tw);
     const uint32_t *src = bk_int + (size_t)q * N;
     double xr[P], xi[P];
 #pragma unroll
@@ -380,7 +406,7 @@ using Plan1024 = Plan<3, 3>;
 
 bool plan_supported(uint32_t N) { return N == 256 || N == 512 || N == 1024; }
 
-template <class PL> static size_t tw_doubles() { return (size_t)2 * (PL::K - 1) * PL::P * PL::L; }
+template <class PL> static size_t tw_doubles() { return 2 * (size_t)TwTable<PL>::COUNT; }
 
 size_t twiddle_doubles(uint32_t N)
 {
