@@ -45,7 +45,8 @@ _lib = None
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libshe_hip.so")
+    """Path of the built library; SHE_HIP_LIB overrides it (to compare builds of the kernels)."""
+    return os.environ.get("SHE_HIP_LIB") or os.path.join(_HERE, "libshe_hip.so")
 
 
 def load_library() -> C.CDLL:

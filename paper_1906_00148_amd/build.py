@@ -18,14 +18,15 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra: list[str] | None = None) -> str:
+def build(verbose: bool = False, extra: list[str] | None = None, out: str | None = None) -> str:
     """Compiles every source each time it is called; returns the path of the shared library."""
-    cmd = [HIPCC] + FLAGS + (extra or []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH + ".tmp"]
+    out = out or LIB_PATH
+    cmd = [HIPCC] + FLAGS + (extra or []) + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out + ".tmp"]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    os.replace(LIB_PATH + ".tmp", LIB_PATH)
-    return LIB_PATH
+    subprocess.check_call(cmd, stderr=None if verbose else subprocess.DEVNULL)
+    os.replace(out + ".tmp", out)
+    return out
 
 
 if __name__ == "__main__":

@@ -102,7 +102,9 @@ template <int P, int SIGN> __device__ __forceinline__ void dft_regs(double (&xr)
 }
 
 // Orders LDS traffic of one wavefront: a wave's LDS operations complete in issue order,
-// so only the compiler has to be kept from moving them across this point.
+// so only the compiler has to be kept from moving them across this point.  It is required:
+// without it the compiler does reorder the exchange's stores and loads (other lanes' slots
+// look independent to it) and results are wrong.
 __device__ __forceinline__ void wave_lds_fence()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -210,8 +212,8 @@ template <class PL> __device__ __forceinline__ void forward(const LaneCtx<PL> &l
     }
 }
 
-// Inverse transform, unnormalised mirror of forward(); the caller's scale folds in 1/M.
-// Out: xr/xi[m] = M * u_{t + L*m}.
+// Inverse transform, the mirror of forward(); the 1/M normalisation is folded into the last
+// constant multiplication.  Out: xr/xi[m] = u_{t + L*m}.
 template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
@@ -239,9 +241,12 @@ template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &l
         }
         dft_regs<P, -1>(xr, xi);
     }
+    constexpr double scale = 1.0 / (double)PL::M;                    // a power of two: products stay exact
+    xr[0] *= scale;
+    xi[0] *= scale;
 #pragma unroll
-    for (int m = 1; m < P; m++) {                                    // conjugate of psi^(L*m)
-        const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
+    for (int m = 1; m < P; m++) {                                    // conjugate of psi^(L*m), times 1/M
+        const double cr = cos_pi64(32 * m / P) * scale, ci = sin_pi64(32 * m / P) * scale;
         const double r = xr[m], i = xi[m];
         xr[m] = r * cr + i * ci;
         xi[m] = i * cr - r * ci;

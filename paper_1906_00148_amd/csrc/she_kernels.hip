@@ -104,7 +104,6 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
     uint32_t dec_off = 1u << (31 - l * bg_bit);
     uint32_t flip = 0;      // top bit of every digit field: field ^ top, read as signed, is field - Bg/2
     for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
-    const double inv_m = 1.0 / (double)M;
     float worst = 0.f;
 
     uint32_t abar_next = mybar[0];
@@ -141,15 +140,6 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
                 for (int o = 0; o < 2; o++)
 #pragma unroll
                     for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
-                // touch the rows needed two transforms later so that they are in L2 by then
-                if (wave == 0) {
-                    const size_t q = (size_t)i * 2 * l + r + 2;
-                    if (q < (size_t)n * 2 * l) {
-                        const char *ahead = (const char *)(bk_hat + q * 2 * P * L);
-                        for (uint32_t off = lane * 128u; off < 2u * P * L * sizeof(double2); off += 64u * 128u)
-                            (void)*(const volatile uint32_t *)(ahead + off);
-                    }
-                }
                 __builtin_amdgcn_sched_barrier(0);
                 double xr[P], xi[P];
 #pragma unroll
@@ -176,7 +166,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
             inverse<PL>(lc, sr[o], si[o]);
 #pragma unroll
             for (int m = 0; m < P; m++) {
-                const double vr = sr[o][m] * inv_m, vi = si[o][m] * inv_m;
+                const double vr = sr[o][m], vi = si[o][m];
                 if (TRACK) {
                     worst = fmaxf(worst, (float)fabs(vr - rint(vr)));
                     worst = fmaxf(worst, (float)fabs(vi - rint(vi)));
