@@ -6,7 +6,7 @@ sample extraction, key switch) over one circuit level of 4096 independent gates 
 n=630, N=1024 (the workload the metric is quoted on), with keys, input ciphertexts and the
 gate arrays already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--conv-layer]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-conv-layer]
 """
 from __future__ import annotations
 
@@ -103,8 +103,11 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-gates", type=int, default=16)
-    ap.add_argument("--conv-layer", action="store_true", help="also time config 5 (one conv layer, ~2.8M gates)")
+    ap.add_argument("--cpu-sample-gates", type=int, default=64)
+    ap.add_argument("--no-conv-layer", action="store_true", help="skip config 5 (one conv layer, ~2.5M gates, ~15 s)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device-to-device copy (reference kernel for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; gates of a level would be sharded across GPUs "
@@ -169,7 +172,14 @@ def main():
                           "latency / gate count (about 13 ms per gate), Xeon E7-4850, different parameter set"},
     }
     ctx.close()
-    if args.conv_layer:
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calibration_copy_bytes"] = int(src.numel() * 4)
+        del src, dst
+    if not args.no_conv_layer:
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)

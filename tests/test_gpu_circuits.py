@@ -57,3 +57,71 @@ def test_cfg4_relu_maxpool_reduced_and_corner_values(ctx):
     pool2 = pool_ids + 5000
     ctx.maxpool(ids, pool2)
     assert np.array_equal(OC.from_bits(ctx.decrypt(pool2), True), OC.plain_maxpool2x2(fm))
+
+
+def test_cfg4_full_feature_map_relu_then_pool():
+    """32x32x16 map of 16-bit values: 245,760 ReLU gates in one level, then 1,376,256 pooling gates."""
+    import paper_1906_00148_amd as pkg
+    fm = S.cfg4_feature_map()
+    H, W, C = fm.shape
+    n_in = fm.size * 16
+    with pkg.Context(pkg.REAL, S.KEY_SEED, 2 * n_in + (H // 2) * (W // 2) * C * 16) as c:
+        ids = encrypt_values(c, fm, 16, S.data_seed(4))
+        relu_ids = ids + n_in
+        g1 = c.relu(ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+        t1 = c.last_timing()
+        assert g1 == H * W * C * 15 and t1["levels"] == 1
+        pool_ids = (2 * n_in + np.arange((H // 2) * (W // 2) * C * 16, dtype=np.uint32)).reshape(H // 2, W // 2, C, 16)
+        g2 = c.maxpool(relu_ids, pool_ids)
+        t2 = c.last_timing()
+        assert g2 == (H // 2) * (W // 2) * C * 3 * 112
+        print(f"\ncfg4: relu {g1} gates {t1['blind_rotate_ms'] + t1['key_switch_ms']:.0f} ms; "
+              f"pool {g2} gates in {t2['levels']} levels {t2['blind_rotate_ms'] + t2['key_switch_ms']:.0f} ms")
+        want = OC.plain_maxpool2x2(OC.plain_relu(fm))
+        assert np.array_equal(OC.from_bits(c.decrypt(pool_ids), True), want)
+        # sampled ReLU outputs
+        sub = S.subset(H * W * C, 512, 4)
+        got = OC.from_bits(c.decrypt(relu_ids.reshape(-1, 16)[sub]), True)
+        assert np.array_equal(got, OC.plain_relu(fm).reshape(-1)[sub])
+
+
+def test_cfg5_conv_layer_full():
+    """28x28x1 -> 3x3 conv, 8 channels (shift-accumulate) -> ReLU -> 2x2 max pool, all 1352 outputs checked."""
+    import paper_1906_00148_amd as pkg
+    img, sign, exp = S.cfg5_conv_layer()
+    H, W = img.shape
+    oc, k = sign.shape[0], sign.shape[1]
+    oh, ow = H - k + 1, W - k + 1
+    n_in = H * W * 8
+    n_conv = oh * ow * oc * 16
+    n_pool = (oh // 2) * (ow // 2) * oc * 16
+    with pkg.Context(pkg.REAL, S.KEY_SEED, n_in + 2 * n_conv + n_pool) as c:
+        in_ids = encrypt_values(c, img, 8, S.data_seed(5))                       # [H][W][8]
+        x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)
+        for dy in range(k):
+            for dx in range(k):
+                x_ids[:, :, :, dy * k + dx, :] = in_ids[dy:dy + oh, dx:dx + ow, None, :]
+        w_sign = np.broadcast_to(sign.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
+        w_exp = np.broadcast_to(exp.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
+        conv_ids = (n_in + np.arange(n_conv, dtype=np.uint32)).reshape(oh, ow, oc, 16)
+        relu_ids = conv_ids + n_conv
+        pool_ids = (n_in + 2 * n_conv + np.arange(n_pool, dtype=np.uint32)).reshape(oh // 2, ow // 2, oc, 16)
+        g1 = c.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, 16, conv_ids.reshape(-1, 16))
+        t1 = c.last_timing()
+        g2 = c.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+        g3 = c.maxpool(relu_ids, pool_ids)
+        t3 = c.last_timing()
+        print(f"\ncfg5: conv {g1} gates / {t1['levels']} levels, relu {g2}, pool {g3} gates / {t3['levels']} levels; "
+              f"total {g1 + g2 + g3}")
+        # plain integer reference: windows, shifts, signed sum mod 2^16, ReLU, pool
+        patches = np.zeros((oh, ow, k * k), np.int64)
+        for dy in range(k):
+            for dx in range(k):
+                patches[:, :, dy * k + dx] = img[dy:dy + oh, dx:dx + ow]
+        conv = np.stack([OC.plain_shift_acc(patches.reshape(-1, k * k), np.tile(sign[ch].reshape(1, -1), (oh * ow, 1)),
+                                            np.tile(exp[ch].reshape(1, -1), (oh * ow, 1)), 16).reshape(oh, ow)
+                         for ch in range(oc)], axis=-1)
+        sub = S.subset(oh * ow * oc, 256, 5)
+        assert np.array_equal(OC.from_bits(c.decrypt(conv_ids.reshape(-1, 16)[sub]), True), conv.reshape(-1)[sub])
+        want = OC.plain_maxpool2x2(OC.plain_relu(conv))
+        assert np.array_equal(OC.from_bits(c.decrypt(pool_ids), True), want)
