@@ -58,9 +58,10 @@ def cpu_baseline(sample_gates: int):
                       f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
 
 
-def conv_layer(ctx_factory):
+def conv_layer(ctx_factory, fold: bool):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
-    accumulators), ReLU, 2x2 max pool; returns latency and gate counts."""
+    accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
+    skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS)."""
     import numpy as np
 
     import synth_inputs as S
@@ -74,6 +75,7 @@ def conv_layer(ctx_factory):
     relu_ids = conv_ids[-1] + 1 + np.arange(oh * ow * oc * 16, dtype=np.uint32)
     pool_ids = relu_ids[-1] + 1 + np.arange((oh // 2) * (ow // 2) * oc * 16, dtype=np.uint32)
     ctx = ctx_factory(int(pool_ids[-1]) + 1)
+    ctx.set_option(1, int(fold))
     bits = ((img[..., None] >> np.arange(8)) & 1).astype(np.uint8)
     in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, 8)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(5), in_ids.ravel())
@@ -91,9 +93,22 @@ def conv_layer(ctx_factory):
     t2 = time.perf_counter()
     g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
     t3 = time.perf_counter()
+    # all 13x13x8 outputs against plain integer arithmetic
+    dec = ctx.decrypt(pool_ids.reshape(-1, 16)).astype(np.int64)
+    got = (dec << np.arange(16)).sum(axis=1)
+    got = np.where(got >= 32768, got - 65536, got).reshape(oh // 2, ow // 2, oc)
+    conv = np.zeros((oh, ow, oc), np.int64)
+    for dy in range(k):
+        for dx in range(k):
+            conv += (img[dy:dy + oh, dx:dx + ow, None] >> -exp[None, None, :, dy, dx].astype(np.int64)) * sign[None, None, :, dy, dx]
+    conv = ((conv + 32768) % 65536) - 32768
+    act = np.maximum(conv, 0)[: oh // 2 * 2, : ow // 2 * 2]
+    want = np.maximum(np.maximum(act[0::2, 0::2], act[0::2, 1::2]), np.maximum(act[1::2, 0::2], act[1::2, 1::2]))
+    assert np.array_equal(got, want), "conv layer decrypts wrongly"
     ctx.close()
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
+            "constant_folding": bool(fold),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -182,7 +197,8 @@ def main():
         out["calibration_copy_bytes"] = int(src.numel() * 4)
         del src, dst
     if not args.no_conv_layer:
-        out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
+        out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
+        out["conv_layer_folded"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))

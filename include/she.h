@@ -129,6 +129,23 @@ int she_relu(she_ctx *ctx, const uint32_t *x_ids, uint32_t count, uint32_t bits,
 int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                 const uint32_t *out_ids, uint64_t *gates_out);
 
+/* Options.  SHE_OPT_FOLD_CONSTANTS (default 0): the layer operators stop spending a bootstrap on
+ * gates whose result is fixed by a trivial-constant or repeated operand (the zeros that a shift
+ * leaves on top of a term, the carry-in of the subtraction, the comparator's first stage): such a
+ * gate becomes a constant, its other operand, or that operand's complement, and complements are
+ * absorbed into the next gate's code or applied as a free word-wise negation (Section 3.2: what
+ * only re-wires ciphertexts costs no gate).  Results decrypt identically; gate counts drop. */
+enum { SHE_OPT_FOLD_CONSTANTS = 1 };
+int she_set_option(she_ctx *ctx, int option, int value);
+
+/* Host-only planning (no GPU, no context): number of bootstrapped gates and of circuit levels that
+ * she_shift_acc / she_relu / she_maxpool would evaluate for these shapes and weights, with or
+ * without constant folding.  gates / levels may be NULL.  Same argument checks as the operators. */
+int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                       uint32_t acc_bits, int fold, uint64_t *gates, uint32_t *levels);
+int she_plan_relu(uint32_t count, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels);
+int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels);
+
 /* ---- diagnostics and plumbing (not part of the paper's problem statement) ---- */
 
 /* Copies slot `id` to dst[0..n] (a_0..a_{n-1}, b) / overwrites it from src. */

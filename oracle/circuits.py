@@ -78,11 +78,24 @@ def from_bits(b: np.ndarray, signed: bool) -> np.ndarray:
 
 
 # ------------------------------------------------------------------ netlists
+# truth tables of the ten gate codes: bit (2*a + b) of the table is gate(a, b)
+_TABLE = {code: sum(plain_gate(code, a, b) << (2 * a + b) for a in (0, 1) for b in (0, 1)) for code in _PLAIN}
+_CODE_OF_TABLE = {tt: code for code, tt in _TABLE.items()}
+NEG = 1 << 31            # flag on a wire reference: "the complement of that wire"
+
+
 @dataclass
 class Netlist:
     """Gates over wire ids.  Wires 0..n_inputs-1 are the inputs, then ZERO and ONE
-    (trivial, noiseless ciphertexts of 0 and 1), then one new wire per gate."""
+    (trivial, noiseless ciphertexts of 0 and 1), then one new wire per gate.
+
+    With fold=True a gate whose value is fixed by constant or repeated operands costs
+    nothing: the builder returns ZERO/ONE, an operand, or an operand's complement (a wire id
+    with the NEG flag: complementing a ciphertext is a free negation of all its words), and a
+    complemented operand of a real gate is absorbed into the gate type (e.g. AND(not a, b) =
+    ANDNY(a, b)).  With fold=False every requested gate is emitted as it is."""
     n_inputs: int
+    fold: bool = False
     gtype: list = field(default_factory=list)
     in0: list = field(default_factory=list)
     in1: list = field(default_factory=list)
@@ -97,11 +110,42 @@ class Netlist:
     def n_wires(self) -> int:
         return self._next
 
-    def gate(self, name: str, a: int, b: int) -> int:
+    def _emit(self, code: int, a: int, b: int) -> int:
         w = self._next
         self._next += 1
-        self.gtype.append(G[name]); self.in0.append(a); self.in1.append(b); self.out.append(w)
+        self.gtype.append(code); self.in0.append(a); self.in1.append(b); self.out.append(w)
         return w
+
+    def _resolve(self, ref: int):
+        """wire reference -> (wire or None, constant or None, complemented?)"""
+        neg, w = bool(ref & NEG), ref & ~NEG
+        if w == self.ZERO:
+            return None, int(neg), False
+        if w == self.ONE:
+            return None, 1 - int(neg), False
+        return w, None, neg
+
+    def gate(self, name: str, a: int, b: int) -> int:
+        code = G[name]
+        if not self.fold:
+            return self._emit(code, a, b)
+        wa, ca, na = self._resolve(a)
+        wb, cb, nb = self._resolve(b)
+        tt = _TABLE[code]
+        # value of the gate as a function of the underlying wires' values x (for a) and y (for b)
+        def f(x, y):
+            va = ca if wa is None else x ^ na
+            vb = cb if wb is None else y ^ nb
+            return (tt >> (2 * va + vb)) & 1
+        if wa is None or wb is None or wa == wb:
+            # at most one free variable v
+            var = wb if wa is None else wa
+            g0, g1 = (f(0, 0), f(1, 1)) if var is not None else (f(0, 0), f(0, 0))
+            if g0 == g1:
+                return self.ONE if g0 else self.ZERO
+            return var if (g0, g1) == (0, 1) else var | NEG
+        table = sum(f(x, y) << (2 * x + y) for x in (0, 1) for y in (0, 1))
+        return self._emit(_CODE_OF_TABLE[table], wa, wb)
 
     def mux(self, s: int, u: int, v: int) -> int:
         """s ? u : v as three 2-input gates"""
@@ -123,6 +167,12 @@ class Netlist:
             val[o] = plain_gate(t, int(val[a]), int(val[b]))
         return val
 
+    @staticmethod
+    def read_plain(val: np.ndarray, refs) -> np.ndarray:
+        """values of wire references (which may carry the NEG flag) in a run_plain() result"""
+        refs = np.asarray(refs, np.int64)
+        return (val[refs & ~NEG] ^ ((refs & NEG) != 0)).astype(np.uint8)
+
     # ---- evaluation on ciphertexts with the gate oracle
     def run_encrypted(self, K: tfhe.Keys, input_cts: np.ndarray, threads: int = 1) -> np.ndarray:
         n = K.params.n
@@ -139,6 +189,15 @@ class Netlist:
                 m = lev == d
                 tfhe.eval_gates(K, pool, t[m], a[m], b[m], o[m], threads)
         return pool
+
+    @staticmethod
+    def read_encrypted(pool: np.ndarray, refs) -> np.ndarray:
+        """ciphertexts of wire references: a complemented reference is the word-wise negation"""
+        refs = np.asarray(refs, np.int64).ravel()
+        cts = pool[refs & ~NEG].copy()
+        flip = (refs & NEG) != 0
+        cts[flip] = (0 - cts[flip].astype(np.int64)).astype(np.uint32)
+        return cts
 
 
 def add_unsigned(nl: Netlist, a: list, b: list, cap: int) -> list:
@@ -207,11 +266,11 @@ def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
     return list(x_bits[s:]) + [nl.ZERO] * min(s, w)
 
 
-def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int):
+def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False):
     """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits])."""
     w_sign = np.asarray(w_sign).reshape(units, terms)
     w_exp = np.asarray(w_exp).reshape(units, terms)
-    nl = Netlist(units * terms * in_bits)
+    nl = Netlist(units * terms * in_bits, fold)
     outs = []
     for u in range(units):
         pos, neg = [], []
@@ -228,9 +287,9 @@ def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bit
     return nl, outs
 
 
-def build_relu(count: int, bits: int):
+def build_relu(count: int, bits: int, fold: bool = False):
     """Each value: sign wire masks every lower bit; the result's sign is ZERO."""
-    nl = Netlist(count * bits)
+    nl = Netlist(count * bits, fold)
     outs = []
     for v in range(count):
         x = list(range(v * bits, (v + 1) * bits))
@@ -251,8 +310,8 @@ def max_signed(nl: Netlist, x: list, y: list) -> list:
     return [nl.mux(gt, x[i], y[i]) for i in range(w)]
 
 
-def build_maxpool(H: int, W: int, Cn: int, bits: int):
-    nl = Netlist(H * W * Cn * bits)
+def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False):
+    nl = Netlist(H * W * Cn * bits, fold)
 
     def px(h, w, c):
         base = ((h * W + w) * Cn + c) * bits

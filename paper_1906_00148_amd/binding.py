@@ -74,6 +74,12 @@ def load_library() -> C.CDLL:
         "she_shift_acc": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, u32p, u64p]),
         "she_relu": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
+        "she_set_option": (C.c_int, [ctx, C.c_int, C.c_int]),
+        "she_plan_shift_acc": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, C.c_int, u64p,
+                                         C.POINTER(C.c_uint32)]),
+        "she_plan_relu": (C.c_int, [C.c_uint32, C.c_uint32, C.c_int, u64p, C.POINTER(C.c_uint32)]),
+        "she_plan_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
+                                       C.POINTER(C.c_uint32)]),
         "she_read_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_write_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_export_keys": (C.c_int, [ctx, u8p, u8p, u32p, u32p]),
@@ -108,6 +114,33 @@ def _i8(a):
 
 def _p(a, ty):
     return a.ctypes.data_as(C.POINTER(ty))
+
+
+OPT_FOLD_CONSTANTS = 1
+
+
+def _plan(rc, gates, levels):
+    if rc:
+        raise SheError(rc, "planning call rejected its arguments")
+    return gates.value, levels.value
+
+
+def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False):
+    """(gates, levels) of she_shift_acc for these weights; runs on the host, no GPU needed."""
+    w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
+    g, lv = C.c_uint64(0), C.c_uint32(0)
+    return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
+                                                   acc_bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
+
+
+def plan_relu(count: int, bits: int, fold: bool = False):
+    g, lv = C.c_uint64(0), C.c_uint32(0)
+    return _plan(load_library().she_plan_relu(count, bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
+
+
+def plan_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False):
+    g, lv = C.c_uint64(0), C.c_uint32(0)
+    return _plan(load_library().she_plan_maxpool(H, W, Cn, bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
 
 
 class Context:
@@ -154,6 +187,9 @@ class Context:
 
     def __exit__(self, *exc):
         self.close()
+
+    def set_option(self, option: int, value: int):
+        self._check(self._L.she_set_option(self._h, option, value))
 
     def set_stream(self, hip_stream: int):
         self._check(self._L.she_set_stream(self._h, C.c_void_p(hip_stream)))

@@ -44,6 +44,7 @@ struct she_ctx {
     size_t d_stage_words = 0;
     unsigned *d_round_err = nullptr;
     bool track_round = false;
+    bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
     bool timing = true;                  // record HIP events around every kernel
     LevelTimer timer;                    // events not yet folded into last_ms
     size_t timer_levels = 0;
@@ -183,6 +184,7 @@ bool params_supported(const she_params &P, std::string &why)
 int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires, const uint32_t *out_ids,
                 uint64_t *gates_out)
 {
+    if (nl.overflow) return fail(c, SHE_ERANGE, "netlist too large for 31-bit wire ids");
     const std::vector<size_t> bounds = nl.levelize();
     nl.bind_outputs(out_wires, out_ids);
     const size_t G = nl.type.size();
@@ -412,6 +414,72 @@ int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_i
     return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates);
 }
 
+// ---- netlist construction shared by the operators and the planning calls ----
+static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids, uint32_t units, uint32_t terms,
+                                             uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                                             uint32_t acc_bits)
+{
+    std::vector<uint32_t> wires;
+    wires.reserve((size_t)units * acc_bits);
+    for (uint32_t u = 0; u < units; u++) {
+        std::vector<std::vector<uint32_t>> pos, neg;
+        for (uint32_t t = 0; t < terms; t++) {
+            const size_t k = (size_t)u * terms + t;
+            const uint32_t drop = (uint32_t)(-(int)w_exp[k]);
+            // x >> drop: the low `drop` wires fall away, trivial zeros refill the top
+            std::vector<uint32_t> term(x_ids + k * in_bits + drop, x_ids + (k + 1) * in_bits);
+            term.resize(in_bits, nl.zero());
+            (w_sign[k] > 0 ? pos : neg).push_back(std::move(term));
+        }
+        const bool has_neg = !neg.empty();
+        std::vector<uint32_t> total = nl_tree(nl, std::move(pos), in_bits, acc_bits);
+        if (has_neg) total = nl_sub(nl, total, nl_tree(nl, std::move(neg), in_bits, acc_bits));
+        wires.insert(wires.end(), total.begin(), total.end());
+    }
+    return wires;
+}
+
+static std::vector<uint32_t> wires_relu(Netlist &nl, const uint32_t *x_ids, uint32_t count, uint32_t bits)
+{
+    std::vector<uint32_t> wires;
+    wires.reserve((size_t)count * bits);
+    for (uint32_t v = 0; v < count; v++) {
+        const uint32_t *x = x_ids + (size_t)v * bits;
+        for (uint32_t i = 0; i + 1 < bits; i++) wires.push_back(nl.gate(SHE_ANDNY, x[bits - 1], x[i]));
+        wires.push_back(nl.zero());
+    }
+    return wires;
+}
+
+static std::vector<uint32_t> wires_maxpool(Netlist &nl, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C,
+                                           uint32_t bits)
+{
+    std::vector<uint32_t> wires;
+    wires.reserve((size_t)(H / 2) * (W / 2) * C * bits);
+    auto pixel = [&](uint32_t h, uint32_t w, uint32_t ch) {
+        const uint32_t *p = x_ids + (((size_t)h * W + w) * C + ch) * bits;
+        return std::vector<uint32_t>(p, p + bits);
+    };
+    for (uint32_t h = 0; h < H / 2; h++)
+        for (uint32_t w = 0; w < W / 2; w++)
+            for (uint32_t ch = 0; ch < C; ch++) {
+                const auto top = nl_max(nl, pixel(2 * h, 2 * w, ch), pixel(2 * h, 2 * w + 1, ch));
+                const auto bot = nl_max(nl, pixel(2 * h + 1, 2 * w, ch), pixel(2 * h + 1, 2 * w + 1, ch));
+                const auto best = nl_max(nl, top, bot);
+                wires.insert(wires.end(), best.begin(), best.end());
+            }
+    return wires;
+}
+
+static bool weights_ok(const int8_t *w_sign, const int8_t *w_exp, size_t count, uint32_t in_bits, const char **why)
+{
+    for (size_t k = 0; k < count; k++) {
+        if (w_sign[k] != 1 && w_sign[k] != -1) { *why = "w_sign must be +1 or -1"; return false; }
+        if (w_exp[k] > 0 || -(int)w_exp[k] >= (int)in_bits) { *why = "w_exp must be in [-(in_bits-1), 0]"; return false; }
+    }
+    return true;
+}
+
 int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
                   const int8_t *w_sign, const int8_t *w_exp, uint32_t acc_bits, const uint32_t *out_ids,
                   uint64_t *gates_out)
@@ -426,29 +494,11 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
     if ((rc = check_ids(c, x_ids, n_in, "she_shift_acc x_ids"))) return rc;
     if ((rc = check_ids(c, out_ids, n_out, "she_shift_acc out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
-    for (size_t k = 0; k < (size_t)units * terms; k++) {
-        if (w_sign[k] != 1 && w_sign[k] != -1) return fail(c, SHE_EINVAL, "w_sign must be +1 or -1");
-        if (w_exp[k] > 0 || -(int)w_exp[k] >= (int)in_bits) return fail(c, SHE_EINVAL, "w_exp must be in [-(in_bits-1), 0]");
-    }
+    const char *why = "";
+    if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return fail(c, SHE_EINVAL, why);
     try {
-        Netlist nl(c->cap);
-        std::vector<uint32_t> wires;
-        wires.reserve(n_out);
-        for (uint32_t u = 0; u < units; u++) {
-            std::vector<std::vector<uint32_t>> pos, neg;
-            for (uint32_t t = 0; t < terms; t++) {
-                const size_t k = (size_t)u * terms + t;
-                const uint32_t drop = (uint32_t)(-(int)w_exp[k]);
-                // x >> drop: the low `drop` wires fall away, trivial zeros refill the top
-                std::vector<uint32_t> term(x_ids + k * in_bits + drop, x_ids + (k + 1) * in_bits);
-                term.resize(in_bits, nl.zero());
-                (w_sign[k] > 0 ? pos : neg).push_back(std::move(term));
-            }
-            const bool has_neg = !neg.empty();
-            std::vector<uint32_t> total = nl_tree(nl, std::move(pos), in_bits, acc_bits);
-            if (has_neg) total = nl_sub(nl, total, nl_tree(nl, std::move(neg), in_bits, acc_bits));
-            wires.insert(wires.end(), total.begin(), total.end());
-        }
+        Netlist nl(c->cap, c->fold);
+        const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
@@ -469,14 +519,8 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap);
-        std::vector<uint32_t> wires;
-        wires.reserve(total);
-        for (uint32_t v = 0; v < count; v++) {
-            const uint32_t *x = x_ids + (size_t)v * bits;
-            for (uint32_t i = 0; i + 1 < bits; i++) wires.push_back(nl.gate(SHE_ANDNY, x[bits - 1], x[i]));
-            wires.push_back(nl.zero());
-        }
+        Netlist nl(c->cap, c->fold);
+        const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
@@ -498,24 +542,75 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap);
-        std::vector<uint32_t> wires;
-        wires.reserve(n_out);
-        auto pixel = [&](uint32_t h, uint32_t w, uint32_t ch) {
-            const uint32_t *p = x_ids + (((size_t)h * W + w) * C + ch) * bits;
-            return std::vector<uint32_t>(p, p + bits);
-        };
-        for (uint32_t h = 0; h < Ho; h++)
-            for (uint32_t w = 0; w < Wo; w++)
-                for (uint32_t ch = 0; ch < C; ch++) {
-                    const auto top = nl_max(nl, pixel(2 * h, 2 * w, ch), pixel(2 * h, 2 * w + 1, ch));
-                    const auto bot = nl_max(nl, pixel(2 * h + 1, 2 * w, ch), pixel(2 * h + 1, 2 * w + 1, ch));
-                    const auto best = nl_max(nl, top, bot);
-                    wires.insert(wires.end(), best.begin(), best.end());
-                }
+        Netlist nl(c->cap, c->fold);
+        const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
+int she_set_option(she_ctx *c, int option, int value)
+{
+    if (!c) return SHE_EINVAL;
+    if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
+    return fail(c, SHE_EINVAL, "unknown option");
+}
+
+// ---- planning: the operators' netlists without a GPU (inputs are wires 0, 1, 2, ... in argument order) ----
+static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels)
+{
+    if (nl.overflow) return SHE_ERANGE;
+    if (gates) *gates = nl.type.size();
+    if (levels) *levels = (uint32_t)(nl.levelize().size() - 1);
+    return SHE_OK;
+}
+
+int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                       uint32_t acc_bits, int fold, uint64_t *gates, uint32_t *levels)
+{
+    if (in_bits < 1 || in_bits > acc_bits || acc_bits > 32) return SHE_EINVAL;
+    const size_t n_in = (size_t)units * terms * in_bits;
+    if (n_in > 0x40000000u || (terms && units && (!w_sign || !w_exp))) return SHE_EINVAL;
+    const char *why = "";
+    if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return SHE_EINVAL;
+    try {
+        std::vector<uint32_t> ids(n_in);
+        for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), fold != 0);
+        wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
+        return plan_finish(nl, gates, levels);
+    } catch (const std::bad_alloc &) {
+        return SHE_ENOMEM;
+    }
+}
+
+int she_plan_relu(uint32_t count, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels)
+{
+    if (bits < 2 || bits > 64 || (size_t)count * bits > 0x40000000u) return SHE_EINVAL;
+    try {
+        std::vector<uint32_t> ids((size_t)count * bits);
+        for (size_t k = 0; k < ids.size(); k++) ids[k] = (uint32_t)k;
+        Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), fold != 0);
+        wires_relu(nl, ids.data(), count, bits);
+        return plan_finish(nl, gates, levels);
+    } catch (const std::bad_alloc &) {
+        return SHE_ENOMEM;
+    }
+}
+
+int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels)
+{
+    const size_t n_in = (size_t)H * W * C * bits;
+    if (bits < 2 || bits > 64 || n_in > 0x40000000u) return SHE_EINVAL;
+    try {
+        std::vector<uint32_t> ids(n_in);
+        for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), fold != 0);
+        wires_maxpool(nl, ids.data(), H, W, C, bits);
+        return plan_finish(nl, gates, levels);
+    } catch (const std::bad_alloc &) {
+        return SHE_ENOMEM;
     }
 }
 

@@ -8,14 +8,67 @@
 
 namespace she {
 
+namespace {
+
+// truth table of a gate code: bit (2a + b) = gate(a, b)
+constexpr uint8_t kTruth[SHE_NUM_GATES] = {
+    /* NAND  */ 0x7, /* AND   */ 0x8, /* OR    */ 0xE, /* XOR   */ 0x6, /* XNOR  */ 0x9,
+    /* NOR   */ 0x1, /* ANDNY */ 0x2, /* ANDYN */ 0x4, /* ORNY  */ 0xB, /* ORYN  */ 0xD};
+
+int code_of_truth(uint8_t table)
+{
+    for (int c = 0; c < SHE_NUM_GATES; c++)
+        if (kTruth[c] == table) return c;
+    return -1;      // constant or single-operand function: never reached for two free operands
+}
+
+struct Operand {     // a wire reference taken apart
+    bool is_const;
+    uint32_t value;  // constant value, or the plain wire id
+    uint32_t flip;   // 1 if the reference is complemented
+};
+
+}  // namespace
+
 uint32_t Netlist::gate(int code, uint32_t a, uint32_t b)
 {
-    const uint32_t w = next_temp++;
-    type.push_back((uint8_t)code);
-    in0.push_back(a);
-    in1.push_back(b);
-    out.push_back(w);
-    return w;
+    auto emit = [&](int c, uint32_t x, uint32_t y) {
+        if (next_temp >= WIRE_NEG - 1) { overflow = true; return zero(); }
+        const uint32_t w = next_temp++;
+        type.push_back((uint8_t)c);
+        in0.push_back(x);
+        in1.push_back(y);
+        out.push_back(w);
+        return w;
+    };
+    if (!fold) return emit(code, a, b);
+
+    auto take = [&](uint32_t ref) {
+        const uint32_t w = ref & ~WIRE_NEG, f = ref >> 31;
+        if (w == zero()) return Operand{true, f, 0};
+        if (w == one()) return Operand{true, 1u - f, 0};
+        return Operand{false, w, f};
+    };
+    const Operand A = take(a), B = take(b);
+    const uint8_t tt = kTruth[code];
+    // the gate as a function of the plain wires' values x (under a) and y (under b)
+    auto eval = [&](uint32_t x, uint32_t y) -> uint32_t {
+        const uint32_t va = A.is_const ? A.value : x ^ A.flip;
+        const uint32_t vb = B.is_const ? B.value : y ^ B.flip;
+        return (tt >> (2 * va + vb)) & 1u;
+    };
+    if (A.is_const || B.is_const || A.value == B.value) {
+        // zero or one free variable: constant, that wire, or its complement
+        const bool none = A.is_const && B.is_const;
+        const uint32_t at0 = eval(0, 0), at1 = none ? at0 : eval(1, 1);
+        if (at0 == at1) return at0 ? one() : zero();
+        const uint32_t wire = A.is_const ? B.value : A.value;
+        return at0 == 0 ? wire : (wire | WIRE_NEG);
+    }
+    uint8_t table = 0;
+    for (uint32_t x = 0; x < 2; x++)
+        for (uint32_t y = 0; y < 2; y++) table |= (uint8_t)(eval(x, y) << (2 * x + y));
+    return emit(code_of_truth(table), A.value, B.value);
 }
 
 // s ? u : v with three 2-input gates
@@ -32,15 +85,16 @@ void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *d
     std::vector<uint32_t> rename(next_temp - first_temp, unbound);     // temporary wire -> caller id
     for (size_t k = 0; k < wires.size(); k++) {
         const uint32_t w = wires[k];
-        if (w >= first_temp && rename[w - first_temp] == unbound) {
+        if (!(w & WIRE_NEG) && w >= first_temp && rename[w - first_temp] == unbound) {
             rename[w - first_temp] = dst[k];
-        } else {                                          // input, constant, or a wire already bound
+        } else {                     // input, constant, complemented wire, or a wire already bound
             copy_src.push_back(w);
             copy_dst.push_back(dst[k]);
         }
     }
-    auto fix = [&](uint32_t &w) {
-        if (w >= first_temp && rename[w - first_temp] != unbound) w = rename[w - first_temp];
+    auto fix = [&](uint32_t &ref) {
+        const uint32_t w = ref & ~WIRE_NEG;
+        if (w >= first_temp && rename[w - first_temp] != unbound) ref = rename[w - first_temp] | (ref & WIRE_NEG);
     };
     for (size_t g = 0; g < type.size(); g++) { fix(in0[g]); fix(in1[g]); fix(out[g]); }
     for (auto &w : copy_src) fix(w);

@@ -76,15 +76,24 @@ void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, co
                     uint8_t *bits);
 
 // ---- netlists of the layer operators (she_circuits.cpp) ----
+constexpr uint32_t WIRE_NEG = 0x80000000u;   // flag on a wire reference: the complement of that wire
+
 struct Netlist {
-    // wire ids: [0, cap) pool slots, cap = trivial 0, cap+1 = trivial 1, cap+2.. temporaries
+    // wire ids: [0, cap) pool slots, cap = trivial 0, cap+1 = trivial 1, cap+2.. temporaries.
+    // With `fold` set, a gate fixed by constant or repeated operands is not emitted: gate()
+    // returns a constant, an operand, or an operand with WIRE_NEG (complementing a ciphertext
+    // is a free negation of its words), and complemented operands of a real gate are absorbed
+    // into the gate code.
     uint32_t cap = 0;
     uint32_t next_temp = 0;
+    bool fold = false;
+    bool overflow = false;                      // more wires than 31-bit ids can name
     std::vector<uint8_t> type;
     std::vector<uint32_t> in0, in1, out;
-    std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates
+    std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates; copy_src may carry WIRE_NEG
 
-    explicit Netlist(uint32_t capacity) : cap(capacity), next_temp(capacity + 2) {}
+    explicit Netlist(uint32_t capacity, bool fold_constants = false)
+        : cap(capacity), next_temp(capacity + 2), fold(fold_constants) {}
     uint32_t zero() const { return cap; }
     uint32_t one() const { return cap + 1; }
     uint32_t gate(int code, uint32_t a, uint32_t b);

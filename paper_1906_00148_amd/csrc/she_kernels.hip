@@ -378,12 +378,15 @@ __global__ void k_gather(CtSpace cs, uint32_t *__restrict__ dst, const uint32_t 
     uint32_t *d = dst + (size_t)blockIdx.x * (n + 1);
     for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) d[i] = s[i];
 }
+// dst <- src, or its complement (word-wise negation) when the source id carries WIRE_NEG
 __global__ void k_copy_ct(CtSpace cs, const uint32_t *__restrict__ src_ids, const uint32_t *__restrict__ dst_ids,
                           uint32_t n)
 {
-    const uint32_t *s = ct_ptr(cs, src_ids[blockIdx.x]);
+    const uint32_t ref = src_ids[blockIdx.x];
+    const bool neg = (ref & WIRE_NEG) != 0;
+    const uint32_t *s = ct_ptr(cs, ref & ~WIRE_NEG);
     uint32_t *d = ct_ptr(cs, dst_ids[blockIdx.x]);
-    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) d[i] = s[i];
+    for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) d[i] = neg ? 0u - s[i] : s[i];
 }
 
 // ------------------------------------------------------------------------------------------

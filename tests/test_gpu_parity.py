@@ -258,3 +258,37 @@ def test_ring_degree_512(toy_keys):
         pool[:48] = O.encrypt_bits(K, bits, 11)
         O.eval_gates(K, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
         assert np.array_equal(ctx.read_cts(out_ids), pool[48:])
+
+
+# ------------------------------------------------------------------ constant folding, ciphertext level
+def test_folded_operators_match_folded_oracle_netlists_toy(toy_ctx, toy_keys):
+    pkg = she()
+    toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 1)
+    try:
+        x = np.array([[5, 7, 2, 6, 1], [3, 3, 0, 7, 4]])
+        sign = np.array([[1, -1, 1, 1, -1], [1, 1, 1, 1, 1]], np.int8)
+        exp = np.array([[0, -1, 0, -2, 0], [0, 0, -1, -2, -2]], np.int8)
+        in_bits, acc_bits = 3, 6
+        ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 51, 0)
+        out_ids = np.arange(1000, 1000 + 2 * acc_bits, dtype=np.uint32).reshape(2, acc_bits)
+        gates = toy_ctx.shift_acc(ids.reshape(2, 5, in_bits), sign, exp, acc_bits, out_ids)
+        nl, outs = OC.build_shift_acc(2, 5, in_bits, sign, exp, acc_bits, fold=True)
+        full, _ = OC.build_shift_acc(2, 5, in_bits, sign, exp, acc_bits, fold=False)
+        assert gates == len(nl.gtype) < len(full.gtype)
+        pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+        want = OC.Netlist.read_encrypted(pool, np.array(outs))
+        assert np.array_equal(toy_ctx.read_cts(out_ids), want)          # includes complemented and constant outputs
+        dec = OC.from_bits(toy_ctx.decrypt(out_ids), True)
+        assert np.array_equal(dec, OC.plain_shift_acc(x, sign, exp, acc_bits))
+        # max pooling of 4-bit values
+        vals = np.array([[[-3], [2]], [[1], [-4]]])
+        ids, fresh = _encrypt_values(toy_ctx, toy_keys, vals, 4, 53, 0)
+        pool_ids = np.arange(3000, 3004, dtype=np.uint32)
+        g2 = toy_ctx.maxpool(ids.reshape(2, 2, 1, 4), pool_ids.reshape(1, 1, 1, 4))
+        nl2, outs2 = OC.build_maxpool(2, 2, 1, 4, fold=True)
+        assert g2 == len(nl2.gtype) == 3 * (7 * 4 - 2)
+        pool2 = nl2.run_encrypted(toy_keys, fresh, threads=8)
+        assert np.array_equal(toy_ctx.read_cts(pool_ids), OC.Netlist.read_encrypted(pool2, np.array(outs2)))
+        assert int(OC.from_bits(toy_ctx.decrypt(pool_ids), True)) == 2
+    finally:
+        toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)

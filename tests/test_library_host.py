@@ -70,3 +70,37 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".cpp", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f
+
+
+def test_planning_calls_match_the_oracle_netlists():
+    """Host logic of the library (netlist builders, folding, levelizer) against the oracle's
+    independent builders: gate and level counts for random shapes, both folding modes."""
+    import numpy as np
+
+    import paper_1906_00148_amd as she
+    from oracle import circuits as OC
+    rng = np.random.default_rng(3)
+    for _ in range(25):
+        units, terms = int(rng.integers(1, 4)), int(rng.integers(0, 12))
+        in_bits = int(rng.integers(1, 9))
+        acc = int(rng.integers(in_bits, min(in_bits + 9, 32) + 1))
+        sign = rng.choice(np.array([-1, 1], np.int8), (units, terms))
+        exp = (-rng.integers(0, in_bits, (units, terms))).astype(np.int8)
+        for fold in (False, True):
+            nl, _ = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold)
+            want = (len(nl.gtype), int(nl.levels().max(initial=0)))
+            assert she.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold) == want, (units, terms, in_bits, acc, fold)
+    for fold in (False, True):
+        nl, _ = OC.build_relu(7, 16, fold=fold)
+        assert she.plan_relu(7, 16, fold) == (len(nl.gtype), 1)
+        nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold)
+        assert she.plan_maxpool(5, 4, 3, 6, fold) == (len(nl.gtype), int(nl.levels().max()))
+    # the benchmark's conv layer: 26x26 pixels x 8 channels of 9-term neurons
+    import synth_inputs as S
+    _, sign, exp = S.cfg5_conv_layer()
+    per_pixel = [she.plan_shift_acc(8, 9, 8, sign.reshape(8, 9), exp.reshape(8, 9), 16, f)[0] for f in (False, True)]
+    assert per_pixel[0] * 676 == 1925248 and per_pixel[1] < 0.6 * per_pixel[0]
+    with pytest.raises(she.SheError):
+        she.plan_shift_acc(1, 2, 8, [[1, 2]], [[0, 0]], 16)                      # bad sign
+    with pytest.raises(she.SheError):
+        she.plan_shift_acc(1, 1, 8, [[1]], [[-8]], 16)                           # shift out of range

@@ -164,3 +164,57 @@ def test_small_circuits_on_ciphertexts(toy_keys):
         cts = tfhe.encrypt_bits(K, np.concatenate([C.to_bits(np.array(a), 3), C.to_bits(np.array(b), 3)]), 5)
         pool = nl.run_encrypted(K, cts, threads=8)
         assert int(C.from_bits(tfhe.decrypt_bits(K, pool[out]), True)) == max(a, b)
+
+
+# ------------------------------------------------------------------ constant folding
+def test_folding_rules_against_truth_tables():
+    # every gate code, every way an operand can be a constant, a complement or the other operand
+    for name in tfhe.GATES:
+        nl = C.Netlist(2, fold=True)
+        refs = {"x": 0, "nx": 0 | C.NEG, "y": 1, "ny": 1 | C.NEG, "0": nl.ZERO, "1": nl.ONE,
+                "n0": nl.ZERO | C.NEG, "n1": nl.ONE | C.NEG}
+
+        def value(tag, x, y):
+            return {"x": x, "nx": 1 - x, "y": y, "ny": 1 - y, "0": 0, "1": 1, "n0": 1, "n1": 0}[tag]
+        for ta, ra in refs.items():
+            for tb, rb in refs.items():
+                before = len(nl.gtype)
+                out = nl.gate(name, ra, rb)
+                free = {t[-1] for t in (ta, tb) if t[-1] in "xy"}
+                assert (len(nl.gtype) > before) == (len(free) == 2), (name, ta, tb)
+                for x in (0, 1):
+                    for y in (0, 1):
+                        val = nl.run_plain([x, y])
+                        got = int(C.Netlist.read_plain(val, [out])[0])
+                        assert got == C.plain_gate(tfhe.GATES[name], value(ta, x, y), value(tb, x, y)), (name, ta, tb)
+
+
+def test_folded_netlists_equal_integer_arithmetic():
+    rng = np.random.default_rng(5)
+    for _ in range(60):
+        terms, in_bits = int(rng.integers(1, 8)), int(rng.integers(2, 5))
+        acc = int(rng.integers(in_bits, in_bits + 4))
+        x = rng.integers(0, 1 << in_bits, (2, terms))
+        sign = rng.choice([-1, 1], (2, terms))
+        exp = -rng.integers(0, in_bits, (2, terms))
+        nl, outs = C.build_shift_acc(2, terms, in_bits, sign, exp, acc, fold=True)
+        plain, _ = C.build_shift_acc(2, terms, in_bits, sign, exp, acc, fold=False)
+        assert len(nl.gtype) <= len(plain.gtype)
+        got = C.from_bits(C.Netlist.read_plain(nl.run_plain(C.to_bits(x, in_bits)), np.array(outs)), True)
+        assert np.array_equal(got, C.plain_shift_acc(x, sign, exp, acc))
+    vals = rng.integers(-128, 128, (4, 4, 2))
+    nl, outs = C.build_maxpool(4, 4, 2, 8, fold=True)
+    got = C.from_bits(C.Netlist.read_plain(nl.run_plain(C.to_bits(vals, 8)), np.array(outs)), True).reshape(2, 2, 2)
+    assert np.array_equal(got, C.plain_maxpool2x2(vals))
+    assert len(nl.gtype) == 2 * 2 * 2 * 3 * (7 * 8 - 2)            # the comparator's first MUX collapses to one gate
+    nl, outs = C.build_relu(5, 8, fold=True)
+    assert len(nl.gtype) == 5 * 7
+
+
+def test_folding_gate_counts_of_the_benchmark_shapes():
+    import synth_inputs as S
+    _, sign, exp = S.cfg3_neuron()
+    full, _ = C.build_shift_acc(1, 576, 8, sign, exp, 16, fold=False)
+    lean, _ = C.build_shift_acc(1, 576, 8, sign, exp, 16, fold=True)
+    assert (len(full.gtype), len(lean.gtype)) == (24144, 16889)
+    assert int(full.levels().max()) == int(lean.levels().max()) == 48
