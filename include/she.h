@@ -135,16 +135,28 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
  * gate becomes a constant, its other operand, or that operand's complement, and complements are
  * absorbed into the next gate's code or applied as a free word-wise negation (Section 3.2: what
  * only re-wires ciphertexts costs no gate).  Results decrypt identically; gate counts drop. */
-enum { SHE_OPT_FOLD_CONSTANTS = 1 };
+enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2 };
 int she_set_option(she_ctx *ctx, int option, int value);
+/* SHE_OPT_NATIVE_MUX (default 0): she_maxpool evaluates every MUX of its comparators and selectors
+ * with she_eval_mux's three-input gate instead of three 2-input gates (7w gates per max become
+ * w gates + 2w MUX entries = 5w blind rotations and 3w key switches, and half the levels). */
 
-/* Host-only planning (no GPU, no context): number of bootstrapped gates and of circuit levels that
- * she_shift_acc / she_relu / she_maxpool would evaluate for these shapes and weights, with or
- * without constant folding.  gates / levels may be NULL.  Same argument checks as the operators. */
+/* Section 3.1 (MUX is named among the homomorphic gates).  One level of nmux independent native
+ * MUX gates: slot out[m] <- slot sel[m] ? slot in1[m] : slot in0[m].  Each is two blind rotations
+ * (of sel AND in1 and of (NOT sel) AND in0), whose extracted samples are added with 1/8 on the body,
+ * and ONE key switch.  Same id rules and error codes as she_eval_gates. */
+int she_eval_mux(she_ctx *ctx, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
+                 size_t nmux);
+
+/* Host-only planning (no GPU, no context): what she_shift_acc / she_relu / she_maxpool would evaluate
+ * for these shapes and weights under `options` (bitwise OR of SHE_OPT_* values): number of netlist
+ * entries (gates + MUX entries), of circuit levels, and of blind rotations (one per gate, two per
+ * MUX entry).  Any output pointer may be NULL.  Same argument checks as the operators. */
 int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
-                       uint32_t acc_bits, int fold, uint64_t *gates, uint32_t *levels);
-int she_plan_relu(uint32_t count, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels);
-int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels);
+                       uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
+int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
+int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
+                     uint64_t *rotations);
 
 /* ---- diagnostics and plumbing (not part of the paper's problem statement) ---- */
 

@@ -96,9 +96,11 @@ class Netlist:
     ANDNY(a, b)).  With fold=False every requested gate is emitted as it is."""
     n_inputs: int
     fold: bool = False
+    native_mux: bool = False     # mux() emits one three-input MUX entry (two blind rotations, one key switch)
     gtype: list = field(default_factory=list)
     in0: list = field(default_factory=list)
     in1: list = field(default_factory=list)
+    in2: list = field(default_factory=list)      # third operand of MUX entries, 0 otherwise
     out: list = field(default_factory=list)
 
     def __post_init__(self):
@@ -110,11 +112,16 @@ class Netlist:
     def n_wires(self) -> int:
         return self._next
 
-    def _emit(self, code: int, a: int, b: int) -> int:
+    def _emit(self, code: int, a: int, b: int, c: int = 0) -> int:
         w = self._next
         self._next += 1
-        self.gtype.append(code); self.in0.append(a); self.in1.append(b); self.out.append(w)
+        self.gtype.append(code); self.in0.append(a); self.in1.append(b); self.in2.append(c); self.out.append(w)
         return w
+
+    @property
+    def rotations(self) -> int:
+        """blind rotations = two-input gates + 2 per native MUX"""
+        return sum(2 if t >= tfhe.MUX_BASE else 1 for t in self.gtype)
 
     def _resolve(self, ref: int):
         """wire reference -> (wire or None, constant or None, complemented?)"""
@@ -148,14 +155,42 @@ class Netlist:
         return self._emit(_CODE_OF_TABLE[table], wa, wb)
 
     def mux(self, s: int, u: int, v: int) -> int:
-        """s ? u : v as three 2-input gates"""
-        return self.gate("OR", self.gate("AND", s, u), self.gate("ANDNY", s, v))
+        """s ? u : v.  Three 2-input gates, or with native_mux one MUX entry whose two blind
+        rotations bootstrap code1(s, u) and code0(s, v) (AND / ANDNY for plain operands)."""
+        if not self.native_mux:
+            return self.gate("OR", self.gate("AND", s, u), self.gate("ANDNY", s, v))
+        if not self.fold:
+            return self._emit(tfhe.MUX_BASE + 16 * G["AND"] + G["ANDNY"], s, u, v)
+        ws, cs, ns = self._resolve(s)
+        if ws is None:                                   # constant selector
+            return u if cs else v
+        if ns:                                           # complemented selector: swap the branches
+            u, v = v, u
+        wu, cu, nu = self._resolve(u)
+        wv, cv, nv = self._resolve(v)
+        if wu == ws and wu is not None:                  # branch taken when s = 1 is s itself (or its complement)
+            cu, wu = 1 - int(nu), None
+        if wv == ws and wv is not None:                  # branch taken when s = 0
+            cv, wv = int(nv), None
+        if wu is None and wv is None:
+            if cu == cv:
+                return self.ONE if cu else self.ZERO
+            return ws if cu else ws | NEG
+        if wu is None:                                   # s ? const : v
+            return self.gate("OR" if cu else "ANDNY", ws, v)
+        if wv is None:                                   # s ? u : const
+            return self.gate("ORNY" if cv else "AND", ws, u)
+        if wu == wv:
+            return u if nu == nv else self.gate("XNOR" if not nu else "XOR", ws, wu)
+        code1 = G["ANDYN"] if nu else G["AND"]           # s and (not) u
+        code0 = G["NOR"] if nv else G["ANDNY"]           # (not s) and (not) v
+        return self._emit(tfhe.MUX_BASE + 16 * code1 + code0, ws, wu, wv)
 
     # ---- depth of each gate when every gate is scheduled as early as possible
     def levels(self) -> np.ndarray:
         lev = np.zeros(self.n_wires, np.int64)
-        for a, b, o in zip(self.in0, self.in1, self.out):
-            lev[o] = 1 + max(lev[a], lev[b])
+        for t, a, b, c, o in zip(self.gtype, self.in0, self.in1, self.in2, self.out):
+            lev[o] = 1 + max(lev[a], lev[b], lev[c] if t >= tfhe.MUX_BASE else 0)
         return lev[np.asarray(self.out, np.int64)] if self.out else np.zeros(0, np.int64)
 
     # ---- evaluation on plaintext bits
@@ -163,8 +198,12 @@ class Netlist:
         val = np.zeros(self.n_wires, np.uint8)
         val[: self.n_inputs] = np.asarray(input_bits, np.uint8).ravel()
         val[self.ONE] = 1
-        for t, a, b, o in zip(self.gtype, self.in0, self.in1, self.out):
-            val[o] = plain_gate(t, int(val[a]), int(val[b]))
+        for t, a, b, c, o in zip(self.gtype, self.in0, self.in1, self.in2, self.out):
+            if t < tfhe.MUX_BASE:
+                val[o] = plain_gate(t, int(val[a]), int(val[b]))
+            else:                                        # at most one of the two rotations gives 1
+                m = t - tfhe.MUX_BASE
+                val[o] = plain_gate(m >> 4, int(val[a]), int(val[b])) | plain_gate(m & 15, int(val[a]), int(val[c]))
         return val
 
     @staticmethod
@@ -181,13 +220,13 @@ class Netlist:
         pool[self.ZERO, n] = (-(1 << 29)) & 0xFFFFFFFF
         pool[self.ONE, n] = 1 << 29
         if threads <= 1:
-            tfhe.eval_gates(K, pool, self.gtype, self.in0, self.in1, self.out, 1)
+            tfhe.eval_netlist(K, pool, self.gtype, self.in0, self.in1, self.in2, self.out, 1)
         else:
             lev = self.levels()
-            t, a, b, o = (np.asarray(v) for v in (self.gtype, self.in0, self.in1, self.out))
+            t, a, b, c, o = (np.asarray(v) for v in (self.gtype, self.in0, self.in1, self.in2, self.out))
             for d in range(1, int(lev.max(initial=0)) + 1):
                 m = lev == d
-                tfhe.eval_gates(K, pool, t[m], a[m], b[m], o[m], threads)
+                tfhe.eval_netlist(K, pool, t[m], a[m], b[m], c[m], o[m], threads)
         return pool
 
     @staticmethod
@@ -310,8 +349,8 @@ def max_signed(nl: Netlist, x: list, y: list) -> list:
     return [nl.mux(gt, x[i], y[i]) for i in range(w)]
 
 
-def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False):
-    nl = Netlist(H * W * Cn * bits, fold)
+def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False):
+    nl = Netlist(H * W * Cn * bits, fold, native_mux)
 
     def px(h, w, c):
         base = ((h * W + w) * Cn + c) * bits

@@ -114,6 +114,10 @@ def lib() -> C.CDLL:
         L.orc_bootstrap.argtypes = [pp, u32p, u32p, u32p, u32p]
         L.orc_gate.restype = C.c_int
         L.orc_gate.argtypes = [pp, u32p, u32p, C.c_int, u32p, u32p, u32p]
+        L.orc_mux.restype = C.c_int
+        L.orc_mux.argtypes = [pp, u32p, u32p, C.c_int, C.c_int, u32p, u32p, u32p, u32p]
+        L.orc_eval_netlist.restype = C.c_int
+        L.orc_eval_netlist.argtypes = [pp, u32p, u32p, u32p, u32p, u32p, u32p, u32p, u32p, C.c_size_t, C.c_int]
         L.orc_eval_gates.restype = C.c_int
         L.orc_eval_gates.argtypes = [pp, u32p, u32p, u32p, u8p, u32p, u32p, u32p, C.c_size_t, C.c_int]
         _lib = L
@@ -301,3 +305,29 @@ def eval_gates(K: Keys, pool: np.ndarray, gtype, in0, in1, out, threads: int = 1
                               _p32(out), gtype.size, threads)
     if rc:
         raise ValueError("orc_eval_gates failed")
+
+
+MUX_BASE = len(GATES)        # netlist type of a native MUX: MUX_BASE + 16*code1 + code0
+
+
+def mux(K: Keys, sel, c1, c0, code1: int = GATES["AND"], code0: int = GATES["ANDNY"]) -> np.ndarray:
+    """Native three-input MUX sel ? c1 : c0 (two blind rotations, one key switch)."""
+    sel, c1, c0 = _u32(sel), _u32(c1), _u32(c0)
+    out = np.zeros_like(sel)
+    cp = K.params.c()
+    if lib().orc_mux(C.byref(cp), _p32(K.bk), _p32(K.ks), code1, code0, _p32(sel), _p32(c1), _p32(c0), _p32(out)):
+        raise ValueError("orc_mux failed")
+    return out
+
+
+def eval_netlist(K: Keys, pool: np.ndarray, gtype, in0, in1, in2, out, threads: int = 1) -> None:
+    """Like eval_gates, with native MUX entries (type >= MUX_BASE, operands in0 = selector, in1, in2)."""
+    assert pool.dtype == np.uint32 and pool.flags.c_contiguous and pool.shape[1] == K.params.n + 1
+    gtype, in0, in1, in2, out = (_u32(v) for v in (gtype, in0, in1, in2, out))
+    for a in (in0, in1, in2, out):
+        assert a.size == gtype.size and (a.size == 0 or int(a.max()) < pool.shape[0])
+    cp = K.params.c()
+    rc = lib().orc_eval_netlist(C.byref(cp), _p32(K.bk), _p32(K.ks), _p32(pool), _p32(gtype), _p32(in0), _p32(in1),
+                                _p32(in2), _p32(out), gtype.size, threads)
+    if rc:
+        raise ValueError("orc_eval_netlist failed")

@@ -390,9 +390,77 @@ int orc_gate(const orc_params *P, const uint32_t *bk, const uint32_t *ks, int ty
     return rc;
 }
 
+/* Blind rotation and extraction only: TLWE of dimension N under the ring key's coefficients. */
+static void bootstrap_wo_keyswitch(const orc_params *P, const uint32_t *bk, const uint32_t *in, uint32_t *ext /* [N+1] */)
+{
+    const uint32_t n = P->n, N = P->N;
+    uint32_t *abar = (uint32_t *)malloc(sizeof(uint32_t) * n);
+    uint32_t *acc = (uint32_t *)malloc(sizeof(uint32_t) * 2 * N);
+    for (uint32_t i = 0; i < n; i++) abar[i] = orc_modswitch(N, in[i]);
+    orc_blind_rotate(P, bk, abar, orc_modswitch(N, in[n]), 1u << 29, acc);
+    orc_sample_extract(N, acc, ext);
+    free(abar); free(acc);
+}
+
+/* Native three-input MUX (Section 3.1 names MUX among the gates): out = sel ? c1 : c0 as
+ * two blind rotations and ONE key switch.  The first rotation bootstraps code1(sel, c1), the
+ * second code0(sel, c0), where for plain operands code1 = AND and code0 = ANDNY (not sel and c0);
+ * a caller that wants a complemented operand passes the matching gate code instead (ANDYN, NOR,
+ * ...).  At most one of the two is +1/8, so their sum plus 1/8 is +-1/8; it is key-switched once. */
+int orc_mux(const orc_params *P, const uint32_t *bk, const uint32_t *ks, int code1, int code0, const uint32_t *sel,
+            const uint32_t *c1, const uint32_t *c0, uint32_t *out)
+{
+    if (!params_ok(P)) return -1;
+    const uint32_t n = P->n, N = P->N;
+    uint32_t *t = (uint32_t *)malloc(sizeof(uint32_t) * (n + 1));
+    uint32_t *e1 = (uint32_t *)malloc(sizeof(uint32_t) * (N + 1));
+    uint32_t *e0 = (uint32_t *)malloc(sizeof(uint32_t) * (N + 1));
+    int rc = orc_gate_lincomb(n, code1, sel, c1, t);
+    if (rc == 0) {
+        bootstrap_wo_keyswitch(P, bk, t, e1);
+        rc = orc_gate_lincomb(n, code0, sel, c0, t);
+    }
+    if (rc == 0) {
+        bootstrap_wo_keyswitch(P, bk, t, e0);
+        for (uint32_t j = 0; j <= N; j++) e1[j] += e0[j];
+        e1[N] += 1u << 29;
+        orc_key_switch(P, ks, e1, out);
+    }
+    free(t); free(e1); free(e0);
+    return rc;
+}
+
 /* A list of gates over a ciphertext pool pool[slot][n+1], evaluated in the
  * order given (so a netlist in topological order may be passed whole).  With
- * threads > 1 the gates must be mutually independent (one circuit level).    */
+ * threads > 1 the gates must be mutually independent (one circuit level).
+ * type[g] < ORC_NGATES: out = type(in0, in1).  type[g] = ORC_NGATES + 16*code1 + code0:
+ * native MUX with selector in0, operands in1 (taken when sel = 1) and in2.    */
+static int eval_one(const orc_params *P, const uint32_t *bk, const uint32_t *ks, uint32_t *pool, size_t w, uint32_t type,
+                    uint32_t a, uint32_t b, uint32_t c, uint32_t o)
+{
+    if (type < ORC_NGATES) return orc_gate(P, bk, ks, (int)type, pool + a * w, pool + b * w, pool + o * w);
+    const uint32_t m = type - ORC_NGATES;
+    return orc_mux(P, bk, ks, (int)(m >> 4), (int)(m & 15), pool + a * w, pool + b * w, pool + c * w, pool + o * w);
+}
+
+int orc_eval_netlist(const orc_params *P, const uint32_t *bk, const uint32_t *ks, uint32_t *pool, const uint32_t *type,
+                     const uint32_t *in0, const uint32_t *in1, const uint32_t *in2, const uint32_t *outid,
+                     size_t ngates, int threads)
+{
+    if (!params_ok(P)) return -1;
+    const size_t w = P->n + 1;
+    int bad = 0;
+    if (threads <= 1) {
+        for (size_t g = 0; g < ngates; g++)
+            if (eval_one(P, bk, ks, pool, w, type[g], in0[g], in1[g], in2[g], outid[g])) bad = 1;
+    } else {
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads)
+        for (size_t g = 0; g < ngates; g++)
+            if (eval_one(P, bk, ks, pool, w, type[g], in0[g], in1[g], in2[g], outid[g])) bad = 1;
+    }
+    return bad ? -1 : 0;
+}
+
 int orc_eval_gates(const orc_params *P, const uint32_t *bk, const uint32_t *ks, uint32_t *pool, const uint8_t *type,
                    const uint32_t *in0, const uint32_t *in1, const uint32_t *outid, size_t ngates, int threads)
 {

@@ -76,10 +76,11 @@ def load_library() -> C.CDLL:
         "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_set_option": (C.c_int, [ctx, C.c_int, C.c_int]),
         "she_plan_shift_acc": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, C.c_int, u64p,
-                                         C.POINTER(C.c_uint32)]),
-        "she_plan_relu": (C.c_int, [C.c_uint32, C.c_uint32, C.c_int, u64p, C.POINTER(C.c_uint32)]),
+                                         C.POINTER(C.c_uint32), u64p]),
+        "she_plan_relu": (C.c_int, [C.c_uint32, C.c_uint32, C.c_int, u64p, C.POINTER(C.c_uint32), u64p]),
         "she_plan_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
-                                       C.POINTER(C.c_uint32)]),
+                                       C.POINTER(C.c_uint32), u64p]),
+        "she_eval_mux": (C.c_int, [ctx, u32p, u32p, u32p, u32p, C.c_size_t]),
         "she_read_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_write_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_export_keys": (C.c_int, [ctx, u8p, u8p, u32p, u32p]),
@@ -117,6 +118,11 @@ def _p(a, ty):
 
 
 OPT_FOLD_CONSTANTS = 1
+OPT_NATIVE_MUX = 2
+
+
+def _options(fold: bool, native_mux: bool) -> int:
+    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0)
 
 
 def _plan(rc, gates, levels):
@@ -130,17 +136,21 @@ def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits
     w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
     g, lv = C.c_uint64(0), C.c_uint32(0)
     return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
-                                                   acc_bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
+                                                   acc_bits, _options(fold, False), C.byref(g), C.byref(lv), None), g, lv)
 
 
 def plan_relu(count: int, bits: int, fold: bool = False):
     g, lv = C.c_uint64(0), C.c_uint32(0)
-    return _plan(load_library().she_plan_relu(count, bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
+    return _plan(load_library().she_plan_relu(count, bits, _options(fold, False), C.byref(g), C.byref(lv), None), g, lv)
 
 
-def plan_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False):
-    g, lv = C.c_uint64(0), C.c_uint32(0)
-    return _plan(load_library().she_plan_maxpool(H, W, Cn, bits, int(fold), C.byref(g), C.byref(lv)), g, lv)
+def plan_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False,
+                 with_rotations: bool = False):
+    """(entries, levels) or, with_rotations, (entries, levels, blind rotations)."""
+    g, lv, rot = C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
+    rc = load_library().she_plan_maxpool(H, W, Cn, bits, _options(fold, native_mux), C.byref(g), C.byref(lv), C.byref(rot))
+    out = _plan(rc, g, lv)
+    return out + (rot.value,) if with_rotations else out
 
 
 class Context:
@@ -211,6 +221,12 @@ class Context:
         assert gtype.size == in0.size == in1.size == out.size
         self._check(self._L.she_eval_gates(self._h, _p(gtype, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
                                            _p(out, C.c_uint32), gtype.size))
+
+    def eval_mux(self, sel, in1, in0, out):
+        sel, in1, in0, out = (_u32(v).ravel() for v in (sel, in1, in0, out))
+        assert sel.size == in1.size == in0.size == out.size
+        self._check(self._L.she_eval_mux(self._h, _p(sel, C.c_uint32), _p(in1, C.c_uint32), _p(in0, C.c_uint32),
+                                         _p(out, C.c_uint32), sel.size))
 
     def shift_acc(self, x_ids, w_sign, w_exp, acc_bits: int, out_ids) -> int:
         x_ids = _u32(x_ids)

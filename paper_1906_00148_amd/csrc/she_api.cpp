@@ -45,6 +45,10 @@ struct she_ctx {
     unsigned *d_round_err = nullptr;
     bool track_round = false;
     bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
+    bool native_mux = false;             // SHE_OPT_NATIVE_MUX
+    uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
+    uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;
+    size_t d_mux_cap = 0;
     bool timing = true;                  // record HIP events around every kernel
     LevelTimer timer;                    // events not yet folded into last_ms
     size_t timer_levels = 0;
@@ -118,6 +122,32 @@ int ensure_gate_arrays(she_ctx *c, size_t gates)
     return SHE_OK;
 }
 
+int ensure_raw(she_ctx *c, size_t jobs)
+{
+    if (jobs <= c->work.raw_jobs) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->work.raw_ext) hipFree(c->work.raw_ext);
+    c->work.raw_ext = nullptr; c->work.raw_jobs = 0;
+    HIP_TRY(c, hipMalloc((void **)&c->work.raw_ext, jobs * (size_t)(c->P.N + 1) * sizeof(uint32_t)));
+    c->work.raw_jobs = jobs;
+    return SHE_OK;
+}
+
+int ensure_mux_arrays(she_ctx *c, size_t muxes)
+{
+    if (muxes <= c->d_mux_cap) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->d_mtype) { hipFree(c->d_mtype); hipFree(c->d_min0); hipFree(c->d_min1); hipFree(c->d_mout); }
+    c->d_mtype = nullptr; c->d_mux_cap = 0;
+    muxes += muxes / 4;
+    HIP_TRY(c, hipMalloc((void **)&c->d_mtype, 2 * muxes));
+    HIP_TRY(c, hipMalloc((void **)&c->d_min0, 2 * muxes * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->d_min1, 2 * muxes * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->d_mout, muxes * sizeof(uint32_t)));
+    c->d_mux_cap = muxes;
+    return SHE_OK;
+}
+
 int ensure_stage(she_ctx *c, size_t words)
 {
     if (words <= c->d_stage_words) return SHE_OK;
@@ -143,6 +173,29 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+    }
+    return SHE_OK;
+}
+
+// Enqueues one level of native MUX entries: jobs 2m and 2m+1 are the two rotations of entry m
+// (device arrays of 2*muxes jobs), d_out has one id per entry.
+int enqueue_mux_level(she_ctx *c, const uint8_t *d_jtype, const uint32_t *d_jin0, const uint32_t *d_jin1,
+                      const uint32_t *d_out, size_t muxes)
+{
+    const CtSpace cs = space(c);
+    LevelTimer *timer = c->timing ? &c->timer : nullptr;
+    const size_t step = MAX_LEVEL_CHUNK / 2;
+    for (size_t off = 0; off < muxes; off += step) {
+        const size_t cnt = std::min<size_t>(step, muxes - off);
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_lincomb(c->P, cs, d_jtype + 2 * off, d_jin0 + 2 * off, d_jin1 + 2 * off, 2 * cnt, c->work, c->stream));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, nullptr, 2 * cnt, c->work,
+                                       c->track_round ? c->d_round_err : nullptr, c->stream, true));
+        if (timer) HIP_TRY(c, timer->mark(c->stream));
+        HIP_TRY(c, launch_mux_combine(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
         HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
     }
@@ -180,21 +233,41 @@ bool params_supported(const she_params &P, std::string &why)
     return true;
 }
 
-// Runs a finished netlist: levelize, bind outputs, upload, one enqueue per level, copies, sync.
+// Runs a finished netlist: levelize, bind outputs, upload, per level one batch of gates and one of
+// MUX entries, copies, sync.
 int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires, const uint32_t *out_ids,
                 uint64_t *gates_out)
 {
     if (nl.overflow) return fail(c, SHE_ERANGE, "netlist too large for 31-bit wire ids");
-    const std::vector<size_t> bounds = nl.levelize();
+    std::vector<size_t> mux_start;
+    const std::vector<size_t> bounds = nl.levelize(&mux_start);
     nl.bind_outputs(out_wires, out_ids);
-    const size_t G = nl.type.size();
+    const size_t G = nl.type.size(), levels = bounds.size() - 1;
     if (gates_out) *gates_out = G;
     int rc = ensure_temp(c, (size_t)nl.next_temp - nl.cap);
     if (rc) return rc;
+    // MUX entries become two rotation jobs each, kept in level order in their own arrays
+    std::vector<uint8_t> jt;
+    std::vector<uint32_t> j0, j1, mo;
+    std::vector<size_t> mux_first(levels + 1, 0);          // index of each level's first entry in mo
     size_t widest = 0;
-    for (size_t lv = 0; lv + 1 < bounds.size(); lv++) widest = std::max(widest, bounds[lv + 1] - bounds[lv]);
+    for (size_t lv = 0; lv < levels; lv++) {
+        mux_first[lv] = mo.size();
+        for (size_t g = mux_start[lv]; g < bounds[lv + 1]; g++) {
+            const uint32_t m = nl.type[g] - MUX_BASE;
+            jt.push_back((uint8_t)(m >> 4)); j0.push_back(nl.in0[g]); j1.push_back(nl.in1[g]);
+            jt.push_back((uint8_t)(m & 15)); j0.push_back(nl.in0[g]); j1.push_back(nl.in2[g]);
+            mo.push_back(nl.out[g]);
+        }
+        widest = std::max(widest, std::max(mux_start[lv] - bounds[lv], 2 * (bounds[lv + 1] - mux_start[lv])));
+    }
+    mux_first[levels] = mo.size();
     if ((rc = ensure_work(c, std::min<size_t>(widest, MAX_LEVEL_CHUNK)))) return rc;
     if ((rc = ensure_gate_arrays(c, std::max(G, nl.copy_src.size())))) return rc;
+    if (!mo.empty()) {
+        if ((rc = ensure_mux_arrays(c, mo.size()))) return rc;
+        if ((rc = ensure_raw(c, std::min<size_t>(widest, MAX_LEVEL_CHUNK)))) return rc;
+    }
     c->timer.clear();
     c->timer_levels = 0;
     if (G) {
@@ -202,9 +275,21 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         HIP_TRY(c, hipMemcpyAsync(c->d_in0, nl.in0.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_in1, nl.in1.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_out, nl.out.data(), G * 4, hipMemcpyHostToDevice, c->stream));
-        for (size_t lv = 0; lv + 1 < bounds.size(); lv++) {
-            const size_t a = bounds[lv], b = bounds[lv + 1];
-            if ((rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, b - a))) return rc;
+        if (!mo.empty()) {
+            HIP_TRY(c, hipMemcpyAsync(c->d_mtype, jt.data(), jt.size(), hipMemcpyHostToDevice, c->stream));
+            HIP_TRY(c, hipMemcpyAsync(c->d_min0, j0.data(), j0.size() * 4, hipMemcpyHostToDevice, c->stream));
+            HIP_TRY(c, hipMemcpyAsync(c->d_min1, j1.data(), j1.size() * 4, hipMemcpyHostToDevice, c->stream));
+            HIP_TRY(c, hipMemcpyAsync(c->d_mout, mo.data(), mo.size() * 4, hipMemcpyHostToDevice, c->stream));
+        }
+        for (size_t lv = 0; lv < levels; lv++) {
+            const size_t a = bounds[lv], m = mux_start[lv];
+            if (m > a && (rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, m - a))) return rc;
+            const size_t f = mux_first[lv], cnt = mux_first[lv + 1] - f;
+            if (cnt) {
+                if (m > a) c->timer_levels--;              // gates and MUX entries of one level count once
+                c->timer_levels++;
+                if ((rc = enqueue_mux_level(c, c->d_mtype + 2 * f, c->d_min0 + 2 * f, c->d_min1 + 2 * f, c->d_mout + f, cnt))) return rc;
+            }
         }
     }
     if (!nl.copy_src.empty()) {
@@ -324,7 +409,8 @@ void she_free(she_ctx *c)
     hipFree(c->temp);
     hipFree(c->work.bar); hipFree(c->work.ext_b); hipFree(c->work.ksd);
     hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out);
-    hipFree(c->d_stage); hipFree(c->d_round_err);
+    hipFree(c->d_stage); hipFree(c->d_round_err); hipFree(c->work.raw_ext);
+    hipFree(c->d_mtype); hipFree(c->d_min0); hipFree(c->d_min1); hipFree(c->d_mout);
     delete c;
 }
 
@@ -414,6 +500,43 @@ int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_i
     return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates);
 }
 
+int she_eval_mux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
+                 size_t nmux)
+{
+    if (!c) return SHE_EINVAL;
+    if (nmux == 0) return SHE_OK;
+    if (!sel || !in1 || !in0 || !out) return fail(c, SHE_EINVAL, "null argument");
+    int rc;
+    if ((rc = check_ids(c, sel, nmux, "she_eval_mux sel"))) return rc;
+    if ((rc = check_ids(c, in1, nmux, "she_eval_mux in1"))) return rc;
+    if ((rc = check_ids(c, in0, nmux, "she_eval_mux in0"))) return rc;
+    if ((rc = check_ids(c, out, nmux, "she_eval_mux out"))) return rc;
+    if ((rc = check_disjoint(c, sel, nmux, in1, nmux, out, nmux))) return rc;
+    if ((rc = check_disjoint(c, in0, nmux, nullptr, 0, out, nmux))) return rc;
+    try {
+        std::vector<uint8_t> jt(2 * nmux);
+        std::vector<uint32_t> j0(2 * nmux), j1(2 * nmux);
+        for (size_t m = 0; m < nmux; m++) {
+            jt[2 * m] = SHE_AND;       j0[2 * m] = sel[m];     j1[2 * m] = in1[m];        // sel and in1
+            jt[2 * m + 1] = SHE_ANDNY; j0[2 * m + 1] = sel[m]; j1[2 * m + 1] = in0[m];    // (not sel) and in0
+        }
+        if ((rc = ensure_work(c, std::min<size_t>(2 * nmux, MAX_LEVEL_CHUNK)))) return rc;
+        if ((rc = ensure_raw(c, std::min<size_t>(2 * nmux, MAX_LEVEL_CHUNK)))) return rc;
+        if ((rc = ensure_mux_arrays(c, nmux))) return rc;
+        HIP_TRY(c, hipMemcpyAsync(c->d_mtype, jt.data(), jt.size(), hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_min0, j0.data(), j0.size() * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_min1, j1.data(), j1.size() * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_mout, out, nmux * 4, hipMemcpyHostToDevice, c->stream));
+        c->timer.clear();
+        c->timer_levels = 1;
+        if ((rc = enqueue_mux_level(c, c->d_mtype, c->d_min0, c->d_min1, c->d_mout, nmux))) return rc;
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        return finish_timing(c);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host staging");
+    }
+}
+
 // ---- netlist construction shared by the operators and the planning calls ----
 static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids, uint32_t units, uint32_t terms,
                                              uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
@@ -497,7 +620,7 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
     const char *why = "";
     if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return fail(c, SHE_EINVAL, why);
     try {
-        Netlist nl(c->cap, c->fold);
+        Netlist nl(c->cap, c->fold, c->native_mux);
         const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -519,7 +642,7 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap, c->fold);
+        Netlist nl(c->cap, c->fold, c->native_mux);
         const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -542,7 +665,7 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold);
+        Netlist nl(c->cap, c->fold, c->native_mux);
         const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -554,20 +677,22 @@ int she_set_option(she_ctx *c, int option, int value)
 {
     if (!c) return SHE_EINVAL;
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
+    if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
     return fail(c, SHE_EINVAL, "unknown option");
 }
 
 // ---- planning: the operators' netlists without a GPU (inputs are wires 0, 1, 2, ... in argument order) ----
-static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels)
+static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
 {
     if (nl.overflow) return SHE_ERANGE;
     if (gates) *gates = nl.type.size();
+    if (rotations) *rotations = nl.rotations();
     if (levels) *levels = (uint32_t)(nl.levelize().size() - 1);
     return SHE_OK;
 }
 
 int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
-                       uint32_t acc_bits, int fold, uint64_t *gates, uint32_t *levels)
+                       uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
 {
     if (in_bits < 1 || in_bits > acc_bits || acc_bits > 32) return SHE_EINVAL;
     const size_t n_in = (size_t)units * terms * in_bits;
@@ -577,38 +702,39 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
     try {
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), fold != 0);
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
         wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
-        return plan_finish(nl, gates, levels);
+        return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
 }
 
-int she_plan_relu(uint32_t count, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels)
+int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
 {
     if (bits < 2 || bits > 64 || (size_t)count * bits > 0x40000000u) return SHE_EINVAL;
     try {
         std::vector<uint32_t> ids((size_t)count * bits);
         for (size_t k = 0; k < ids.size(); k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), fold != 0);
+        Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
         wires_relu(nl, ids.data(), count, bits);
-        return plan_finish(nl, gates, levels);
+        return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
 }
 
-int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int fold, uint64_t *gates, uint32_t *levels)
+int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
+                     uint64_t *rotations)
 {
     const size_t n_in = (size_t)H * W * C * bits;
     if (bits < 2 || bits > 64 || n_in > 0x40000000u) return SHE_EINVAL;
     try {
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), fold != 0);
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
         wires_maxpool(nl, ids.data(), H, W, C, bits);
-        return plan_finish(nl, gates, levels);
+        return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }

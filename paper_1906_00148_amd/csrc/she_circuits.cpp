@@ -30,17 +30,28 @@ struct Operand {     // a wire reference taken apart
 
 }  // namespace
 
+static uint32_t emit_entry(Netlist &nl, int c, uint32_t x, uint32_t y, uint32_t z)
+{
+    if (nl.next_temp >= WIRE_NEG - 1) { nl.overflow = true; return nl.zero(); }
+    const uint32_t w = nl.next_temp++;
+    nl.type.push_back((uint8_t)c);
+    nl.in0.push_back(x);
+    nl.in1.push_back(y);
+    nl.in2.push_back(z);
+    nl.out.push_back(w);
+    return w;
+}
+
+uint64_t Netlist::rotations() const
+{
+    uint64_t r = 0;
+    for (uint8_t t : type) r += t >= MUX_BASE ? 2 : 1;
+    return r;
+}
+
 uint32_t Netlist::gate(int code, uint32_t a, uint32_t b)
 {
-    auto emit = [&](int c, uint32_t x, uint32_t y) {
-        if (next_temp >= WIRE_NEG - 1) { overflow = true; return zero(); }
-        const uint32_t w = next_temp++;
-        type.push_back((uint8_t)c);
-        in0.push_back(x);
-        in1.push_back(y);
-        out.push_back(w);
-        return w;
-    };
+    auto emit = [&](int c, uint32_t x, uint32_t y) { return emit_entry(*this, c, x, y, 0); };
     if (!fold) return emit(code, a, b);
 
     auto take = [&](uint32_t ref) {
@@ -71,12 +82,39 @@ uint32_t Netlist::gate(int code, uint32_t a, uint32_t b)
     return emit(code_of_truth(table), A.value, B.value);
 }
 
-// s ? u : v with three 2-input gates
+// s ? u : v.  Three 2-input gates, or (native_mux) one entry whose two blind rotations bootstrap
+// code1(s, u) and code0(s, v): AND and ANDNY for plain operands, ANDYN / NOR when u / v is complemented.
 uint32_t Netlist::mux(uint32_t s, uint32_t u, uint32_t v)
 {
-    const uint32_t taken = gate(SHE_AND, s, u);
-    const uint32_t other = gate(SHE_ANDNY, s, v);
-    return gate(SHE_OR, taken, other);
+    if (!native_mux) {
+        const uint32_t taken = gate(SHE_AND, s, u);
+        const uint32_t other = gate(SHE_ANDNY, s, v);
+        return gate(SHE_OR, taken, other);
+    }
+    if (!fold) return emit_entry(*this, MUX_BASE + 16 * SHE_AND + SHE_ANDNY, s, u, v);
+
+    auto is_const = [&](uint32_t ref) { const uint32_t w = ref & ~WIRE_NEG; return w == zero() || w == one(); };
+    auto const_value = [&](uint32_t ref) { return ((ref & ~WIRE_NEG) == one() ? 1u : 0u) ^ (ref >> 31); };
+    if (is_const(s)) return const_value(s) ? u : v;
+    if (s & WIRE_NEG) { std::swap(u, v); s &= ~WIRE_NEG; }            // not s ? u : v  ==  s ? v : u
+    // a branch that repeats the selector is a constant on that branch
+    if (!is_const(u) && (u & ~WIRE_NEG) == s) u = (u & WIRE_NEG) ? zero() : one();
+    if (!is_const(v) && (v & ~WIRE_NEG) == s) v = (v & WIRE_NEG) ? one() : zero();
+    const bool cu = is_const(u), cv = is_const(v);
+    if (cu && cv) {
+        const uint32_t a = const_value(u), b = const_value(v);
+        if (a == b) return a ? one() : zero();
+        return a ? s : (s | WIRE_NEG);
+    }
+    if (cu) return gate(const_value(u) ? SHE_OR : SHE_ANDNY, s, v);     // s ? 1 : v = s or v;   s ? 0 : v = not s and v
+    if (cv) return gate(const_value(v) ? SHE_ORNY : SHE_AND, s, u);     // s ? u : 1 = not s or u; s ? u : 0 = s and u
+    if ((u & ~WIRE_NEG) == (v & ~WIRE_NEG)) {
+        if (u == v) return u;
+        return gate((u & WIRE_NEG) ? SHE_XOR : SHE_XNOR, s, u & ~WIRE_NEG);   // s ? u : not u
+    }
+    const int code1 = (u & WIRE_NEG) ? SHE_ANDYN : SHE_AND;             // s and (not) u
+    const int code0 = (v & WIRE_NEG) ? SHE_NOR : SHE_ANDNY;             // (not s) and (not) v
+    return emit_entry(*this, MUX_BASE + 16 * code1 + code0, s, u & ~WIRE_NEG, v & ~WIRE_NEG);
 }
 
 void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst)
@@ -96,40 +134,52 @@ void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *d
         const uint32_t w = ref & ~WIRE_NEG;
         if (w >= first_temp && rename[w - first_temp] != unbound) ref = rename[w - first_temp] | (ref & WIRE_NEG);
     };
-    for (size_t g = 0; g < type.size(); g++) { fix(in0[g]); fix(in1[g]); fix(out[g]); }
+    for (size_t g = 0; g < type.size(); g++) {
+        fix(in0[g]); fix(in1[g]); fix(out[g]);
+        if (type[g] >= MUX_BASE) fix(in2[g]);
+    }
     for (auto &w : copy_src) fix(w);
 }
 
 // Must run before bind_outputs (every gate output is still a temporary wire).
-std::vector<size_t> Netlist::levelize()
+std::vector<size_t> Netlist::levelize(std::vector<size_t> *mux_start)
 {
-    // depth of a wire = 0 for inputs and constants, else 1 + deepest operand; gates were
+    // depth of a wire = 0 for inputs and constants, else 1 + deepest operand; entries were
     // appended in topological order, so one pass suffices
     const uint32_t first_temp = cap + 2;
     std::vector<uint32_t> depth(next_temp - first_temp, 0);
     std::vector<uint32_t> lev(type.size());
     uint32_t deepest = 0;
+    auto depth_of = [&](uint32_t w) { return w >= first_temp ? depth[w - first_temp] : 0u; };
     for (size_t g = 0; g < type.size(); g++) {
-        uint32_t d = 0;
-        if (in0[g] >= first_temp) d = depth[in0[g] - first_temp];
-        if (in1[g] >= first_temp) d = std::max(d, depth[in1[g] - first_temp]);
+        uint32_t d = std::max(depth_of(in0[g]), depth_of(in1[g]));
+        if (type[g] >= MUX_BASE) d = std::max(d, depth_of(in2[g]));
         lev[g] = d + 1;
         depth[out[g] - first_temp] = d + 1;
         deepest = std::max(deepest, d + 1);
     }
-    std::vector<size_t> start(deepest + 2, 0);
-    for (uint32_t v : lev) start[v + 1]++;
+    // bucket = 2*level + (1 for a MUX entry): gates of a level come before its MUX entries
+    std::vector<size_t> start(2 * (size_t)deepest + 3, 0);
+    auto bucket = [&](size_t g) { return 2 * (size_t)lev[g] + (type[g] >= MUX_BASE ? 1 : 0); };
+    for (size_t g = 0; g < type.size(); g++) start[bucket(g) + 1]++;
     for (size_t i = 1; i < start.size(); i++) start[i] += start[i - 1];
     std::vector<size_t> cursor(start.begin(), start.end() - 1);
     std::vector<uint8_t> t2(type.size());
-    std::vector<uint32_t> a2(type.size()), b2(type.size()), o2(type.size());
+    std::vector<uint32_t> a2(type.size()), b2(type.size()), c2(type.size()), o2(type.size());
     for (size_t g = 0; g < type.size(); g++) {
-        const size_t pos = cursor[lev[g]]++;
-        t2[pos] = type[g]; a2[pos] = in0[g]; b2[pos] = in1[g]; o2[pos] = out[g];
+        const size_t pos = cursor[bucket(g)]++;
+        t2[pos] = type[g]; a2[pos] = in0[g]; b2[pos] = in1[g]; c2[pos] = in2[g]; o2[pos] = out[g];
     }
-    type.swap(t2); in0.swap(a2); in1.swap(b2); out.swap(o2);
-    // start[1..deepest+1] are the level boundaries (level 0 holds no gates)
-    return std::vector<size_t>(start.begin() + 1, start.end());
+    type.swap(t2); in0.swap(a2); in1.swap(b2); in2.swap(c2); out.swap(o2);
+    // level lv (1-based) occupies [start[2 lv], start[2 lv + 2]), its MUX entries start at start[2 lv + 1]
+    std::vector<size_t> bounds;
+    if (mux_start) mux_start->clear();
+    for (uint32_t lv = 1; lv <= deepest; lv++) {
+        bounds.push_back(start[2 * lv]);
+        if (mux_start) mux_start->push_back(start[2 * lv + 1]);
+    }
+    bounds.push_back(type.size());
+    return bounds;
 }
 
 // a + b for equally wide unsigned vectors; one more bit than the operands unless that

@@ -38,6 +38,8 @@ struct LevelWork {                // scratch of one level launch, sized for `gat
     uint16_t *ksd = nullptr;      // [gates/KS_GROUP][N][KS_GROUP] rounded top bits of the extracted mask
     uint32_t bar_stride = 0;
     size_t gates = 0;
+    uint32_t *raw_ext = nullptr;  // [jobs][N+1] extracted samples of MUX rotations (not yet key-switched)
+    size_t raw_jobs = 0;
 };
 
 // ---- kernel launchers (she_kernels.hip); each returns a hipError_t and never synchronises ----
@@ -51,7 +53,10 @@ hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t 
                           const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                                size_t gates, const LevelWork &W, unsigned *d_round_err /* nullptr = no tracking */,
-                               hipStream_t st);
+                               hipStream_t st, bool raw = false /* write W.raw_ext instead of digits and slots */);
+// MUX m: sample = raw_ext[2m] + raw_ext[2m+1] + (0, 1/8) -> key-switch digits, body and slot initialisation of gate m
+hipError_t launch_mux_combine(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                              size_t muxes, const LevelWork &W, hipStream_t st);
 hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                              size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_scatter(const CtSpace &cs, const uint32_t *d_src /* [count][n+1] */, const uint32_t *d_ids,
@@ -77,6 +82,7 @@ void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, co
 
 // ---- netlists of the layer operators (she_circuits.cpp) ----
 constexpr uint32_t WIRE_NEG = 0x80000000u;   // flag on a wire reference: the complement of that wire
+constexpr int MUX_BASE = SHE_NUM_GATES;       // netlist type of a native MUX entry: MUX_BASE + 16*code1 + code0
 
 struct Netlist {
     // wire ids: [0, cap) pool slots, cap = trivial 0, cap+1 = trivial 1, cap+2.. temporaries.
@@ -87,13 +93,15 @@ struct Netlist {
     uint32_t cap = 0;
     uint32_t next_temp = 0;
     bool fold = false;
+    bool native_mux = false;                    // mux() emits one three-input entry instead of three gates
     bool overflow = false;                      // more wires than 31-bit ids can name
     std::vector<uint8_t> type;
-    std::vector<uint32_t> in0, in1, out;
+    std::vector<uint32_t> in0, in1, in2, out;   // in2: third operand of MUX entries (0 otherwise)
     std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates; copy_src may carry WIRE_NEG
 
-    explicit Netlist(uint32_t capacity, bool fold_constants = false)
-        : cap(capacity), next_temp(capacity + 2), fold(fold_constants) {}
+    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false)
+        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native) {}
+    uint64_t rotations() const;                 // blind rotations: one per gate, two per MUX entry
     uint32_t zero() const { return cap; }
     uint32_t one() const { return cap + 1; }
     uint32_t gate(int code, uint32_t a, uint32_t b);
@@ -101,8 +109,9 @@ struct Netlist {
     // route the wires in `wires` to the caller's ids `dst`: gate outputs are renamed,
     // anything else (inputs, constants, a wire used twice) is copied at the end
     void bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst);
-    // stable sort of the gates by depth; returns the first gate index of each level (+ end)
-    std::vector<size_t> levelize();
+    // stable sort of the entries by (depth, gates before MUX entries); returns the first index of each
+    // level (+ end); mux_start[lv] receives the index of level lv's first MUX entry
+    std::vector<size_t> levelize(std::vector<size_t> *mux_start = nullptr);
 };
 std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const std::vector<uint32_t> &b, uint32_t cap_bits);
 std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const std::vector<uint32_t> &q);

@@ -69,7 +69,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
     const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
     const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
     uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err, CtSpace cs,
-    const uint32_t *__restrict__ out_ids)
+    const uint32_t *__restrict__ out_ids, uint32_t *__restrict__ raw_ext)
 {
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
     __shared__ uint32_t s_acc[BR_WAVES * GPW][2][N];
@@ -182,8 +182,14 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
 
     if (TRACK && round_err) atomicMax(round_err, __float_as_uint(worst));
 
-    // sample extraction: a''_0 = A_0, a''_j = -A_{N-j}, b'' = B_0; keep the top ks_bits of each a'' rounded
-    if (live) {
+    // sample extraction: a''_0 = A_0, a''_j = -A_{N-j}, b'' = B_0
+    if (live && raw_ext) {
+        // a rotation of a MUX: the sample itself is kept, two of them are summed before the key switch
+        uint32_t *dst = raw_ext + (size_t)g * (N + 1);
+        for (int j = t; j < N; j += L) dst[j] = (j == 0) ? acc[0][0] : 0u - acc[0][N - j];
+        if (t == 0) dst[N] = acc[1][0];
+    } else if (live) {
+        // keep the top ks_bits of each a'' rounded
         const uint32_t rnd = 1u << (31 - ks_bits), sh = 32 - ks_bits;
         uint16_t *dst = ksd + ((size_t)(g / KS_GROUP) * N) * KS_GROUP + (g % KS_GROUP);
         for (int j = t; j < N; j += L) {
@@ -197,6 +203,27 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
             const uint32_t body = acc[1][0];
             for (uint32_t c = t; c <= n; c += L) o[c] = (c == n) ? body : 0u;
         }
+    }
+}
+
+// Second half of a native MUX: the two rotations' samples are added, 1/8 goes on the body, and the
+// sum is prepared for the key switch exactly as the blind rotation's epilogue prepares a gate.
+__global__ __launch_bounds__(256) void k_mux_combine(const uint32_t *__restrict__ raw_ext, uint32_t N, uint32_t n,
+                                                     uint32_t ks_bits, uint32_t *__restrict__ ext_b,
+                                                     uint16_t *__restrict__ ksd, CtSpace cs,
+                                                     const uint32_t *__restrict__ out_ids)
+{
+    const uint32_t g = blockIdx.x;
+    const uint32_t *e1 = raw_ext + (size_t)(2 * g) * (N + 1), *e0 = e1 + (N + 1);
+    const uint32_t rnd = 1u << (31 - ks_bits), sh = 32 - ks_bits;
+    uint16_t *dst = ksd + ((size_t)(g / KS_GROUP) * N) * KS_GROUP + (g % KS_GROUP);
+    for (uint32_t j = threadIdx.x; j < N; j += blockDim.x)
+        dst[(size_t)j * KS_GROUP] = (uint16_t)((e1[j] + e0[j] + rnd) >> sh);
+    const uint32_t body = e1[N] + e0[N] + (1u << 29);
+    if (threadIdx.x == 0) ext_b[g] = body;
+    if (out_ids) {
+        uint32_t *o = ct_ptr(cs, out_ids[g]);
+        for (uint32_t c = threadIdx.x; c <= n; c += blockDim.x) o[c] = (c == n) ? body : 0u;
     }
 }
 
@@ -454,31 +481,42 @@ hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t 
 
 template <class PL>
 static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
-                                 unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st)
+                                 unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st,
+                                 uint32_t *raw_ext)
 {
     const uint32_t per_block = BR_WAVES * PL::GPW;
     const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
     const uint32_t ks_bits = P.ks_t * P.ks_basebit;
     if (d_round_err)
         hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out);
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
     else
         hipLaunchKernelGGL((k_blind_rotate<PL, false>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out);
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
     return hipGetLastError();
 }
 
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
-                               size_t gates, const LevelWork &W, unsigned *d_round_err, hipStream_t st)
+                               size_t gates, const LevelWork &W, unsigned *d_round_err, hipStream_t st, bool raw)
 {
     if (!gates) return hipSuccess;
     if (!K.ks_bytes) d_out = nullptr;      // the generic key switch writes the slot itself
+    uint32_t *raw_ext = raw ? W.raw_ext : nullptr;
     switch (P.N) {
-    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, cs, d_out, st);
-    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, cs, d_out, st);
-    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, cs, d_out, st);
+    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
+    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
+    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
     }
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_mux_combine(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
+                              size_t muxes, const LevelWork &W, hipStream_t st)
+{
+    if (!muxes) return hipSuccess;
+    hipLaunchKernelGGL(k_mux_combine, dim3((unsigned)muxes), dim3(256), 0, st, W.raw_ext, P.N, P.n,
+                       P.ks_t * P.ks_basebit, W.ext_b, W.ksd, cs, K.ks_bytes ? d_out : nullptr);
+    return hipGetLastError();
 }
 
 hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,

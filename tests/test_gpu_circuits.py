@@ -57,6 +57,20 @@ def test_cfg4_relu_maxpool_reduced_and_corner_values(ctx):
     pool2 = pool_ids + 5000
     ctx.maxpool(ids, pool2)
     assert np.array_equal(OC.from_bits(ctx.decrypt(pool2), True), OC.plain_maxpool2x2(fm))
+    # the same with native three-input MUX gates (and with folding on top)
+    import paper_1906_00148_amd as pkg
+    for fold in (0, 1):
+        ctx.set_option(pkg.OPT_NATIVE_MUX, 1)
+        ctx.set_option(pkg.OPT_FOLD_CONSTANTS, fold)
+        try:
+            pool3 = pool_ids + 10000 * (1 + fold)
+            g3 = ctx.maxpool(ids, pool3)
+            assert g3 == pkg.plan_maxpool(8, 8, 4, 16, bool(fold), True)[0]
+            assert ctx.last_timing()["levels"] == 36
+            assert np.array_equal(OC.from_bits(ctx.decrypt(pool3), True), OC.plain_maxpool2x2(fm))
+        finally:
+            ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
+            ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
 
 
 def test_cfg4_full_feature_map_relu_then_pool():

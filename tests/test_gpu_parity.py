@@ -292,3 +292,40 @@ def test_folded_operators_match_folded_oracle_netlists_toy(toy_ctx, toy_keys):
         assert int(OC.from_bits(toy_ctx.decrypt(pool_ids), True)) == 2
     finally:
         toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
+
+
+# ------------------------------------------------------------------ native MUX
+def test_eval_mux_bit_exact_toy_and_real(toy_ctx, toy_keys, real_ctx, real_keys):
+    for ctx, K, reps in ((toy_ctx, toy_keys, 5), (real_ctx, real_keys, 1)):
+        combos = [(s, a, b) for s in (0, 1) for a in (0, 1) for b in (0, 1)] * reps
+        bits = np.array(combos, np.uint8).ravel()
+        n = len(combos)
+        ids = np.arange(3 * n, dtype=np.uint32)
+        ctx.encrypt_bits(bits, 61, ids)
+        fresh = O.encrypt_bits(K, bits, 61).reshape(n, 3, -1)
+        out = np.arange(3 * n, 4 * n, dtype=np.uint32)
+        ctx.eval_mux(ids[0::3], ids[1::3], ids[2::3], out)
+        got = ctx.read_cts(out)
+        assert ctx.decrypt(out).tolist() == [a if s else b for s, a, b in combos]
+        for m in range(n if K.params.N == 256 else 4):
+            assert np.array_equal(got[m], O.mux(K, fresh[m, 0], fresh[m, 1], fresh[m, 2])), m
+
+
+def test_maxpool_with_native_mux_matches_oracle_netlist_toy(toy_ctx, toy_keys):
+    pkg = she()
+    vals = np.array([[[-3, 5], [2, -8]], [[1, 7], [-4, 6]]])                  # H=2, W=2, C=2, 4-bit
+    for fold in (0, 1):
+        toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 1)
+        toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, fold)
+        try:
+            ids, fresh = _encrypt_values(toy_ctx, toy_keys, vals, 4, 63, 0)
+            pool_ids = np.arange(3000, 3008, dtype=np.uint32)
+            g = toy_ctx.maxpool(ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
+            nl, outs = OC.build_maxpool(2, 2, 2, 4, fold=bool(fold), native_mux=True)
+            assert g == len(nl.gtype)
+            pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+            assert np.array_equal(toy_ctx.read_cts(pool_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+            assert OC.from_bits(toy_ctx.decrypt(pool_ids.reshape(2, 4)), True).tolist() == [2, 7]
+        finally:
+            toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
+            toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)

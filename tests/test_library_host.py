@@ -93,8 +93,9 @@ def test_planning_calls_match_the_oracle_netlists():
     for fold in (False, True):
         nl, _ = OC.build_relu(7, 16, fold=fold)
         assert she.plan_relu(7, 16, fold) == (len(nl.gtype), 1)
-        nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold)
-        assert she.plan_maxpool(5, 4, 3, 6, fold) == (len(nl.gtype), int(nl.levels().max()))
+        for native in (False, True):
+            nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold, native_mux=native)
+            assert she.plan_maxpool(5, 4, 3, 6, fold, native, True) == (len(nl.gtype), int(nl.levels().max()), nl.rotations)
     # the benchmark's conv layer: 26x26 pixels x 8 channels of 9-term neurons
     import synth_inputs as S
     _, sign, exp = S.cfg5_conv_layer()

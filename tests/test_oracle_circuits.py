@@ -218,3 +218,40 @@ def test_folding_gate_counts_of_the_benchmark_shapes():
     lean, _ = C.build_shift_acc(1, 576, 8, sign, exp, 16, fold=True)
     assert (len(full.gtype), len(lean.gtype)) == (24144, 16889)
     assert int(full.levels().max()) == int(lean.levels().max()) == 48
+
+
+# ------------------------------------------------------------------ native MUX entries in netlists
+def test_mux_rules_exhaustive():
+    for fold in (False, True):
+        nl = C.Netlist(3, fold, True)
+        refs = {"x": 0, "y": 1, "z": 2}
+        if fold:
+            refs.update({"nx": 0 | C.NEG, "ny": 1 | C.NEG, "nz": 2 | C.NEG, "0": nl.ZERO, "1": nl.ONE})
+
+        def value(tag, x, y, z):
+            return {"x": x, "nx": 1 - x, "y": y, "ny": 1 - y, "z": z, "nz": 1 - z, "0": 0, "1": 1}[tag]
+        for ts, rs in refs.items():
+            for tu, ru in refs.items():
+                for tv, rv in refs.items():
+                    before = len(nl.gtype)
+                    o = nl.mux(rs, ru, rv)
+                    distinct = len({t[-1] for t in (ts, tu, tv) if t[-1] in "xyz"})
+                    if fold:
+                        assert (len(nl.gtype) - before) <= 1
+                        if distinct < 3:
+                            assert all(t < tfhe.MUX_BASE for t in nl.gtype[before:]), (ts, tu, tv)
+                    for x, y, z in itertools.product((0, 1), repeat=3):
+                        got = int(C.Netlist.read_plain(nl.run_plain([x, y, z]), [o])[0])
+                        assert got == (value(tu, x, y, z) if value(ts, x, y, z) else value(tv, x, y, z))
+
+
+def test_max_with_native_mux():
+    for fold in (False, True):
+        nl = C.Netlist(8, fold, True)
+        out = C.max_signed(nl, [0, 1, 2, 3], [4, 5, 6, 7])
+        for a, b in itertools.product(range(-8, 8), repeat=2):
+            bits = np.concatenate([C.to_bits(np.array(a), 4), C.to_bits(np.array(b), 4)])
+            assert int(C.from_bits(C.Netlist.read_plain(nl.run_plain(bits), out), True)) == max(a, b)
+    nl = C.Netlist(32, False, True)
+    C.max_signed(nl, list(range(16)), list(range(16, 32)))
+    assert (len(nl.gtype), nl.rotations, int(nl.levels().max())) == (48, 80, 18)      # 16 XNOR + 32 MUX

@@ -368,3 +368,62 @@ def test_oracle_digests_are_frozen():
     spec.loader.exec_module(mod)
     with open(os.path.join(here, "oracle_digests.json")) as f:
         assert mod.compute() == json.load(f)
+
+
+# ----------------------------------------------------------------- native three-input MUX
+def _mux_cases(K, reps, seed):
+    combos = [(s, a, b) for s in (0, 1) for a in (0, 1) for b in (0, 1)]
+    bits = np.array([c for _ in range(reps) for c in combos], np.uint8).ravel()
+    return combos * reps, tfhe.encrypt_bits(K, bits, seed).reshape(len(combos) * reps, 3, -1)
+
+
+def test_mux_truth_table_and_noise_toy(toy_keys):
+    K = toy_keys
+    cases, cts = _mux_cases(K, 4, 91)
+    errs = []
+    for (s, a, b), c in zip(cases, cts):
+        out = tfhe.mux(K, c[0], c[1], c[2])
+        want = a if s else b
+        ph = tfhe.lwe_phase(K.lwe_key, out)
+        assert (int(centred(ph)) > 0) == bool(want), (s, a, b)
+        errs.append(int(centred(ph - (EIGHTH if want else -EIGHTH))))
+    errs = np.array(errs, np.float64) / 2 ** 32
+    # two blind rotations feed one key switch: variance 2 V_BR + V_KS
+    P = K.params
+    v_br = P.n * 2 * P.l * P.N * ((1 << P.bg_bit) ** 2 / 4.0) * P.bk_std ** 2 + P.n * (1 + P.N) * 2.0 ** (-2 * (P.l * P.bg_bit + 1))
+    v_ks = P.N * P.ks_t * P.lwe_std ** 2 + P.N * 2.0 ** (-2 * (P.ks_t * P.ks_basebit + 1)) / 3
+    assert errs.std() < math.sqrt(2 * v_br + v_ks) and np.abs(errs).max() < 1 / 16
+
+
+def test_mux_real_params(real_keys):
+    K = real_keys
+    cases, cts = _mux_cases(K, 1, 92)
+    for (s, a, b), c in zip(cases, cts):
+        assert int(tfhe.decrypt_bits(K, tfhe.mux(K, c[0], c[1], c[2]))[0]) == (a if s else b)
+
+
+def test_mux_with_complemented_operand_codes(toy_keys):
+    # ANDYN / NOR as rotation codes realise sel ? not c1 : c0 and sel ? c1 : not c0
+    K = toy_keys
+    G = tfhe.GATES
+    cases, cts = _mux_cases(K, 1, 93)
+    for (s, a, b), c in zip(cases, cts):
+        o = tfhe.mux(K, c[0], c[1], c[2], code1=G["ANDYN"], code0=G["ANDNY"])
+        assert int(tfhe.decrypt_bits(K, o)[0]) == ((1 - a) if s else b)
+        o = tfhe.mux(K, c[0], c[1], c[2], code1=G["AND"], code0=G["NOR"])
+        assert int(tfhe.decrypt_bits(K, o)[0]) == (a if s else (1 - b))
+
+
+def test_mux_is_sum_of_two_rotations_then_one_key_switch(toy_keys):
+    # rebuilt from the oracle's own pieces: pins the composition (order of additions, the 1/8 offset)
+    K, P = toy_keys, toy_keys.params
+    c = tfhe.encrypt_bits(K, np.array([1, 0, 1], np.uint8), 94)
+    ext = []
+    for code, other in ((tfhe.GATES["AND"], c[1]), (tfhe.GATES["ANDNY"], c[2])):
+        t = tfhe.gate_lincomb(code, c[0], other)
+        abar = [tfhe.modswitch(P.N, int(x)) for x in t[:-1]]
+        acc = tfhe.blind_rotate(P, K.bk, abar, tfhe.modswitch(P.N, int(t[-1])))
+        ext.append(tfhe.sample_extract(acc).astype(np.int64))
+    total = (ext[0] + ext[1]) & M32
+    total[-1] = (total[-1] + EIGHTH) & M32
+    assert np.array_equal(tfhe.mux(K, c[0], c[1], c[2]), tfhe.key_switch(P, K.ks, total.astype(np.uint32)))
