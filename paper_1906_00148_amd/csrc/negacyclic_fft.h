@@ -176,47 +176,62 @@ template <class PL> __device__ __forceinline__ void load_twiddles(double2 *lds, 
     __syncthreads();
 }
 
-// Forward transform.  In: xr/xi[m] = u_{t + L*m} (folded, not yet twisted).  Out: spectrum in
-// the lane/register order that inverse() and the pointwise products share.
-template <class PL> __device__ __forceinline__ void forward(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+// Forward transform of NB independent polynomials held by the same lanes (NB register sets, NB
+// exchange buffers); their passes are written side by side so that one set's arithmetic can fill the
+// other's LDS round trips.  In: xr/xi[b][m] = u_{t + L*m} (folded, not yet twisted).  Out: spectra in
+// the lane/register order that inverse_n() and the pointwise products share.
+template <class PL, int NB>
+__device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                          double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
     // register-dependent part of the twist: psi^(L*m) = exp(i*pi*m/(2P))
 #pragma unroll
-    for (int m = 1; m < P; m++) {
-        const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
-        const double r = xr[m], i = xi[m];
-        xr[m] = r * cr - i * ci;
-        xi[m] = r * ci + i * cr;
-    }
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int m = 1; m < P; m++) {
+            const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
+            const double r = xr[b][m], i = xi[b][m];
+            xr[b][m] = r * cr - i * ci;
+            xi[b][m] = r * ci + i * cr;
+        }
 #pragma unroll
     for (int s = 0; s < K; s++) {
-        dft_regs<P, +1>(xr, xi);
+#pragma unroll
+        for (int b = 0; b < NB; b++) dft_regs<P, +1>(xr[b], xi[b]);
         if (s == K - 1) break;
         wave_lds_fence();
 #pragma unroll
         for (int k = 0; k < P; k++) {
-            if (k >= (s == 0 ? 0 : 1)) {
-                const double2 w = lc.twiddle(s, k);
-                const double r = xr[k], i = xi[k];
-                xr[k] = r * w.x - i * w.y;
-                xi[k] = r * w.y + i * w.x;
+            double2 w = make_double2(1.0, 0.0);
+            if (k >= (s == 0 ? 0 : 1)) w = lc.twiddle(s, k);
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                if (k >= (s == 0 ? 0 : 1)) {
+                    const double r = xr[b][k], i = xi[b][k];
+                    xr[b][k] = r * w.x - i * w.y;
+                    xi[b][k] = r * w.y + i * w.x;
+                }
+                xch[b][k * PL::XROW + lc.t] = make_double2(xr[b][k], xi[b][k]);   // stores overlap the remaining products
             }
-            lc.xch[k * PL::XROW + lc.t] = make_double2(xr[k], xi[k]);     // stores overlap the remaining products
         }
         wave_lds_fence();
         const int Tn = ipow(P, K - 2 - s);
 #pragma unroll
-        for (int m = 0; m < P; m++) {
-            const double2 v = lc.xch[lc.rd_base[s] + m * Tn];
-            xr[m] = v.x; xi[m] = v.y;
-        }
+        for (int b = 0; b < NB; b++)
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                const double2 v = xch[b][lc.rd_base[s] + m * Tn];
+                xr[b][m] = v.x; xi[b][m] = v.y;
+            }
     }
 }
 
-// Inverse transform, the mirror of forward(); the 1/M normalisation is folded into the last
-// constant multiplication.  Out: xr/xi[m] = u_{t + L*m}.
-template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+// Inverse transforms, the mirror of forward_n(); the 1/M normalisation is folded into the last
+// constant multiplication.  Out: xr/xi[b][m] = u_{t + L*m}.
+template <class PL, int NB>
+__device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                          double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
 #pragma unroll
@@ -226,33 +241,56 @@ template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &l
             const int Tn = ipow(P, K - 2 - s);
             wave_lds_fence();
 #pragma unroll
-            for (int m = 0; m < P; m++) lc.xch[lc.rd_base[s] + m * Tn] = make_double2(xr[m], xi[m]);
+            for (int b = 0; b < NB; b++)
+#pragma unroll
+                for (int m = 0; m < P; m++) xch[b][lc.rd_base[s] + m * Tn] = make_double2(xr[b][m], xi[b][m]);
             wave_lds_fence();
 #pragma unroll
-            for (int k = 0; k < P; k++) {
-                const double2 v = lc.xch[k * PL::XROW + lc.t];
-                xr[k] = v.x; xi[k] = v.y;
-            }
+            for (int b = 0; b < NB; b++)
+#pragma unroll
+                for (int k = 0; k < P; k++) {
+                    const double2 v = xch[b][k * PL::XROW + lc.t];
+                    xr[b][k] = v.x; xi[b][k] = v.y;
+                }
 #pragma unroll
             for (int k = (s == 0 ? 0 : 1); k < P; k++) {            // conjugate twiddle
                 const double2 w = lc.twiddle(s, k);
-                const double r = xr[k], i = xi[k];
-                xr[k] = r * w.x + i * w.y;
-                xi[k] = i * w.x - r * w.y;
+#pragma unroll
+                for (int b = 0; b < NB; b++) {
+                    const double r = xr[b][k], i = xi[b][k];
+                    xr[b][k] = r * w.x + i * w.y;
+                    xi[b][k] = i * w.x - r * w.y;
+                }
             }
         }
-        dft_regs<P, -1>(xr, xi);
+#pragma unroll
+        for (int b = 0; b < NB; b++) dft_regs<P, -1>(xr[b], xi[b]);
     }
     constexpr double scale = 1.0 / (double)PL::M;                    // a power of two: products stay exact
-    xr[0] *= scale;
-    xi[0] *= scale;
 #pragma unroll
-    for (int m = 1; m < P; m++) {                                    // conjugate of psi^(L*m), times 1/M
-        const double cr = cos_pi64(32 * m / P) * scale, ci = sin_pi64(32 * m / P) * scale;
-        const double r = xr[m], i = xi[m];
-        xr[m] = r * cr + i * ci;
-        xi[m] = i * cr - r * ci;
+    for (int b = 0; b < NB; b++) {
+        xr[b][0] *= scale;
+        xi[b][0] *= scale;
+#pragma unroll
+        for (int m = 1; m < P; m++) {                                // conjugate of psi^(L*m), times 1/M
+            const double cr = cos_pi64(32 * m / P) * scale, ci = sin_pi64(32 * m / P) * scale;
+            const double r = xr[b][m], i = xi[b][m];
+            xr[b][m] = r * cr + i * ci;
+            xi[b][m] = i * cr - r * ci;
+        }
     }
+}
+
+// One polynomial at a time.
+template <class PL> __device__ __forceinline__ void forward(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+{
+    double2 *const xch[1] = {lc.xch};
+    forward_n<PL, 1>(lc, xch, reinterpret_cast<double (&)[1][PL::P]>(xr), reinterpret_cast<double (&)[1][PL::P]>(xi));
+}
+template <class PL> __device__ __forceinline__ void inverse(const LaneCtx<PL> &lc, double (&xr)[PL::P], double (&xi)[PL::P])
+{
+    double2 *const xch[1] = {lc.xch};
+    inverse_n<PL, 1>(lc, xch, reinterpret_cast<double (&)[1][PL::P]>(xr), reinterpret_cast<double (&)[1][PL::P]>(xi));
 }
 
 }  // namespace she
