@@ -154,9 +154,8 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
 #pragma unroll
                     for (int k = 0; k < P; k++) {
                         const double2 b = bv[o][k];
-                        // two fused multiply-adds per part (a += x*y - z*w would cost a multiply, an fma and an add)
-                        sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
-                        si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
+                        sr[o][k] += xr[k] * b.x - xi[k] * b.y;
+                        si[o][k] += xr[k] * b.y + xi[k] * b.x;
                     }
                 }
             }
@@ -485,53 +484,9 @@ static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_
                                  unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st,
                                  uint32_t *raw_ext)
 {
-    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
-    const uint32_t per_block = BR_WAVES * PL::GPW;
-    hipLaunchKernelGGL((k_bk_transform<PL>), dim3((polys + per_block - 1) / per_block), dim3(64 * BR_WAVES), 0, st,
-                       d_bk_int, K.twiddles, K.bk_hat, polys);
-    return hipGetLastError();
-}
-
-hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st)
-{
-    switch (P.N) {
-    case 256: return bk_transform_t<Plan256>(P, d_bk_int, K, st);
-    case 512: return bk_transform_t<Plan512>(P, d_bk_int, K, st);
-    case 1024: return bk_transform_t<Plan1024>(P, d_bk_int, K, st);
-    }
-    return hipErrorInvalidValue;
-}
-
-static uint32_t ilog2(uint32_t v) { uint32_t r = 0; while ((1u << r) < v) r++; return r; }
-
-hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
-                          const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st)
-{
-    if (!gates) return hipSuccess;
-    hipLaunchKernelGGL(k_lincomb, dim3((unsigned)gates), dim3(128), 0, st, cs, d_type, d_in0, d_in1, P.n,
-                       ilog2(2 * P.N), W.bar, W.bar_stride);
-    return hipGetLastError();
-}
-
-template <class PL>
-static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
-                                 unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st,
-                                 uint32_t *raw_ext)
-{
-    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
-    static const bool duo = getenv("SHE_BR_DUO") && atoi(getenv("SHE_BR_DUO")) != 0;
-    if (duo) {
-        const dim3 grid2((unsigned)((gates + 2 * BR_WAVES - 1) / (2 * BR_WAVES))), block2(64 * BR_WAVES);
-        if (d_round_err)
-            hipLaunchKernelGGL((k_blind_rotate_duo<PL, true>), grid2, block2, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                               K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
-        else
-            hipLaunchKernelGGL((k_blind_rotate_duo<PL, false>), grid2, block2, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
-                               K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
-        return hipGetLastError();
-    }
     const uint32_t per_block = BR_WAVES * PL::GPW;
     const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
+    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
     if (d_round_err)
         hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
                            K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
