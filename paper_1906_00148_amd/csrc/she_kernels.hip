@@ -154,8 +154,9 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
 #pragma unroll
                     for (int k = 0; k < P; k++) {
                         const double2 b = bv[o][k];
-                        sr[o][k] += xr[k] * b.x - xi[k] * b.y;
-                        si[o][k] += xr[k] * b.y + xi[k] * b.x;
+                        // two fused multiply-adds per part (a += x*y - z*w would cost a multiply, an fma and an add)
+                        sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
+                        si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
                     }
                 }
             }
