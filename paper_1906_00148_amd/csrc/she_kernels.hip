@@ -107,10 +107,18 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
     float worst = 0.f;
 
     uint32_t abar_next = mybar[0];
+    // spectra of the key row in use; row 0 of the next step is requested before the inverse transforms
+    double2 bv[2][P];
+    {
+        const double2 *row = bk_hat + t;
+#pragma unroll
+        for (int o = 0; o < 2; o++)
+#pragma unroll
+            for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
+    }
     for (uint32_t i = 0; i < n; i++) {
         const uint32_t abar = abar_next;
         abar_next = mybar[i + 1];                                          // i+1 == n reads bbar: harmless
-        const double2 *bki = bk_hat + (size_t)i * (2 * l) * 2 * P * L;
 
         double sr[2][P], si[2][P];                                         // spectra of the two output components
 #pragma unroll
@@ -133,13 +141,6 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
             for (uint32_t p = 0; p < l; p++) {
                 const uint32_t sh = 32 - (p + 1) * bg_bit;
                 const uint32_t r = c * l + p;
-                const double2 *row = bki + (size_t)r * 2 * P * L + t;
-                // the row's spectra are requested now and consumed after the transform
-                double2 bv[2][P];
-#pragma unroll
-                for (int o = 0; o < 2; o++)
-#pragma unroll
-                    for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
                 double xr[P], xi[P];
 #pragma unroll
                 for (int m = 0; m < P; m++) {
@@ -159,6 +160,17 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
                         si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
                     }
                 }
+                // request the next row (of this step, or row 0 of the next one) as soon as the registers are free;
+                // after the last step this reads the last row once more, which is harmless
+                {
+                    const size_t nxt = std::min<size_t>((size_t)i * 2 * l + r + 1, (size_t)n * 2 * l - 1);
+                    const double2 *row = bk_hat + nxt * 2 * P * L + t;
+#pragma unroll
+                    for (int o = 0; o < 2; o++)
+#pragma unroll
+                        for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
 #pragma unroll
