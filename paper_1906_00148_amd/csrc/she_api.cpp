@@ -226,6 +226,11 @@ bool params_supported(const she_params &P, std::string &why)
     if (!plan_supported(P.N)) { why = "N must be 256, 512 or 1024"; return false; }
     if (P.n < 1 || P.n > 4096) { why = "n must be in [1, 4096]"; return false; }
     if (P.l < 1 || P.l > 8 || P.bg_bit < 1 || P.l * P.bg_bit > 31) { why = "need 1 <= l <= 8 and l*bg_bit <= 31"; return false; }
+    // the FP64 transforms stay exact after rounding only while the products are small enough:
+    // typical magnitude ~ sqrt(2 l N) * Bg/2 * 2^31 must leave a wide margin below 2^53
+    if ((uint64_t)2 * P.l * P.N * ((uint64_t)1 << (2 * P.bg_bit)) > ((uint64_t)1 << 30)) {
+        why = "need 2*l*N*Bg^2 <= 2^30 (exactness of the FP64 polynomial products)"; return false;
+    }
     if (P.ks_t < 1 || P.ks_basebit < 1 || P.ks_basebit > 4 || P.ks_t * P.ks_basebit > 16) {
         why = "need ks_basebit <= 4 and ks_t*ks_basebit <= 16"; return false;
     }

@@ -329,3 +329,28 @@ def test_maxpool_with_native_mux_matches_oracle_netlist_toy(toy_ctx, toy_keys):
         finally:
             toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
             toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
+
+
+# ------------------------------------------------------------------ other gadget and key-switch shapes
+@pytest.mark.parametrize("shape", [dict(n=64, N=256, l=2, bg_bit=10, ks_t=5, ks_basebit=3),
+                                   dict(n=80, N=512, l=4, bg_bit=6, ks_t=4, ks_basebit=4),
+                                   dict(n=48, N=1024, l=2, bg_bit=8, ks_t=16, ks_basebit=1)])
+def test_other_parameter_shapes_use_the_generic_key_switch(shape):
+    """Gadget lengths 1..4 and key-switch bases other than 4 (these take the select-and-subtract
+    key-switch kernel, not the MFMA one): gates and a native MUX, every word against the oracle."""
+    pkg = she()
+    K = O.keygen(O.Params(**shape), 77)
+    with pkg.Context(pkg.Params(**shape), 77, 256) as ctx:
+        bits, codes = S.gate_level(20, S.GATE_NAMES_5, 13)
+        in_ids = np.arange(40, dtype=np.uint32)
+        out_ids = np.arange(40, 60, dtype=np.uint32)
+        ctx.encrypt_bits(bits, 17, in_ids)
+        ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+        pool = np.zeros((64, shape["n"] + 1), np.uint32)
+        pool[:40] = O.encrypt_bits(K, bits, 17)
+        O.eval_gates(K, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
+        assert np.array_equal(ctx.read_cts(out_ids), pool[40:60])
+        assert ctx.decrypt(out_ids).tolist() == [plain(c, bits[2 * g], bits[2 * g + 1]) for g, c in enumerate(codes)]
+        ctx.eval_mux([0, 3], [1, 4], [2, 5], [60, 61])
+        for m, (s, a, b) in enumerate(((0, 1, 2), (3, 4, 5))):
+            assert np.array_equal(ctx.read_ct(60 + m), O.mux(K, pool[s], pool[a], pool[b]))

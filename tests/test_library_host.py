@@ -43,7 +43,8 @@ def test_bad_parameters_are_rejected_before_any_gpu_work(lib):
     import paper_1906_00148_amd as she
     from paper_1906_00148_amd.binding import _CParams
     h = ctypes.c_void_p()
-    for bad in (dict(k=2), dict(N=300), dict(n=0), dict(l=5, bg_bit=7), dict(ks_t=9, ks_basebit=2)):
+    for bad in (dict(k=2), dict(N=300), dict(n=0), dict(l=5, bg_bit=7), dict(ks_t=9, ks_basebit=2),
+                dict(N=1024, l=1, bg_bit=12)):
         kw = dict(n=128, N=256, k=1, bg_bit=7, l=3, ks_t=8, ks_basebit=2, lwe_std=2.0 ** -15, bk_std=2.0 ** -25)
         kw.update(bad)
         cp = _CParams(**kw)
