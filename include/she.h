@@ -135,8 +135,14 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
  * gate becomes a constant, its other operand, or that operand's complement, and complements are
  * absorbed into the next gate's code or applied as a free word-wise negation (Section 3.2: what
  * only re-wires ciphertexts costs no gate).  Results decrypt identically; gate counts drop. */
-enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2 };
+enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2, SHE_OPT_SPLIT_BELOW = 3 };
 int she_set_option(she_ctx *ctx, int option, int value);
+int she_get_option(she_ctx *ctx, int option, int *value);   /* SHE_EINVAL for an unknown option or a null pointer */
+/* SHE_OPT_SPLIT_BELOW (default: 6 x the device's compute units, 1536 on MI355X): a kernel launch of at
+ * most this many blind rotations spreads each one over two wavefronts (one per accumulator component),
+ * which shortens the serial chain per CMux when the level is too small to fill the chip; larger launches
+ * keep one wavefront per rotation.  0 never splits.  Every ciphertext comes out the same word for word
+ * either way (both kernels round exact integers). */
 /* SHE_OPT_NATIVE_MUX (default 0): she_maxpool evaluates every MUX of its comparators and selectors
  * with she_eval_mux's three-input gate instead of three 2-input gates (7w gates per max become
  * w gates + 2w MUX entries = 5w blind rotations and 3w key switches, and half the levels). */

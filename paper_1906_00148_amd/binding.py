@@ -75,6 +75,7 @@ def load_library() -> C.CDLL:
         "she_relu": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_set_option": (C.c_int, [ctx, C.c_int, C.c_int]),
+        "she_get_option": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_int)]),
         "she_plan_shift_acc": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, C.c_int, u64p,
                                          C.POINTER(C.c_uint32), u64p]),
         "she_plan_relu": (C.c_int, [C.c_uint32, C.c_uint32, C.c_int, u64p, C.POINTER(C.c_uint32), u64p]),
@@ -119,6 +120,7 @@ def _p(a, ty):
 
 OPT_FOLD_CONSTANTS = 1
 OPT_NATIVE_MUX = 2
+OPT_SPLIT_BELOW = 3
 
 
 def _options(fold: bool, native_mux: bool) -> int:
@@ -200,6 +202,11 @@ class Context:
 
     def set_option(self, option: int, value: int):
         self._check(self._L.she_set_option(self._h, option, value))
+
+    def get_option(self, option: int) -> int:
+        v = C.c_int(0)
+        self._check(self._L.she_get_option(self._h, option, C.byref(v)))
+        return int(v.value)
 
     def set_stream(self, hip_stream: int):
         self._check(self._L.she_set_stream(self._h, C.c_void_p(hip_stream)))

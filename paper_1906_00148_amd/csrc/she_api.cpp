@@ -46,6 +46,7 @@ struct she_ctx {
     bool track_round = false;
     bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
     bool native_mux = false;             // SHE_OPT_NATIVE_MUX
+    size_t split_below = 0;              // SHE_OPT_SPLIT_BELOW (set at creation: 6 x compute units)
     uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
     uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;
     size_t d_mux_cap = 0;
@@ -171,7 +172,8 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream));
+        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream,
+                                       false, cnt <= c->split_below));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
@@ -193,7 +195,7 @@ int enqueue_mux_level(she_ctx *c, const uint8_t *d_jtype, const uint32_t *d_jin0
         HIP_TRY(c, launch_lincomb(c->P, cs, d_jtype + 2 * off, d_jin0 + 2 * off, d_jin1 + 2 * off, 2 * cnt, c->work, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, nullptr, 2 * cnt, c->work,
-                                       c->track_round ? c->d_round_err : nullptr, c->stream, true));
+                                       c->track_round ? c->d_round_err : nullptr, c->stream, true, 2 * cnt <= c->split_below));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_mux_combine(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
         HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
@@ -351,6 +353,13 @@ int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, 
     c->stride = round_up(params->n + 1, 32);
     auto bail = [&](int code) { g_keygen_error = c->err; she_free(c.release()); return code; };
     if (hipGetDevice(&c->device) != hipSuccess) return bail(fail(c.get(), SHE_EDEVICE, "hipGetDevice"));
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1)
+            return bail(fail(c.get(), SHE_EDEVICE, "hipDeviceGetAttribute(multiprocessor count)"));
+        c->dk.cus = (uint32_t)cus;
+        c->split_below = 6 * (size_t)cus;
+    }
 
     try {
         generate_keys(c->P, seed, c->hk);
@@ -683,6 +692,21 @@ int she_set_option(she_ctx *c, int option, int value)
     if (!c) return SHE_EINVAL;
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
+    if (option == SHE_OPT_SPLIT_BELOW) {
+        if (value < 0) return fail(c, SHE_EINVAL, "SHE_OPT_SPLIT_BELOW takes a gate count >= 0");
+        c->split_below = (size_t)value;
+        return SHE_OK;
+    }
+    return fail(c, SHE_EINVAL, "unknown option");
+}
+
+int she_get_option(she_ctx *c, int option, int *value)
+{
+    if (!c) return SHE_EINVAL;
+    if (!value) return fail(c, SHE_EINVAL, "null argument");
+    if (option == SHE_OPT_FOLD_CONSTANTS) { *value = c->fold; return SHE_OK; }
+    if (option == SHE_OPT_NATIVE_MUX) { *value = c->native_mux; return SHE_OK; }
+    if (option == SHE_OPT_SPLIT_BELOW) { *value = (int)std::min<size_t>(c->split_below, 0x7FFFFFFF); return SHE_OK; }
     return fail(c, SHE_EINVAL, "unknown option");
 }
 

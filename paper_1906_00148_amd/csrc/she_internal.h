@@ -30,6 +30,7 @@ struct DeviceKeys {
     uint32_t ks_cols = 0;         // n+1 rounded up to 32
     double2 *twiddles = nullptr;  // [K-1][P][L]
     uint32_t ks_stride = 0;
+    uint32_t cus = 1;             // compute units of the device (launch shaping)
 };
 
 struct LevelWork {                // scratch of one level launch, sized for `gates` gates
@@ -53,7 +54,8 @@ hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t 
                           const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                                size_t gates, const LevelWork &W, unsigned *d_round_err /* nullptr = no tracking */,
-                               hipStream_t st, bool raw = false /* write W.raw_ext instead of digits and slots */);
+                               hipStream_t st, bool raw = false /* write W.raw_ext instead of digits and slots */,
+                               bool split = false /* two wavefronts per gate: for levels that leave the chip underfilled */);
 // MUX m: sample = raw_ext[2m] + raw_ext[2m+1] + (0, 1/8) -> key-switch digits, body and slot initialisation of gate m
 hipError_t launch_mux_combine(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                               size_t muxes, const LevelWork &W, hipStream_t st);

@@ -219,6 +219,176 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Blind rotation of a small level: one gate per workgroup of two wavefronts.
+// A level of a few hundred gates leaves most SIMDs with one wavefront or none, and the time of
+// the kernel above is then the latency of one wavefront's serial chain of 6 forward and 2
+// inverse transforms per CMux.  Here wavefront c of a gate owns accumulator component c: it
+// decomposes ACC_c, transforms its l digit polynomials, multiplies them with rows c*l..c*l+l-1
+// of the key for both output components, hands the partial spectrum of the other component to
+// its partner through LDS, and inverse-transforms its own component.  The chain per CMux is
+// l forward transforms, one exchange and one inverse transform.  Results are bit-identical to
+// k_blind_rotate's only up to FP64 summation order; both are exact after rounding.
+// ------------------------------------------------------------------------------------------
+// Workgroup barrier for LDS traffic only: earlier LDS operations of this wavefront are complete
+// (they finish in issue order, the counter reaches zero when the last one has), global loads
+// stay in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <class PL, bool TRACK, int GB>
+__global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
+    const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
+    const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
+    uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err, CtSpace cs,
+    const uint32_t *__restrict__ out_ids, uint32_t *__restrict__ raw_ext)
+{
+    constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N;
+    static_assert(PL::GPW == 1, "one transform per wavefront");
+    __shared__ uint32_t s_acc[2 * GB][N];
+    __shared__ double2 s_xch[2 * GB][PL::XSLOTS];
+    __shared__ double2 s_tw[TwTable<PL>::COUNT];
+
+    const int wave = threadIdx.x >> 6, t = threadIdx.x & 63;
+    const int c = wave & 1;                                               // component owned
+    // a wavefront pair past the end shadows the last gate and stores nothing: it still meets every barrier
+    const uint32_t g_raw = blockIdx.x * GB + (wave >> 1);
+    const bool live = g_raw < gates;
+    const uint32_t g = live ? g_raw : gates - 1;
+    load_twiddles<PL>(s_tw, tw_table);
+
+    LaneCtx<PL> lc;
+    lc.init(t, s_xch[wave], s_tw);
+    uint32_t *acc = s_acc[wave];
+    const double2 *theirs = s_xch[wave ^ 1];
+    const uint16_t *mybar = bar + (size_t)g * bar_stride;
+
+    // ACC = (0, X^(-bbar) * testv), testv = 1/8 on every coefficient
+    {
+        const uint32_t bbar = mybar[n];
+        for (int j = t; j < N; j += L) acc[j] = c == 0 ? 0u : ((((uint32_t)j + bbar) & N) ? 0u - (1u << 29) : (1u << 29));
+    }
+    wave_lds_fence();
+
+    const uint32_t Bg = 1u << bg_bit, half_bg = Bg >> 1;
+    uint32_t dec_off = 1u << (31 - l * bg_bit);
+    uint32_t flip = 0;
+    for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
+    float worst = 0.f;
+
+    // spectra of the key row in use, own output component first
+    const size_t row_elems = (size_t)2 * P * L;
+    const int mine_off = c * P * L + t, other_off = (c ^ 1) * P * L + t;
+    double2 bm[P], bo[P];
+    {
+        const double2 *row = bk_hat + (size_t)(c * l) * row_elems;
+#pragma unroll
+        for (int k = 0; k < P; k++) { bm[k] = row[mine_off + k * L]; bo[k] = row[other_off + k * L]; }
+    }
+    uint32_t abar_next = mybar[0];
+    for (uint32_t i = 0; i < n; i++) {
+        const uint32_t abar = abar_next;
+        abar_next = mybar[i + 1];                                          // i+1 == n reads bbar: harmless
+
+        double mr[P], mi[P], orr[P], oi[P];                                // partial spectra: own component, the other one
+#pragma unroll
+        for (int k = 0; k < P; k++) { mr[k] = mi[k] = orr[k] = oi[k] = 0.0; }
+
+        // D_c = X^abar * ACC_c - ACC_c at this lane's 2P coefficients
+        uint32_t dlo[P], dhi[P];
+#pragma unroll
+        for (int m = 0; m < P; m++) {
+            const uint32_t j0 = t + L * m, j1 = j0 + M;
+            const uint32_t s0 = (j0 - abar) & (2 * N - 1), s1 = (j1 - abar) & (2 * N - 1);
+            uint32_t v0 = acc[s0 & (N - 1)], v1 = acc[s1 & (N - 1)];
+            v0 = (s0 & N) ? 0u - v0 : v0;
+            v1 = (s1 & N) ? 0u - v1 : v1;
+            dlo[m] = (v0 - acc[j0] + dec_off) ^ flip;
+            dhi[m] = (v1 - acc[j1] + dec_off) ^ flip;
+        }
+        for (uint32_t p = 0; p < l; p++) {
+            const uint32_t sh = 32 - (p + 1) * bg_bit;
+            double xr[P], xi[P];
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                xr[m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], sh, bg_bit);
+                xi[m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], sh, bg_bit);
+            }
+            forward<PL>(lc, xr, xi);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < P; k++) {
+                mr[k] = __builtin_fma(-xi[k], bm[k].y, __builtin_fma(xr[k], bm[k].x, mr[k]));
+                mi[k] = __builtin_fma(xi[k], bm[k].x, __builtin_fma(xr[k], bm[k].y, mi[k]));
+                orr[k] = __builtin_fma(-xi[k], bo[k].y, __builtin_fma(xr[k], bo[k].x, orr[k]));
+                oi[k] = __builtin_fma(xi[k], bo[k].x, __builtin_fma(xr[k], bo[k].y, oi[k]));
+            }
+            // next row of this component: same step, or the first of the next step (the last row again at the end)
+            {
+                const uint32_t ni = (p + 1 < l) ? i : std::min(i + 1, n - 1), np = (p + 1 < l) ? p + 1 : 0;
+                const double2 *row = bk_hat + ((size_t)ni * 2 * l + c * l + np) * row_elems;
+#pragma unroll
+                for (int k = 0; k < P; k++) { bm[k] = row[mine_off + k * L]; bo[k] = row[other_off + k * L]; }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // hand the other component's partial spectrum to the partner, take the partner's for this one
+        wave_lds_fence();
+#pragma unroll
+        for (int k = 0; k < P; k++) lc.xch[k * PL::XROW + t] = make_double2(orr[k], oi[k]);
+        lds_barrier();
+#pragma unroll
+        for (int k = 0; k < P; k++) {
+            const double2 v = theirs[k * PL::XROW + t];
+            mr[k] += v.x; mi[k] += v.y;
+        }
+        lds_barrier();                                                      // the partner has read this buffer: free for the inverse
+        inverse<PL>(lc, mr, mi);
+#pragma unroll
+        for (int m = 0; m < P; m++) {
+            const double vr = mr[m], vi = mi[m];
+            if (TRACK) {
+                worst = fmaxf(worst, (float)fabs(vr - rint(vr)));
+                worst = fmaxf(worst, (float)fabs(vi - rint(vi)));
+            }
+            acc[t + L * m] += (uint32_t)__double2loint(vr + 6755399441055744.0);
+            acc[t + L * m + M] += (uint32_t)__double2loint(vi + 6755399441055744.0);
+        }
+        wave_lds_fence();
+    }
+
+    if (TRACK && round_err) atomicMax(round_err, __float_as_uint(worst));
+
+    // sample extraction: wavefront 0 holds A (mask a''_0 = A_0, a''_j = -A_{N-j}), wavefront 1 holds B (body b'' = B_0)
+    if (!live) return;
+    if (raw_ext) {
+        uint32_t *dst = raw_ext + (size_t)g * (N + 1);
+        if (c == 0) {
+            for (int j = t; j < N; j += L) dst[j] = (j == 0) ? acc[0] : 0u - acc[N - j];
+        } else if (t == 0) {
+            dst[N] = acc[0];
+        }
+    } else if (c == 0) {
+        const uint32_t rnd = 1u << (31 - ks_bits), sh = 32 - ks_bits;
+        uint16_t *dst = ksd + ((size_t)(g / KS_GROUP) * N) * KS_GROUP + (g % KS_GROUP);
+        for (int j = t; j < N; j += L) {
+            const uint32_t a = (j == 0) ? acc[0] : 0u - acc[N - j];
+            dst[(size_t)j * KS_GROUP] = (uint16_t)((a + rnd) >> sh);
+        }
+    } else {
+        const uint32_t body = acc[0];
+        if (t == 0) ext_b[g] = body;
+        if (out_ids) {                       // the key switch subtracts its rows from (0, b'')
+            uint32_t *o = ct_ptr(cs, out_ids[g]);
+            for (uint32_t w = t; w <= n; w += L) o[w] = (w == n) ? body : 0u;
+        }
+    }
+}
+
 // Second half of a native MUX: the two rotations' samples are added, 1/8 goes on the body, and the
 // sum is prepared for the key switch exactly as the blind rotation's epilogue prepares a gate.
 __global__ __launch_bounds__(256) void k_mux_combine(const uint32_t *__restrict__ raw_ext, uint32_t N, uint32_t n,
@@ -495,11 +665,28 @@ hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t 
 template <class PL>
 static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_t gates, const LevelWork &W,
                                  unsigned *d_round_err, const CtSpace &cs, const uint32_t *d_out, hipStream_t st,
-                                 uint32_t *raw_ext)
+                                 uint32_t *raw_ext, bool split)
 {
+    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
+    if (split) {
+        // One gate (two wavefronts) or two gates per workgroup.  Measured at n=630, N=1024 on 256 compute units, in ms
+        // for 256 / 512 / 768 / 1024 / 1280 / 1536 gates: one per workgroup 3.4 / 5.1 / 5.3 / 6.2 / 9.2 / 12.1, two per
+        // workgroup 4.2 / 4.2 / 6.2 / 6.3 / 10.1 / 9.8 (the unsplit kernel: 6.5 up to 1024 gates, 10.4 to 11.1 beyond).
+        // What counts is the wavefronts on the fullest compute unit; two workgroups of one gate share a SIMD pair badly.
+        const size_t per_cu = (gates + K.cus - 1) / std::max<uint32_t>(K.cus, 1);
+        const bool two = per_cu == 2 || per_cu == 6;
+        const dim3 grid((unsigned)(two ? (gates + 1) / 2 : gates)), block(two ? 256 : 128);
+#define SHE_LAUNCH_SPLIT(TRACK, GB)                                                                                   \
+    hipLaunchKernelGGL((k_blind_rotate_split<PL, TRACK, GB>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l,      \
+                       P.bg_bit, K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs,     \
+                       d_out, raw_ext)
+        if (d_round_err) { if (two) SHE_LAUNCH_SPLIT(true, 2); else SHE_LAUNCH_SPLIT(true, 1); }
+        else { if (two) SHE_LAUNCH_SPLIT(false, 2); else SHE_LAUNCH_SPLIT(false, 1); }
+#undef SHE_LAUNCH_SPLIT
+        return hipGetLastError();
+    }
     const uint32_t per_block = BR_WAVES * PL::GPW;
     const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
-    const uint32_t ks_bits = P.ks_t * P.ks_basebit;
     if (d_round_err)
         hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
                            K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
@@ -510,15 +697,15 @@ static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_
 }
 
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
-                               size_t gates, const LevelWork &W, unsigned *d_round_err, hipStream_t st, bool raw)
+                               size_t gates, const LevelWork &W, unsigned *d_round_err, hipStream_t st, bool raw, bool split)
 {
     if (!gates) return hipSuccess;
     if (!K.ks_bytes) d_out = nullptr;      // the generic key switch writes the slot itself
     uint32_t *raw_ext = raw ? W.raw_ext : nullptr;
     switch (P.N) {
-    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
-    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
-    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext);
+    case 256: return blind_rotate_t<Plan256>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext, split);
+    case 512: return blind_rotate_t<Plan512>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext, split);
+    case 1024: return blind_rotate_t<Plan1024>(P, K, gates, W, d_round_err, cs, d_out, st, raw_ext, split);
     }
     return hipErrorInvalidValue;
 }

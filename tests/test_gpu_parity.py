@@ -126,6 +126,32 @@ def test_gates_on_bootstrapped_inputs_chain_toy(toy_ctx, toy_keys):
         cur_id = nid
 
 
+def test_both_blind_rotation_kernels_on_ragged_launches_toy(toy_ctx, toy_keys):
+    # 601 gates: launches of 1 / 130 / 301 / 601 gates put one gate (two wavefronts) or two gates in a
+    # workgroup of the split kernel, with a dangling wavefront pair at odd counts; every word against the oracle
+    pkg = she()
+    G = 601
+    bits, codes = S.gate_level(G, S.GATE_NAMES_5, 11)
+    in_ids = np.arange(2 * G, dtype=np.uint32)
+    out_ids = np.arange(2 * G, 3 * G, dtype=np.uint32)
+    toy_ctx.encrypt_bits(bits, 4242, in_ids)
+    pool = np.zeros((3 * G, toy_keys.params.n + 1), np.uint32)
+    pool[: 2 * G] = O.encrypt_bits(toy_keys, bits, 4242)
+    O.eval_gates(toy_keys, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=16)
+    default_split = toy_ctx.get_option(pkg.OPT_SPLIT_BELOW)
+    try:
+        for split_below in (0, 1 << 30):
+            toy_ctx.set_option(pkg.OPT_SPLIT_BELOW, split_below)
+            for count in (601, 1, 130, 301):
+                scratch = np.arange(3 * G, 3 * G + count, dtype=np.uint32)
+                toy_ctx.eval_gates(codes[:count], in_ids[0:2 * count:2], in_ids[1:2 * count:2], scratch)
+                assert np.array_equal(toy_ctx.read_cts(scratch), pool[2 * G:2 * G + count]), (split_below, count)
+    finally:
+        toy_ctx.set_option(pkg.OPT_SPLIT_BELOW, default_split)
+    with pytest.raises(pkg.SheError):
+        toy_ctx.set_option(pkg.OPT_SPLIT_BELOW, -1)
+
+
 # ------------------------------------------------------------------ config 2: real parameters
 def test_cfg2_real_level(real_ctx, real_keys):
     G = 4096
@@ -152,9 +178,26 @@ def test_cfg2_real_level(real_ctx, real_keys):
     O.eval_gates(real_keys, pool, codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub], threads=16)
     got = real_ctx.read_cts(out_ids[sub])
     assert np.array_equal(got, pool[out_ids[sub]])
-    # the production kernel (tracking off) gives the same words
-    real_ctx.eval_gates(codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub])
-    assert np.array_equal(real_ctx.read_cts(out_ids[sub]), pool[out_ids[sub]])
+    # the production kernels (tracking off) give the same words: one wavefront per gate, then two
+    pkg = she()
+    default_split = real_ctx.get_option(pkg.OPT_SPLIT_BELOW)
+    assert default_split >= 1024          # six per compute unit
+    try:
+        for split_below in (0, 1 << 30):
+            real_ctx.set_option(pkg.OPT_SPLIT_BELOW, split_below)
+            real_ctx.eval_gates(codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub])
+            assert np.array_equal(real_ctx.read_cts(out_ids[sub]), pool[out_ids[sub]]), split_below
+        # and the split kernel with tracking on, on a launch that puts two gates in a workgroup
+        real_ctx.set_round_tracking(True)
+        real_ctx.get_round_error(reset=True)
+        first = np.arange(300)
+        real_ctx.eval_gates(codes[first], in_ids[0::2][first], in_ids[1::2][first], out_ids[first])
+        assert 0 < real_ctx.get_round_error() < 0.2
+        assert np.array_equal(real_ctx.decrypt(out_ids[first]), want_bits[first])
+        assert np.array_equal(real_ctx.read_cts(out_ids[sub]), pool[out_ids[sub]])
+    finally:
+        real_ctx.set_round_tracking(False)
+        real_ctx.set_option(pkg.OPT_SPLIT_BELOW, default_split)
 
 
 # ------------------------------------------------------------------ layer operators, toy parameters, ciphertext level
@@ -295,7 +338,20 @@ def test_folded_operators_match_folded_oracle_netlists_toy(toy_ctx, toy_keys):
 
 
 # ------------------------------------------------------------------ native MUX
-def test_eval_mux_bit_exact_toy_and_real(toy_ctx, toy_keys, real_ctx, real_keys):
+@pytest.mark.parametrize("split_below", [0, 1 << 30])
+def test_eval_mux_bit_exact_toy_and_real(toy_ctx, toy_keys, real_ctx, real_keys, split_below):
+    pkg = she()
+    default_split = toy_ctx.get_option(pkg.OPT_SPLIT_BELOW)
+    for ctx in (toy_ctx, real_ctx):
+        ctx.set_option(pkg.OPT_SPLIT_BELOW, split_below)
+    try:
+        _check_eval_mux(toy_ctx, toy_keys, real_ctx, real_keys)
+    finally:
+        for ctx in (toy_ctx, real_ctx):
+            ctx.set_option(pkg.OPT_SPLIT_BELOW, default_split)
+
+
+def _check_eval_mux(toy_ctx, toy_keys, real_ctx, real_keys):
     for ctx, K, reps in ((toy_ctx, toy_keys, 5), (real_ctx, real_keys, 1)):
         combos = [(s, a, b) for s in (0, 1) for a in (0, 1) for b in (0, 1)] * reps
         bits = np.array(combos, np.uint8).ravel()
