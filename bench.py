@@ -115,6 +115,57 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False):
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
 
 
+def network(ctx_factory):
+    """A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
+    network's layer sequence, shrunk), chained on the device without decrypting in between; folding and native MUX on."""
+    import numpy as np
+
+    import synth_inputs as S
+    from paper_1906_00148_amd.layers import Chain
+
+    img, w1, w2, w3 = S.cfg6_network()
+
+    def conv_plain(x, sign, exp):
+        k = sign.shape[1]
+        oh, ow = x.shape[0] - k + 1, x.shape[1] - k + 1
+        out = np.zeros((oh, ow, sign.shape[0]), np.int64)
+        for dy in range(k):
+            for dx in range(k):
+                for ci in range(x.shape[2]):
+                    out += (x[dy:dy + oh, dx:dx + ow, ci, None] >> -exp[None, None, :, dy, dx, ci].astype(np.int64)) \
+                        * sign[None, None, :, dy, dx, ci]
+        return ((out + 32768) % 65536) - 32768
+
+    def pool_plain(x):
+        x = np.maximum(x, 0)[: x.shape[0] // 2 * 2, : x.shape[1] // 2 * 2]
+        return np.maximum(np.maximum(x[0::2, 0::2], x[0::2, 1::2]), np.maximum(x[1::2, 0::2], x[1::2, 1::2]))
+
+    feat = pool_plain(conv_plain(pool_plain(conv_plain(img[..., None], *w1)), *w2)).reshape(-1)
+    want = ((feat[None, :] >> -w3[1].astype(np.int64)) * w3[0]).sum(axis=1)
+    want = ((want + 32768) % 65536) - 32768
+
+    ctx = ctx_factory(32768)
+    ctx.set_option(1, 1)
+    ctx.set_option(2, 1)
+    bits = ((img[..., None, None] >> np.arange(8)) & 1).astype(np.uint8)
+    x_ids = np.arange(bits.size, dtype=np.uint32).reshape(bits.shape)
+    ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
+    net = Chain(ctx, x_ids.size)
+    t0 = time.perf_counter()
+    a = net.maxpool(net.relu(net.conv(x_ids, w1[0], w1[1], 16)))
+    b = net.maxpool(net.relu(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16)))
+    scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
+    dt = time.perf_counter() - t0
+    dec = ctx.decrypt(scores).astype(np.int64)
+    got = (dec << np.arange(16)).sum(axis=1)
+    got = np.where(got >= 32768, got - 65536, got)
+    assert np.array_equal(got, want), "network decrypts wrongly"
+    ctx.close()
+    return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
+                        "constant folding and native MUX on", "latency_s": dt, "entries": int(net.gates),
+            "entries_per_s": net.gates / dt}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,6 +251,7 @@ def main():
     if not args.no_conv_layer:
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
         out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True)
+        out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))

@@ -62,6 +62,28 @@ def plain_maxpool2x2(x: np.ndarray) -> np.ndarray:
     return np.maximum(np.maximum(x[0::2, 0::2], x[0::2, 1::2]), np.maximum(x[1::2, 0::2], x[1::2, 1::2]))
 
 
+def plain_conv(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int) -> np.ndarray:
+    """Valid stride-1 convolution of x[H][W][C] (unsigned) with shift weights [OC][k][k][C]:
+    out[y][x][o] = sum sign * (pixel >> |exp|), wrapped to acc_bits (signed)."""
+    x = np.asarray(x, np.int64)
+    OC, k = w_sign.shape[0], w_sign.shape[1]
+    oh, ow = x.shape[0] - k + 1, x.shape[1] - k + 1
+    out = np.zeros((oh, ow, OC), np.int64)
+    for yy in range(oh):
+        for xx in range(ow):
+            patch = x[yy:yy + k, xx:xx + k, :]
+            for o in range(OC):
+                out[yy, xx, o] = plain_shift_acc(patch.reshape(1, -1), w_sign[o].reshape(1, -1), w_exp[o].reshape(1, -1), acc_bits)[0]
+    return out
+
+
+def plain_network(img, w1, w2, w3, acc_bits: int = 16) -> np.ndarray:
+    """conv - ReLU - pool - conv - ReLU - pool - dense with shift weights; the class scores (signed)."""
+    a = plain_maxpool2x2(plain_relu(plain_conv(np.asarray(img)[..., None], w1[0], w1[1], acc_bits)))
+    b = plain_maxpool2x2(plain_relu(plain_conv(a, w2[0], w2[1], acc_bits)))
+    return plain_shift_acc(np.broadcast_to(b.reshape(1, -1), (w3[0].shape[0], b.size)), w3[0], w3[1], acc_bits)
+
+
 def to_bits(v: np.ndarray, bits: int) -> np.ndarray:
     """two's-complement bits, LSB first, new last axis"""
     v = np.asarray(v, np.int64) & ((1 << bits) - 1)

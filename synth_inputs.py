@@ -64,6 +64,19 @@ def cfg5_conv_layer(H: int = 28, W: int = 28, out_ch: int = 8, ksize: int = 3, s
     return img, sign, exp
 
 
+def cfg6_network(size: int = 14, ch1: int = 4, ch2: int = 4, classes: int = 10, seed: int | None = None):
+    """A small conv - ReLU - pool - conv - ReLU - pool - dense network on one 8-bit image (the layer
+    sequence of the MNIST network, shrunk): image [size][size], conv kernels [ch1][3][3][1] and
+    [ch2][3][3][ch1], dense weights [classes][features], all log-quantized (sign, exponent)."""
+    rng = np.random.default_rng(data_seed(6) if seed is None else seed)
+    img = rng.integers(0, 256, (size, size)).astype(np.int64)
+    w1 = log_weights((ch1, 3, 3, 1), rng, 7)
+    w2 = log_weights((ch2, 3, 3, ch1), rng, 7)
+    side = ((size - 2) // 2 - 2) // 2
+    w3 = log_weights((classes, side * side * ch2), rng, 7)
+    return img, w1, w2, w3
+
+
 def subset(total: int, count: int, seed: int) -> np.ndarray:
     """Sorted seeded sample of `count` indices out of `total` (for spot checks)."""
     rng = np.random.default_rng(seed)

@@ -143,3 +143,32 @@ def test_cfg5_conv_layer_full(fold):
         assert np.array_equal(OC.from_bits(c.decrypt(conv_ids.reshape(-1, 16)[sub]), True), conv.reshape(-1)[sub])
         want = OC.plain_maxpool2x2(OC.plain_relu(conv))
         assert np.array_equal(OC.from_bits(c.decrypt(pool_ids), True), want)
+
+
+def test_chained_network_conv_relu_pool_conv_relu_pool_dense(ctx):
+    # seven layers on ciphertexts that stay on the device; only the ten class scores are decrypted
+    import time
+
+    import paper_1906_00148_amd as pkg
+    from paper_1906_00148_amd.layers import Chain
+    img, w1, w2, w3 = S.cfg6_network()
+    for fold, native_mux in ((0, 0), (1, 1)):
+        ctx.set_option(pkg.OPT_FOLD_CONSTANTS, fold)
+        ctx.set_option(pkg.OPT_NATIVE_MUX, native_mux)
+        try:
+            x_ids = encrypt_values(ctx, img[..., None], 8, S.data_seed(6))
+            net = Chain(ctx, x_ids.size)
+            t0 = time.perf_counter()
+            a = net.maxpool(net.relu(net.conv(x_ids, w1[0], w1[1], 16)))
+            b = net.maxpool(net.relu(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16)))
+            scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
+            dt = time.perf_counter() - t0
+            got = OC.from_bits(ctx.decrypt(scores), True)
+            print(f"\nnetwork (fold={fold}, native_mux={native_mux}): {net.gates} gates, {dt:.2f} s, scores {got.tolist()}")
+            assert np.array_equal(got, OC.plain_network(img, w1, w2, w3))
+            # an intermediate layer too: the first pooled feature map
+            assert np.array_equal(OC.from_bits(ctx.decrypt(a), True),
+                                  OC.plain_maxpool2x2(OC.plain_relu(OC.plain_conv(img[..., None], w1[0], w1[1], 16))))
+        finally:
+            ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
+            ctx.set_option(pkg.OPT_NATIVE_MUX, 0)

@@ -6,6 +6,7 @@ import itertools
 import numpy as np
 import pytest
 
+import synth_inputs as S
 from oracle import circuits as C
 from oracle import tfhe
 
@@ -255,3 +256,21 @@ def test_max_with_native_mux():
     nl = C.Netlist(32, False, True)
     C.max_signed(nl, list(range(16)), list(range(16, 32)))
     assert (len(nl.gtype), nl.rotations, int(nl.levels().max())) == (48, 80, 18)      # 16 XNOR + 32 MUX
+
+
+def test_plain_conv_against_scipy_correlation_and_network_shapes():
+    # with all exponents 0 a shift-weight convolution is a correlation with a +-1 kernel
+    from scipy.signal import correlate
+    rng = np.random.default_rng(8)
+    x = rng.integers(0, 256, (7, 6, 3))
+    sign = rng.choice(np.array([-1, 1], np.int8), (2, 3, 3, 3))
+    got = C.plain_conv(x, sign, np.zeros_like(sign), 16)
+    for o in range(2):
+        want = correlate(x, sign[o].astype(np.int64), mode="valid")[:, :, 0]
+        assert np.array_equal(got[:, :, o], want)
+    # shifts floor each term before the sum
+    one = C.plain_conv(np.full((3, 3, 1), 7), np.ones((1, 3, 3, 1), np.int8), np.full((1, 3, 3, 1), -1, np.int8), 16)
+    assert one.tolist() == [[[27]]]
+    img, w1, w2, w3 = S.cfg6_network()
+    scores = C.plain_network(img, w1, w2, w3)
+    assert scores.shape == (10,) and w3[0].shape == (10, 2 * 2 * 4)
