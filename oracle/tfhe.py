@@ -118,6 +118,12 @@ def lib() -> C.CDLL:
         L.orc_mux.argtypes = [pp, u32p, u32p, C.c_int, C.c_int, u32p, u32p, u32p, u32p]
         L.orc_eval_netlist.restype = C.c_int
         L.orc_eval_netlist.argtypes = [pp, u32p, u32p, u32p, u32p, u32p, u32p, u32p, u32p, C.c_size_t, C.c_int]
+        L.orc_trgsw_encrypt_bits.restype = C.c_int
+        L.orc_trgsw_encrypt_bits.argtypes = [pp, u8p, u8p, C.c_size_t, C.c_uint64, C.c_double, u32p]
+        L.orc_trlwe_encrypt.restype = C.c_int
+        L.orc_trlwe_encrypt.argtypes = [pp, u8p, u32p, C.c_size_t, C.c_uint64, C.c_double, u32p]
+        L.orc_cmux.restype = None
+        L.orc_cmux.argtypes = [pp, u32p, u32p, u32p, u32p]
         L.orc_eval_gates.restype = C.c_int
         L.orc_eval_gates.argtypes = [pp, u32p, u32p, u32p, u8p, u32p, u32p, u32p, C.c_size_t, C.c_int]
         _lib = L
@@ -218,6 +224,49 @@ def trlwe_phase(ring_key, acc) -> np.ndarray:
     ring_key, acc = _u8(ring_key), _u32(acc).reshape(2, -1)
     out = np.zeros(acc.shape[1], np.uint32)
     lib().orc_trlwe_phase(acc.shape[1], _p8(ring_key), _p32(acc), _p32(out))
+    return out
+
+
+# ---------------------------------------------------------------- leveled mode
+def trgsw_encrypt_bits(K, bits, seed: int, sigma: float | None = None) -> np.ndarray:
+    """Fresh TRGSW samples [count][2][l][2][N] of bits under the ring key (noise: bk_std unless given)."""
+    P = K.params
+    bits = _u8(bits).ravel()
+    out = np.zeros((bits.size, 2, P.l, 2, P.N), np.uint32)
+    cp = P.c()
+    rc = lib().orc_trgsw_encrypt_bits(C.byref(cp), _p8(K.ring_key), _p8(bits), bits.size, seed,
+                                      P.bk_std if sigma is None else sigma, _p32(out))
+    assert rc == 0
+    return out
+
+
+def trlwe_encrypt(K, mu, seed: int, sigma: float | None = None) -> np.ndarray:
+    """Fresh TRLWE samples [count][2][N] of the torus polynomials mu[count][N]."""
+    P = K.params
+    mu = _u32(mu).reshape(-1, P.N)
+    out = np.zeros((mu.shape[0], 2, P.N), np.uint32)
+    cp = P.c()
+    rc = lib().orc_trlwe_encrypt(C.byref(cp), _p8(K.ring_key), _p32(mu), mu.shape[0], seed,
+                                 P.bk_std if sigma is None else sigma, _p32(out))
+    assert rc == 0
+    return out
+
+
+def trlwe_trivial(P: Params, mu) -> np.ndarray:
+    """Noiseless samples (0, mu): plaintext constants."""
+    mu = _u32(mu).reshape(-1, P.N)
+    out = np.zeros((mu.shape[0], 2, P.N), np.uint32)
+    out[:, 1] = mu
+    return out
+
+
+def cmux(P: Params, sel, d1, d0) -> np.ndarray:
+    """d0 + sel [.] (d1 - d0) for one TRGSW selector and two TRLWE samples."""
+    sel, d1, d0 = _u32(sel), _u32(d1).reshape(2, P.N), _u32(d0).reshape(2, P.N)
+    assert sel.size == 2 * P.l * 2 * P.N
+    out = np.zeros((2, P.N), np.uint32)
+    cp = P.c()
+    lib().orc_cmux(C.byref(cp), _p32(sel), _p32(d1), _p32(d0), _p32(out))
     return out
 
 

@@ -26,6 +26,12 @@
  * paper (it prints no ciphertext values).  Everything else is pinned by the
  * CPU tests: X^N = -1, brute-force products, gadget reconstruction, phase
  * identities, gate truth tables and the analytic noise bound.
+ *
+ * Leveled mode (Section 4, "TFHE setting": all three sample levels are used
+ * without bootstrapping): fresh TRGSW samples of bits, TRLWE samples of torus
+ * polynomials and the CMux  d0 + C [.] (d1 - d0)  built on the same external
+ * product as the blind rotation.  Pinned by: selection of the right message,
+ * the exact phase identity for a noiseless selector, and the noise bound.
  */
 #include <math.h>
 #include <stdint.h>
@@ -47,7 +53,8 @@ typedef struct {
 enum { ORC_NAND, ORC_AND, ORC_OR, ORC_XOR, ORC_XNOR, ORC_NOR, ORC_ANDNY, ORC_ANDYN, ORC_ORNY, ORC_ORYN,
        ORC_NGATES };
 
-enum { TAG_LWE_KEY = 1, TAG_RING_KEY = 2, TAG_BK_ROW = 3, TAG_KS_ROW = 4, TAG_FRESH = 5 };
+enum { TAG_LWE_KEY = 1, TAG_RING_KEY = 2, TAG_BK_ROW = 3, TAG_KS_ROW = 4, TAG_FRESH = 5, TAG_TRGSW_ROW = 6,
+       TAG_TRLWE = 7 };
 
 /* ------------------------------------------------------------------------- */
 /* Random streams.  One stream per object, addressed by (seed, tag, index);   */
@@ -238,6 +245,59 @@ void orc_trlwe_phase(uint32_t N, const uint8_t *ring_key, const uint32_t *acc /*
 }
 
 /* ------------------------------------------------------------------------- */
+/* Leveled mode: TRGSW selectors, TRLWE data, CMux                             */
+/* ------------------------------------------------------------------------- */
+
+/* Fresh TRGSW samples of bits under the ring key.  Sample k has the layout of
+ * one BK_i, [c<2][p<l][comp<2][N]: row (c,p) is a TRLWE encryption of zero with
+ * noise sigma, stream (seed, TAG_TRGSW_ROW, (k*2+c)*l+p) (words 0..N-1 the mask,
+ * word N+2j the Gaussian of body coefficient j), plus bit*2^(32-(p+1)*bg_bit)
+ * on coefficient 0 of component c. */
+int orc_trgsw_encrypt_bits(const orc_params *P, const uint8_t *ring_key, const uint8_t *bits, size_t count,
+                           uint64_t seed, double sigma, uint32_t *out /* [count][2][l][2][N] */)
+{
+    if (!params_ok(P)) return -1;
+    const uint32_t N = P->N, l = P->l;
+    uint32_t *sp = (uint32_t *)malloc(sizeof(uint32_t) * N);
+    if (!sp) return -2;
+    for (uint32_t j = 0; j < N; j++) sp[j] = ring_key[j];
+    for (size_t k = 0; k < count; k++)
+        for (uint32_t c = 0; c < 2; c++)
+            for (uint32_t p = 0; p < l; p++) {
+                uint64_t row = ((uint64_t)k * 2 + c) * l + p;
+                uint64_t key = orc_stream_key(seed, TAG_TRGSW_ROW, row);
+                uint32_t *A = out + row * 2 * N, *B = A + N;
+                for (uint32_t j = 0; j < N; j++) A[j] = stream_torus(key, j);
+                orc_negacyclic_mul(N, A, sp, B);
+                for (uint32_t j = 0; j < N; j++) B[j] += orc_gaussian32(key, N + 2 * (uint64_t)j, sigma);
+                if (bits[k]) (c == 0 ? A : B)[0] += 1u << (32 - (p + 1) * P->bg_bit);
+            }
+    free(sp);
+    return 0;
+}
+
+/* Fresh TRLWE samples of torus polynomials mu_k: A uniform from stream
+ * (seed, TAG_TRLWE, k) words 0..N-1, B = A (*) s' + mu + E with E_j from word N+2j. */
+int orc_trlwe_encrypt(const orc_params *P, const uint8_t *ring_key, const uint32_t *mu /* [count][N] */, size_t count,
+                      uint64_t seed, double sigma, uint32_t *out /* [count][2][N] */)
+{
+    if (!params_ok(P)) return -1;
+    const uint32_t N = P->N;
+    uint32_t *sp = (uint32_t *)malloc(sizeof(uint32_t) * N);
+    if (!sp) return -2;
+    for (uint32_t j = 0; j < N; j++) sp[j] = ring_key[j];
+    for (size_t k = 0; k < count; k++) {
+        uint64_t key = orc_stream_key(seed, TAG_TRLWE, k);
+        uint32_t *A = out + k * 2 * N, *B = A + N;
+        for (uint32_t j = 0; j < N; j++) A[j] = stream_torus(key, j);
+        orc_negacyclic_mul(N, A, sp, B);
+        for (uint32_t j = 0; j < N; j++) B[j] += mu[k * N + j] + orc_gaussian32(key, N + 2 * (uint64_t)j, sigma);
+    }
+    free(sp);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Gate = linear combination + bootstrap                                       */
 /* ------------------------------------------------------------------------- */
 
@@ -311,6 +371,18 @@ void orc_external_product(const orc_params *P, const uint32_t *G, const uint32_t
             }
     }
     free(dig); free(prod);
+}
+
+/* CMux: out = d0 + C [.] (d1 - d0); encrypts the message of d1 if C encrypts 1, of d0 if 0.
+ * C is one TRGSW sample [2][l][2][N], d1 / d0 / out are TRLWE samples [2][N] (out may alias neither). */
+void orc_cmux(const orc_params *P, const uint32_t *C, const uint32_t *d1, const uint32_t *d0, uint32_t *out)
+{
+    const uint32_t N = P->N;
+    uint32_t *D = (uint32_t *)malloc(sizeof(uint32_t) * 2 * N);
+    for (uint32_t j = 0; j < 2 * N; j++) D[j] = d1[j] - d0[j];
+    orc_external_product(P, C, D, out);
+    for (uint32_t j = 0; j < 2 * N; j++) out[j] += d0[j];
+    free(D);
 }
 
 /* ACC <- (0, X^(-bbar) * testv), testv = mu on every coefficient;

@@ -172,3 +172,19 @@ def test_chained_network_conv_relu_pool_conv_relu_pool_dense(ctx):
         finally:
             ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
             ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
+
+
+def test_paper_bitwidths_five_bit_inputs_mixed_width_tree(ctx):
+    # Section 3.3's shape: 5-bit inputs, tree level j adds (5+j)-bit numbers, 16-bit accumulator; 64 neurons of 25 terms
+    rng = np.random.default_rng(S.data_seed(7))
+    units, terms, b = 64, 25, 5
+    x = rng.integers(0, 1 << b, (units, terms))
+    sign, exp = S.log_weights((units, terms), rng, b - 1)
+    ids = encrypt_values(ctx, x, b, S.data_seed(7))
+    out = np.arange(250000, 250000 + units * 16, dtype=np.uint32).reshape(units, 16)
+    gates = ctx.shift_acc(ids, sign, exp, 16, out)
+    nl, _ = OC.build_shift_acc(units, terms, b, sign, exp, 16)
+    wide, _ = OC.build_shift_acc(units, terms, 16, sign, exp, 16)       # every adder 16 bits wide
+    assert gates == len(nl.gtype) and gates < 0.6 * len(wide.gtype)
+    assert np.array_equal(OC.from_bits(ctx.decrypt(out), True), OC.plain_shift_acc(x, sign, exp, 16))
+    print(f"\nb=5: {gates} gates mixed-width against {len(wide.gtype)} with 16-bit adders throughout")
