@@ -164,6 +164,47 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
 int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
                      uint64_t *rotations);
 
+/* ---- leveled mode (Section 4, "TFHE setting": the three sample levels TLWE / TRLWE / TRGSW used
+ * without bootstrapping) ----
+ * Selector bits are TRGSW samples, data are TRLWE samples of torus polynomials, and the one
+ * homomorphic operation is the CMux  out = d0 + C [.] (d1 - d0)  (the external product of the
+ * blind rotation's inner step): out carries d1's message if C encrypts 1 and d0's if 0, and the
+ * noise grows additively per CMux instead of being reset.  Lookup tables and decision trees
+ * evaluate as levels of CMuxes.  Both kinds of sample live in device pools of their own, addressed
+ * by 32-bit ids: TRGSW samples in the kernels' spectral form (2l x 2 spectra of N/2 complex
+ * doubles), TRLWE samples as [2][N] Torus32 words (mask polynomial, body polynomial). */
+
+/* Allocates (or re-allocates, dropping the contents) the two pools.  SHE_EINVAL for a zero capacity. */
+int she_leveled_init(she_ctx *ctx, uint32_t trgsw_capacity, uint32_t trlwe_capacity);
+
+/* Fresh TRGSW samples of bits[0..count) under the ring key with noise bk_std; sample k has the
+ * layout of one bootstrapping-key entry, rows (c, p) = TRLWE samples of zero from noise stream
+ * (seed, (k*2+c)*l+p) plus bits[k] * 2^(32-(p+1)*bg_bit) on coefficient 0 of component c, and is
+ * stored, transformed, in selector slot dst_ids[k].  SHE_EINVAL before she_leveled_init or for a
+ * bit other than 0/1, SHE_ERANGE for an id outside the selector pool. */
+int she_trgsw_encrypt_bits(she_ctx *ctx, const uint8_t *bits, size_t count, uint64_t seed, const uint32_t *dst_ids);
+
+/* Fresh TRLWE samples of the torus polynomials mu[count][N] (noise bk_std, stream (seed, k)) into
+ * data slots dst_ids[k]. */
+int she_trlwe_encrypt(she_ctx *ctx, const uint32_t *mu, size_t count, uint64_t seed, const uint32_t *dst_ids);
+
+/* Copies samples[count][2][N] into / out of data slots (a noiseless constant is the sample (0, mu)). */
+int she_trlwe_write(she_ctx *ctx, const uint32_t *samples, size_t count, const uint32_t *dst_ids);
+int she_trlwe_read(she_ctx *ctx, const uint32_t *ids, size_t count, uint32_t *samples);
+
+/* Decryption side: phases[k][N] = B - A (*) s' of data slot ids[k], with the ring key of the context. */
+int she_trlwe_phase(she_ctx *ctx, const uint32_t *ids, size_t count, uint32_t *phases);
+
+/* ONE level of `count` mutually independent CMuxes: data slot out[m] <- selector sel[m] ? data slot
+ * in1[m] : data slot in0[m].  Per entry: gadget decomposition of in1 - in0 (signed digits, rounded
+ * to nearest), 2l forward transforms, 2l x 2 pointwise products with the selector's spectra, two
+ * inverse transforms, addition of in0.  Results are exact integers (the same rounding argument as
+ * the blind rotation).  No out id may equal an in1 / in0 id of the same call or another out id
+ * (SHE_EINVAL); ids outside their pools give SHE_ERANGE.  she_last_timing then reports the kernel's
+ * time in ms[1]. */
+int she_eval_cmux(she_ctx *ctx, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
+                  size_t count);
+
 /* ---- diagnostics and plumbing (not part of the paper's problem statement) ---- */
 
 /* Copies slot `id` to dst[0..n] (a_0..a_{n-1}, b) / overwrites it from src. */

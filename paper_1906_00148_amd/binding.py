@@ -82,6 +82,13 @@ def load_library() -> C.CDLL:
         "she_plan_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
                                        C.POINTER(C.c_uint32), u64p]),
         "she_eval_mux": (C.c_int, [ctx, u32p, u32p, u32p, u32p, C.c_size_t]),
+        "she_leveled_init": (C.c_int, [ctx, C.c_uint32, C.c_uint32]),
+        "she_trgsw_encrypt_bits": (C.c_int, [ctx, u8p, C.c_size_t, C.c_uint64, u32p]),
+        "she_trlwe_encrypt": (C.c_int, [ctx, u32p, C.c_size_t, C.c_uint64, u32p]),
+        "she_trlwe_write": (C.c_int, [ctx, u32p, C.c_size_t, u32p]),
+        "she_trlwe_read": (C.c_int, [ctx, u32p, C.c_size_t, u32p]),
+        "she_trlwe_phase": (C.c_int, [ctx, u32p, C.c_size_t, u32p]),
+        "she_eval_cmux": (C.c_int, [ctx, u32p, u32p, u32p, u32p, C.c_size_t]),
         "she_read_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_write_ct": (C.c_int, [ctx, C.c_uint32, u32p]),
         "she_export_keys": (C.c_int, [ctx, u8p, u8p, u32p, u32p]),
@@ -262,6 +269,43 @@ class Context:
         self._check(self._L.she_maxpool(self._h, _p(x_ids, C.c_uint32), H, W, Cn, bits, _p(out_ids, C.c_uint32),
                                         C.byref(gates)))
         return gates.value
+
+    # ---- leveled mode
+    def leveled_init(self, trgsw_capacity: int, trlwe_capacity: int):
+        self._check(self._L.she_leveled_init(self._h, trgsw_capacity, trlwe_capacity))
+
+    def trgsw_encrypt_bits(self, bits, seed: int, dst_ids):
+        bits, dst_ids = _u8(bits).ravel(), _u32(dst_ids).ravel()
+        assert bits.size == dst_ids.size
+        self._check(self._L.she_trgsw_encrypt_bits(self._h, _p(bits, C.c_uint8), bits.size, seed, _p(dst_ids, C.c_uint32)))
+
+    def trlwe_encrypt(self, mu, seed: int, dst_ids):
+        mu, dst_ids = _u32(mu).reshape(-1, self.params.N), _u32(dst_ids).ravel()
+        assert mu.shape[0] == dst_ids.size
+        self._check(self._L.she_trlwe_encrypt(self._h, _p(mu, C.c_uint32), dst_ids.size, seed, _p(dst_ids, C.c_uint32)))
+
+    def trlwe_write(self, samples, dst_ids):
+        samples, dst_ids = _u32(samples).reshape(-1, 2, self.params.N), _u32(dst_ids).ravel()
+        assert samples.shape[0] == dst_ids.size
+        self._check(self._L.she_trlwe_write(self._h, _p(samples, C.c_uint32), dst_ids.size, _p(dst_ids, C.c_uint32)))
+
+    def trlwe_read(self, ids) -> np.ndarray:
+        ids = _u32(ids).ravel()
+        out = np.zeros((ids.size, 2, self.params.N), np.uint32)
+        self._check(self._L.she_trlwe_read(self._h, _p(ids, C.c_uint32), ids.size, _p(out, C.c_uint32)))
+        return out
+
+    def trlwe_phase(self, ids) -> np.ndarray:
+        ids = _u32(ids).ravel()
+        out = np.zeros((ids.size, self.params.N), np.uint32)
+        self._check(self._L.she_trlwe_phase(self._h, _p(ids, C.c_uint32), ids.size, _p(out, C.c_uint32)))
+        return out
+
+    def eval_cmux(self, sel, in1, in0, out):
+        sel, in1, in0, out = (_u32(v).ravel() for v in (sel, in1, in0, out))
+        assert sel.size == in1.size == in0.size == out.size
+        self._check(self._L.she_eval_cmux(self._h, _p(sel, C.c_uint32), _p(in1, C.c_uint32), _p(in0, C.c_uint32),
+                                          _p(out, C.c_uint32), sel.size))
 
     # ---- diagnostics
     def read_ct(self, idx: int) -> np.ndarray:

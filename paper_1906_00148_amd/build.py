@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libshe_hip.so")
-SOURCES = ["she_kernels.hip", "she_api.cpp", "she_host.cpp", "she_circuits.cpp"]
+SOURCES = ["she_kernels.hip", "she_api.cpp", "she_host.cpp", "she_circuits.cpp", "she_leveled.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

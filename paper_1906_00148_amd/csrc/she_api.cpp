@@ -4,61 +4,11 @@
 #include <memory>
 #include <new>
 
-#include "she_internal.h"
+#include "she_ctx.h"
 
 using namespace she;
 
-namespace {
-struct LevelTimer {           // events around the three kernel families of every chunk
-    std::vector<hipEvent_t> ev;
-    ~LevelTimer() { clear(); }
-    void clear() { for (auto e : ev) hipEventDestroy(e); ev.clear(); }
-    hipError_t mark(hipStream_t st)
-    {
-        hipEvent_t e;
-        hipError_t rc = hipEventCreate(&e);
-        if (rc != hipSuccess) return rc;
-        ev.push_back(e);
-        return hipEventRecord(e, st);
-    }
-};
-}  // namespace
-
-struct she_ctx {
-    she_params P{};
-    int device = 0;
-    hipStream_t stream = nullptr;
-    HostKeys hk;
-    DeviceKeys dk;
-    uint32_t cap = 0, stride = 0;
-    uint32_t *pool = nullptr;
-    bool pool_owned = true;
-    uint32_t *temp = nullptr;            // internal slots: 0 = trivial 0, 1 = trivial 1, then temporaries
-    size_t temp_slots = 0;
-    LevelWork work;
-    // device staging for host-array calls (grown on demand)
-    uint8_t *d_type = nullptr;
-    uint32_t *d_in0 = nullptr, *d_in1 = nullptr, *d_out = nullptr;
-    size_t d_gate_cap = 0;
-    uint32_t *d_stage = nullptr;         // ciphertext staging [slots][n+1] and id lists
-    size_t d_stage_words = 0;
-    unsigned *d_round_err = nullptr;
-    bool track_round = false;
-    bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
-    bool native_mux = false;             // SHE_OPT_NATIVE_MUX
-    size_t split_below = 0;              // SHE_OPT_SPLIT_BELOW (set at creation: 6 x compute units)
-    uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
-    uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;
-    size_t d_mux_cap = 0;
-    bool timing = true;                  // record HIP events around every kernel
-    LevelTimer timer;                    // events not yet folded into last_ms
-    size_t timer_levels = 0;
-    double last_ms[4] = {0, 0, 0, 0};
-    std::string err;
-};
-
-namespace {
-
+namespace she {
 thread_local std::string g_keygen_error;
 
 int fail(she_ctx *c, int code, const std::string &msg)
@@ -66,14 +16,22 @@ int fail(she_ctx *c, int code, const std::string &msg)
     if (c) c->err = msg; else g_keygen_error = msg;
     return code;
 }
+}  // namespace she
 
-#define HIP_TRY(ctx, expr)                                                                        \
-    do {                                                                                          \
-        hipError_t e_ = (expr);                                                                   \
-        if (e_ != hipSuccess)                                                                     \
-            return fail(ctx, e_ == hipErrorOutOfMemory ? SHE_ENOMEM : SHE_EDEVICE,                \
-                        std::string(#expr) + ": " + hipGetErrorString(e_));                       \
-    } while (0)
+namespace she {
+int ensure_stage(she_ctx *c, size_t words)
+{
+    if (words <= c->d_stage_words) return SHE_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->d_stage) hipFree(c->d_stage);
+    c->d_stage = nullptr; c->d_stage_words = 0;
+    HIP_TRY(c, hipMalloc((void **)&c->d_stage, words * sizeof(uint32_t)));
+    c->d_stage_words = words;
+    return SHE_OK;
+}
+}  // namespace she
+
+namespace {
 
 CtSpace space(const she_ctx *c) { return CtSpace{c->pool, c->temp, c->cap, c->stride}; }
 
@@ -149,16 +107,6 @@ int ensure_mux_arrays(she_ctx *c, size_t muxes)
     return SHE_OK;
 }
 
-int ensure_stage(she_ctx *c, size_t words)
-{
-    if (words <= c->d_stage_words) return SHE_OK;
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (c->d_stage) hipFree(c->d_stage);
-    c->d_stage = nullptr; c->d_stage_words = 0;
-    HIP_TRY(c, hipMalloc((void **)&c->d_stage, words * sizeof(uint32_t)));
-    c->d_stage_words = words;
-    return SHE_OK;
-}
 
 // Enqueues one level (device arrays), cut into chunks of at most MAX_LEVEL_CHUNK gates.
 int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
@@ -425,6 +373,7 @@ void she_free(she_ctx *c)
     hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out);
     hipFree(c->d_stage); hipFree(c->d_round_err); hipFree(c->work.raw_ext);
     hipFree(c->d_mtype); hipFree(c->d_min0); hipFree(c->d_min1); hipFree(c->d_mout);
+    free_leveled(c);
     delete c;
 }
 

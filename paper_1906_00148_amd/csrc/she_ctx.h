@@ -1,0 +1,79 @@
+// The context behind the C ABI and the helpers its source files share (internal).
+#pragma once
+#include <string>
+#include <vector>
+
+#include "she_internal.h"
+
+namespace she {
+struct LevelTimer {           // events around the three kernel families of every chunk
+    std::vector<hipEvent_t> ev;
+    ~LevelTimer() { clear(); }
+    void clear() { for (auto e : ev) hipEventDestroy(e); ev.clear(); }
+    hipError_t mark(hipStream_t st)
+    {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) return rc;
+        ev.push_back(e);
+        return hipEventRecord(e, st);
+    }
+};
+
+struct LeveledPools {         // leveled mode: TRGSW selectors (spectral form) and TRLWE samples
+    double2 *trgsw_hat = nullptr;   // [trgsw_cap][2l][2][P][L]
+    uint32_t *trlwe = nullptr;      // [trlwe_cap][2][N]
+    uint32_t trgsw_cap = 0, trlwe_cap = 0;
+    uint32_t *d_ids = nullptr;      // device staging of the id arrays of one call (4 x ids_cap)
+    size_t ids_cap = 0;
+};
+}  // namespace she
+
+struct she_ctx {
+    she_params P{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    she::HostKeys hk;
+    she::DeviceKeys dk;
+    uint32_t cap = 0, stride = 0;
+    uint32_t *pool = nullptr;
+    bool pool_owned = true;
+    uint32_t *temp = nullptr;            // internal slots: 0 = trivial 0, 1 = trivial 1, then temporaries
+    size_t temp_slots = 0;
+    she::LevelWork work;
+    // device staging for host-array calls (grown on demand)
+    uint8_t *d_type = nullptr;
+    uint32_t *d_in0 = nullptr, *d_in1 = nullptr, *d_out = nullptr;
+    size_t d_gate_cap = 0;
+    uint32_t *d_stage = nullptr;         // ciphertext staging [slots][n+1] and id lists
+    size_t d_stage_words = 0;
+    unsigned *d_round_err = nullptr;
+    bool track_round = false;
+    bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
+    bool native_mux = false;             // SHE_OPT_NATIVE_MUX
+    size_t split_below = 0;              // SHE_OPT_SPLIT_BELOW (set at creation: 6 x compute units)
+    uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
+    uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;
+    size_t d_mux_cap = 0;
+    bool timing = true;                  // record HIP events around every kernel
+    she::LevelTimer timer;               // events not yet folded into last_ms
+    size_t timer_levels = 0;
+    double last_ms[4] = {0, 0, 0, 0};
+    she::LeveledPools lev;
+    std::string err;
+};
+
+namespace she {
+extern thread_local std::string g_keygen_error;        // message of a failed she_keygen (no context yet)
+int fail(she_ctx *c, int code, const std::string &msg); // records the message, returns the code
+int ensure_stage(she_ctx *c, size_t words);             // grows she_ctx::d_stage
+void free_leveled(she_ctx *c);                          // releases the leveled-mode pools
+}  // namespace she
+
+#define HIP_TRY(ctx, expr)                                                                        \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return she::fail(ctx, e_ == hipErrorOutOfMemory ? SHE_ENOMEM : SHE_EDEVICE,           \
+                             std::string(#expr) + ": " + hipGetErrorString(e_));                  \
+    } while (0)

@@ -18,7 +18,8 @@ namespace she {
 namespace {
 
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
-enum : uint64_t { kTagLweKey = 1, kTagRingKey = 2, kTagBkRow = 3, kTagKsRow = 4, kTagFresh = 5 };
+enum : uint64_t { kTagLweKey = 1, kTagRingKey = 2, kTagBkRow = 3, kTagKsRow = 4, kTagFresh = 5, kTagTrgswRow = 6,
+                  kTagTrlwe = 7 };
 
 inline uint64_t finalise(uint64_t z)
 {
@@ -74,6 +75,29 @@ void tlwe_sample(uint32_t n, const uint8_t *key, uint32_t message, double sigma,
     out[n] = body;
 }
 
+// TRLWE sample of zero under the ring key whose set bits are listed in `ones`: words 0..N-1 of the
+// stream are the mask A, word N+2j feeds the error of body coefficient j; B = A*s' + E.
+void trlwe_of_zero(uint32_t N, const std::vector<uint32_t> &ones, const Stream &st, double sigma, uint32_t *A, uint32_t *B)
+{
+    for (uint32_t j = 0; j < N; j++) {
+        A[j] = st.torus(j);
+        B[j] = st.gaussian(N + 2 * (uint64_t)j, sigma);
+    }
+    // B += A * s' in Z[X]/(X^N+1): each set key bit adds a negacyclic rotation of A
+    for (uint32_t s : ones) {
+        for (uint32_t j = 0; j < N - s; j++) B[j + s] += A[j];
+        for (uint32_t j = N - s; j < N; j++) B[j + s - N] -= A[j];
+    }
+}
+
+std::vector<uint32_t> set_bits(const std::vector<uint8_t> &key)
+{
+    std::vector<uint32_t> ones;
+    for (uint32_t j = 0; j < key.size(); j++)
+        if (key[j]) ones.push_back(j);
+    return ones;
+}
+
 }  // namespace
 
 void generate_keys(const she_params &P, uint64_t seed, HostKeys &K)
@@ -87,26 +111,15 @@ void generate_keys(const she_params &P, uint64_t seed, HostKeys &K)
         Stream r(seed, kTagRingKey, 0);
         for (uint32_t j = 0; j < N; j++) K.ring_key[j] = r.bit(j);
     }
-    std::vector<uint32_t> ones;                    // positions of the ring key's set bits
-    for (uint32_t j = 0; j < N; j++)
-        if (K.ring_key[j]) ones.push_back(j);
+    const std::vector<uint32_t> ones = set_bits(K.ring_key);
 
     // Bootstrapping key: BK_i = TRGSW(s_i) as 2l TRLWE rows.  Row (c, p) is (A, A*s' + E) with
     // s_i * Bg^-(p+1) added to the constant coefficient of component c.
     K.bk.assign((size_t)n * 2 * l * 2 * N, 0u);
     parallel_for((size_t)n * 2 * l, [&](size_t row) {
         const uint32_t i = (uint32_t)(row / (2 * l)), c = (uint32_t)(row / l) & 1u, p = (uint32_t)(row % l);
-        Stream st(seed, kTagBkRow, row);
         uint32_t *A = K.bk.data() + row * 2 * N, *B = A + N;
-        for (uint32_t j = 0; j < N; j++) {
-            A[j] = st.torus(j);
-            B[j] = st.gaussian(N + 2 * (uint64_t)j, P.bk_std);
-        }
-        // B += A * s' in Z[X]/(X^N+1): each set key bit adds a negacyclic rotation of A
-        for (uint32_t s : ones) {
-            for (uint32_t j = 0; j < N - s; j++) B[j + s] += A[j];
-            for (uint32_t j = N - s; j < N; j++) B[j + s - N] -= A[j];
-        }
+        trlwe_of_zero(N, ones, Stream(seed, kTagBkRow, row), P.bk_std, A, B);
         if (K.lwe_key[i]) (c ? B : A)[0] += 1u << (32 - (p + 1) * P.bg_bit);
     });
 
@@ -129,6 +142,48 @@ void fresh_samples(const she_params &P, const std::vector<uint8_t> &lwe_key, con
     parallel_for(nbits, [&](size_t k) {
         const uint32_t msg = bits[k] ? (1u << 29) : 0u - (1u << 29);
         tlwe_sample(P.n, lwe_key.data(), msg, P.lwe_std, Stream(enc_seed, kTagFresh, k), out + k * (P.n + 1));
+    });
+}
+
+void fresh_trgsw(const she_params &P, const std::vector<uint8_t> &ring_key, const uint8_t *bits, size_t count,
+                 uint64_t seed, uint32_t *out)
+{
+    const uint32_t N = P.N, l = P.l;
+    const std::vector<uint32_t> ones = set_bits(ring_key);
+    parallel_for(count * 2 * l, [&](size_t row) {
+        const size_t k = row / (2 * l);
+        const uint32_t c = (uint32_t)(row / l) & 1u, p = (uint32_t)(row % l);
+        uint32_t *A = out + row * 2 * N, *B = A + N;
+        trlwe_of_zero(N, ones, Stream(seed, kTagTrgswRow, row), P.bk_std, A, B);
+        if (bits[k]) (c ? B : A)[0] += 1u << (32 - (p + 1) * P.bg_bit);
+    });
+}
+
+void fresh_trlwe(const she_params &P, const std::vector<uint8_t> &ring_key, const uint32_t *mu, size_t count,
+                 uint64_t seed, uint32_t *out)
+{
+    const uint32_t N = P.N;
+    const std::vector<uint32_t> ones = set_bits(ring_key);
+    parallel_for(count, [&](size_t k) {
+        uint32_t *A = out + k * 2 * N, *B = A + N;
+        trlwe_of_zero(N, ones, Stream(seed, kTagTrlwe, k), P.bk_std, A, B);
+        for (uint32_t j = 0; j < N; j++) B[j] += mu[k * N + j];
+    });
+}
+
+void trlwe_phases(const she_params &P, const std::vector<uint8_t> &ring_key, const uint32_t *cts, size_t count,
+                  uint32_t *phases)
+{
+    const uint32_t N = P.N;
+    const std::vector<uint32_t> ones = set_bits(ring_key);
+    parallel_for(count, [&](size_t k) {
+        const uint32_t *A = cts + k * 2 * N, *B = A + N;
+        uint32_t *ph = phases + k * N;
+        for (uint32_t j = 0; j < N; j++) ph[j] = B[j];
+        for (uint32_t s : ones) {
+            for (uint32_t j = 0; j < N - s; j++) ph[j + s] -= A[j];
+            for (uint32_t j = N - s; j < N; j++) ph[j + s - N] += A[j];
+        }
     });
 }
 

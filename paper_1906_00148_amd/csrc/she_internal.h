@@ -50,6 +50,12 @@ void fill_twiddles(uint32_t N, double *host_out);
 size_t bk_hat_elems(const she_params &P);   // number of double2 in DeviceKeys::bk_hat
 
 hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st);
+// leveled mode: spectra of `samples` TRGSW samples d_int[s][2l][2][N] into slots d_ids[s] of trgsw_hat; CMux batch
+hipError_t launch_trgsw_transform(const she_params &P, const DeviceKeys &K, const uint32_t *d_int, double2 *trgsw_hat,
+                                  const uint32_t *d_ids, size_t samples, hipStream_t st);
+hipError_t launch_cmux(const she_params &P, const DeviceKeys &K, const double2 *trgsw_hat, uint32_t *trlwe,
+                       const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
+                       size_t count, unsigned *d_round_err, hipStream_t st);
 hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
                           const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
@@ -79,6 +85,14 @@ void fresh_samples(const she_params &P, const std::vector<uint8_t> &lwe_key, con
                    uint64_t enc_seed, uint32_t *out /* [nbits][n+1] */);
 // key-switching key as signed byte planes for the MFMA kernel: out[i][plane][col][j*4+v]
 void pack_ks_bytes(const she_params &P, const std::vector<uint32_t> &ks, uint32_t cols_p, std::vector<int8_t> &out);
+// leveled mode: fresh TRGSW samples of bits [count][2][l][2][N], fresh TRLWE samples of mu[count][N] as [count][2][N]
+// (noise bk_std, or none), phases B - A*s' of TRLWE samples
+void fresh_trgsw(const she_params &P, const std::vector<uint8_t> &ring_key, const uint8_t *bits, size_t count,
+                 uint64_t seed, uint32_t *out);
+void fresh_trlwe(const she_params &P, const std::vector<uint8_t> &ring_key, const uint32_t *mu, size_t count,
+                 uint64_t seed, uint32_t *out);
+void trlwe_phases(const she_params &P, const std::vector<uint8_t> &ring_key, const uint32_t *cts, size_t count,
+                  uint32_t *phases);
 void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, const uint32_t *cts, size_t count,
                     uint8_t *bits);
 

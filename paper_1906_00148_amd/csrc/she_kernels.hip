@@ -414,7 +414,9 @@ __global__ __launch_bounds__(256) void k_mux_combine(const uint32_t *__restrict_
 template <class PL>
 __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *__restrict__ bk_int,
                                                                 const double2 *__restrict__ tw_table,
-                                                                double2 *__restrict__ bk_hat, uint32_t polys)
+                                                                double2 *__restrict__ bk_hat, uint32_t polys,
+                                                                const uint32_t *__restrict__ dst_ids,
+                                                                uint32_t polys_per_sample)
 {
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
     __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
@@ -437,10 +439,109 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
     }
     forward<PL>(lc, xr, xi);
     if (live) {
-        double2 *dst = bk_hat + (size_t)q * P * L + t;
+        // sample s of the source goes to sample dst_ids[s] of the destination (in place when there is no list)
+        const size_t qo = dst_ids ? (size_t)dst_ids[q / polys_per_sample] * polys_per_sample + q % polys_per_sample : q;
+        double2 *dst = bk_hat + qo * P * L + t;
 #pragma unroll
         for (int k = 0; k < P; k++) dst[k * L] = make_double2(xr[k], xi[k]);
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// Leveled CMux: out = d0 + C [.] (d1 - d0) for a TRGSW selector C in spectral form and TRLWE
+// samples in HBM.  One CMux per wavefront; the same decomposition, transforms and products as
+// one step of the blind rotation, with the operands streamed from memory instead of LDS.
+// ------------------------------------------------------------------------------------------
+template <class PL, bool TRACK>
+__global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
+                                                           uint32_t *trlwe, const uint32_t *__restrict__ sel,
+                                                           const uint32_t *__restrict__ in1, const uint32_t *__restrict__ in0,
+                                                           const uint32_t *__restrict__ out, uint32_t count, uint32_t l,
+                                                           uint32_t bg_bit, const double2 *__restrict__ tw_table,
+                                                           unsigned *round_err)
+{
+    constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N;
+    static_assert(PL::GPW == 1, "one transform per wavefront");
+    __shared__ double2 s_xch[BR_WAVES][PL::XSLOTS];
+    __shared__ double2 s_tw[TwTable<PL>::COUNT];
+    const int wave = threadIdx.x >> 6, t = threadIdx.x & 63;
+    const uint32_t g = blockIdx.x * BR_WAVES + wave;
+    load_twiddles<PL>(s_tw, tw_table);
+    if (g >= count) return;
+
+    LaneCtx<PL> lc;
+    lc.init(t, s_xch[wave], s_tw);
+    const uint32_t *d1 = trlwe + (size_t)in1[g] * 2 * N, *d0 = trlwe + (size_t)in0[g] * 2 * N;
+    uint32_t *dst = trlwe + (size_t)out[g] * 2 * N;
+    const double2 *rows = trgsw_hat + (size_t)sel[g] * 2 * l * 2 * P * L + t;
+
+    const uint32_t Bg = 1u << bg_bit, half_bg = Bg >> 1;
+    uint32_t dec_off = 1u << (31 - l * bg_bit);
+    uint32_t flip = 0;
+    for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
+
+    double2 bv[2][P];
+#pragma unroll
+    for (int o = 0; o < 2; o++)
+#pragma unroll
+        for (int k = 0; k < P; k++) bv[o][k] = rows[(o * P + k) * L];
+
+    double sr[2][P], si[2][P];
+#pragma unroll
+    for (int k = 0; k < P; k++) { sr[0][k] = si[0][k] = sr[1][k] = si[1][k] = 0.0; }
+
+    for (int c = 0; c < 2; c++) {
+        uint32_t dlo[P], dhi[P];
+#pragma unroll
+        for (int m = 0; m < P; m++) {
+            const uint32_t j0 = c * N + t + L * m, j1 = j0 + M;
+            dlo[m] = (d1[j0] - d0[j0] + dec_off) ^ flip;
+            dhi[m] = (d1[j1] - d0[j1] + dec_off) ^ flip;
+        }
+        for (uint32_t p = 0; p < l; p++) {
+            const uint32_t sh = 32 - (p + 1) * bg_bit;
+            const uint32_t r = c * l + p;
+            double xr[P], xi[P];
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                xr[m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], sh, bg_bit);
+                xi[m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], sh, bg_bit);
+            }
+            forward<PL>(lc, xr, xi);
+#pragma unroll
+            for (int o = 0; o < 2; o++)
+#pragma unroll
+                for (int k = 0; k < P; k++) {
+                    const double2 b = bv[o][k];
+                    sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
+                    si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
+                }
+            if (r + 1 < 2 * l) {
+                const double2 *row = rows + (size_t)(r + 1) * 2 * P * L;
+#pragma unroll
+                for (int o = 0; o < 2; o++)
+#pragma unroll
+                    for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
+            }
+        }
+    }
+    float worst = 0.f;
+#pragma unroll
+    for (int o = 0; o < 2; o++) {
+        inverse<PL>(lc, sr[o], si[o]);
+#pragma unroll
+        for (int m = 0; m < P; m++) {
+            const double vr = sr[o][m], vi = si[o][m];
+            if (TRACK) {
+                worst = fmaxf(worst, (float)fabs(vr - rint(vr)));
+                worst = fmaxf(worst, (float)fabs(vi - rint(vi)));
+            }
+            const uint32_t j0 = o * N + t + L * m, j1 = j0 + M;
+            dst[j0] = d0[j0] + (uint32_t)__double2loint(vr + 6755399441055744.0);
+            dst[j1] = d0[j1] + (uint32_t)__double2loint(vi + 6755399441055744.0);
+        }
+    }
+    if (TRACK && round_err) atomicMax(round_err, __float_as_uint(worst));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -637,8 +738,59 @@ static hipError_t bk_transform_t(const she_params &P, const uint32_t *d_bk_int, 
     const uint32_t polys = P.n * 2 * P.l * 2;
     const uint32_t per_block = BR_WAVES * PL::GPW;
     hipLaunchKernelGGL((k_bk_transform<PL>), dim3((polys + per_block - 1) / per_block), dim3(64 * BR_WAVES), 0, st,
-                       d_bk_int, K.twiddles, K.bk_hat, polys);
+                       d_bk_int, K.twiddles, K.bk_hat, polys, (const uint32_t *)nullptr, 1u);
     return hipGetLastError();
+}
+
+template <class PL>
+static hipError_t trgsw_transform_t(const she_params &P, const DeviceKeys &K, const uint32_t *d_int, double2 *trgsw_hat,
+                                    const uint32_t *d_ids, size_t samples, hipStream_t st)
+{
+    const uint32_t pps = 2 * P.l * 2, polys = (uint32_t)(samples * pps);
+    const uint32_t per_block = BR_WAVES * PL::GPW;
+    hipLaunchKernelGGL((k_bk_transform<PL>), dim3((polys + per_block - 1) / per_block), dim3(64 * BR_WAVES), 0, st,
+                       d_int, K.twiddles, trgsw_hat, polys, d_ids, pps);
+    return hipGetLastError();
+}
+
+template <class PL>
+static hipError_t cmux_t(const she_params &P, const DeviceKeys &K, const double2 *trgsw_hat, uint32_t *trlwe,
+                         const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
+                         size_t count, unsigned *d_round_err, hipStream_t st)
+{
+    const dim3 grid((unsigned)((count + BR_WAVES - 1) / BR_WAVES)), block(64 * BR_WAVES);
+    if (d_round_err)
+        hipLaunchKernelGGL((k_cmux<PL, true>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
+                           (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
+    else
+        hipLaunchKernelGGL((k_cmux<PL, false>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
+                           (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
+    return hipGetLastError();
+}
+
+hipError_t launch_trgsw_transform(const she_params &P, const DeviceKeys &K, const uint32_t *d_int, double2 *trgsw_hat,
+                                  const uint32_t *d_ids, size_t samples, hipStream_t st)
+{
+    if (!samples) return hipSuccess;
+    switch (P.N) {
+    case 256: return trgsw_transform_t<Plan256>(P, K, d_int, trgsw_hat, d_ids, samples, st);
+    case 512: return trgsw_transform_t<Plan512>(P, K, d_int, trgsw_hat, d_ids, samples, st);
+    case 1024: return trgsw_transform_t<Plan1024>(P, K, d_int, trgsw_hat, d_ids, samples, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_cmux(const she_params &P, const DeviceKeys &K, const double2 *trgsw_hat, uint32_t *trlwe,
+                       const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
+                       size_t count, unsigned *d_round_err, hipStream_t st)
+{
+    if (!count) return hipSuccess;
+    switch (P.N) {
+    case 256: return cmux_t<Plan256>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
+    case 512: return cmux_t<Plan512>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
+    case 1024: return cmux_t<Plan1024>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, const DeviceKeys &K, hipStream_t st)

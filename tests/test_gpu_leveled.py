@@ -1,0 +1,179 @@
+"""GPU parity tests of the leveled mode: fresh TRGSW / TRLWE samples and batched CMux through the
+C ABI against the CPU oracle, word for word (exact integer results on both sides)."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from oracle import tfhe as O
+
+pytestmark = pytest.mark.gpu
+
+
+def she():
+    import paper_1906_00148_amd as pkg
+    return pkg
+
+
+def signed(x):
+    return np.asarray(x, np.uint32).astype(np.int32).astype(np.int64)
+
+
+def messages(rng, count, N):
+    return np.where(rng.integers(0, 2, (count, N)) == 1, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
+
+
+@pytest.fixture(scope="module")
+def toy_ctx():
+    pkg = she()
+    ctx = pkg.Context(pkg.TOY, S.KEY_SEED, 64)
+    ctx.leveled_init(64, 1024)
+    yield ctx
+    ctx.close()
+
+
+@pytest.fixture(scope="module")
+def real_ctx():
+    pkg = she()
+    ctx = pkg.Context(pkg.REAL, S.KEY_SEED, 64)
+    ctx.leveled_init(16, 256)
+    yield ctx
+    ctx.close()
+
+
+def test_fresh_trlwe_samples_match_the_oracle(toy_ctx, toy_keys):
+    P = toy_keys.params
+    rng = np.random.default_rng(11)
+    mu = rng.integers(0, 1 << 32, (7, P.N), dtype=np.uint64).astype(np.uint32)
+    ids = np.array([3, 900, 5, 17, 1023, 0, 44], np.uint32)
+    toy_ctx.trlwe_encrypt(mu, 4242, ids)
+    want = O.trlwe_encrypt(toy_keys, mu, 4242)
+    assert np.array_equal(toy_ctx.trlwe_read(ids), want)
+    phases = toy_ctx.trlwe_phase(ids)
+    for k in range(7):
+        assert np.array_equal(phases[k], O.trlwe_phase(toy_keys.ring_key, want[k]))
+    assert np.abs(signed(phases - mu)).max() < 6 * P.bk_std * 2.0 ** 32
+    # plain write / read
+    raw = rng.integers(0, 1 << 32, (2, 2, P.N), dtype=np.uint64).astype(np.uint32)
+    toy_ctx.trlwe_write(raw, [8, 9])
+    assert np.array_equal(toy_ctx.trlwe_read([9, 8]), raw[::-1])
+
+
+@pytest.mark.parametrize("count", [1, 5, 301])
+def test_cmux_level_bit_exact_toy(toy_ctx, toy_keys, count):
+    """One level of CMuxes, a ragged count over the four entries of a workgroup; every word against the oracle."""
+    P = toy_keys.params
+    rng = np.random.default_rng(100 + count)
+    nsel, ndat = 24, 400
+    bits = rng.integers(0, 2, nsel).astype(np.uint8)
+    sel_ids = rng.permutation(64)[:nsel].astype(np.uint32)
+    toy_ctx.trgsw_encrypt_bits(bits, 555, sel_ids)
+    sels = O.trgsw_encrypt_bits(toy_keys, bits, 555)
+    mu = messages(rng, ndat, P.N)
+    dat_ids = np.arange(ndat, dtype=np.uint32)
+    toy_ctx.trlwe_encrypt(mu, 777, dat_ids)
+    data = O.trlwe_encrypt(toy_keys, mu, 777)
+    s = rng.integers(0, nsel, count)
+    i1, i0 = rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+    out_ids = (ndat + np.arange(count)).astype(np.uint32)
+    toy_ctx.set_round_tracking(True)
+    toy_ctx.get_round_error(reset=True)
+    toy_ctx.eval_cmux(sel_ids[s], dat_ids[i1], dat_ids[i0], out_ids)
+    assert toy_ctx.get_round_error() < 0.2
+    toy_ctx.set_round_tracking(False)
+    got = toy_ctx.trlwe_read(out_ids)
+    phases = toy_ctx.trlwe_phase(out_ids)
+    for m in range(count):
+        want = O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])
+        assert np.array_equal(got[m], want), m
+        chosen = mu[i1[m]] if bits[s[m]] else mu[i0[m]]
+        assert np.array_equal(signed(phases[m]) > 0, signed(chosen) > 0), m
+    # tracking off: same words
+    toy_ctx.eval_cmux(sel_ids[s], dat_ids[i1], dat_ids[i0], out_ids)
+    assert np.array_equal(toy_ctx.trlwe_read(out_ids), got)
+
+
+def test_cmux_bit_exact_real_parameters(real_ctx, real_keys):
+    P = real_keys.params
+    rng = np.random.default_rng(7)
+    bits = np.array([1, 0, 1, 1, 0], np.uint8)
+    sel_ids = np.array([2, 9, 0, 15, 7], np.uint32)
+    real_ctx.trgsw_encrypt_bits(bits, 31, sel_ids)
+    sels = O.trgsw_encrypt_bits(real_keys, bits, 31)
+    mu = messages(rng, 6, P.N)
+    real_ctx.trlwe_encrypt(mu, 32, np.arange(6, dtype=np.uint32))
+    data = O.trlwe_encrypt(real_keys, mu, 32)
+    s = np.array([0, 1, 2, 3, 4, 0, 1, 2, 3])
+    i1 = np.array([0, 1, 2, 3, 4, 5, 0, 1, 2])
+    i0 = np.array([5, 4, 3, 2, 1, 0, 0, 3, 4])               # entry 6 has equal branches
+    out_ids = (100 + np.arange(9)).astype(np.uint32)
+    real_ctx.set_round_tracking(True)
+    real_ctx.get_round_error(reset=True)
+    real_ctx.eval_cmux(sel_ids[s], i1, i0, out_ids)
+    assert real_ctx.get_round_error() < 0.2
+    real_ctx.set_round_tracking(False)
+    got = real_ctx.trlwe_read(out_ids)
+    for m in range(9):
+        assert np.array_equal(got[m], O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])), m
+    assert np.array_equal(got[6], data[0])
+
+
+def test_lookup_tree_of_cmux_levels(toy_ctx, toy_keys):
+    """A 16-row plaintext table addressed by 4 encrypted bits: 4 levels of 8, 4, 2, 1 CMuxes, for 6 addresses
+    side by side; the root's phase is the addressed row, every intermediate word equals the oracle's."""
+    P = toy_keys.params
+    rng = np.random.default_rng(21)
+    table = messages(rng, 16, P.N)
+    rows = O.trlwe_trivial(P, table)
+    addrs = [0, 5, 10, 15, 7, 8]
+    nb = 4
+    abits = np.array([[(a >> b) & 1 for b in range(nb)] for a in addrs], np.uint8)
+    sel_ids = np.arange(len(addrs) * nb, dtype=np.uint32).reshape(len(addrs), nb)
+    toy_ctx.trgsw_encrypt_bits(abits.ravel(), 909, sel_ids.ravel())
+    sels = O.trgsw_encrypt_bits(toy_keys, abits.ravel(), 909).reshape(len(addrs), nb, -1)
+    toy_ctx.trlwe_write(rows, np.arange(16, dtype=np.uint32))
+    # per address q: level b writes its 16 >> (b+1) results at base[q][b]
+    cur = [list(range(16)) for _ in addrs]
+    ocur = [list(rows) for _ in addrs]
+    nxt = 16
+    for b in range(nb):
+        s, i1, i0, out = [], [], [], []
+        for q in range(len(addrs)):
+            new = []
+            for i in range(len(cur[q]) // 2):
+                s.append(sel_ids[q, b]); i1.append(cur[q][2 * i + 1]); i0.append(cur[q][2 * i]); out.append(nxt)
+                new.append(nxt)
+                nxt += 1
+            ocur[q] = [O.cmux(P, sels[q, b], ocur[q][2 * i + 1], ocur[q][2 * i]) for i in range(len(cur[q]) // 2)]
+            cur[q] = new
+        toy_ctx.eval_cmux(s, i1, i0, out)
+    roots = np.array([c[0] for c in cur], np.uint32)
+    got = toy_ctx.trlwe_read(roots)
+    phases = toy_ctx.trlwe_phase(roots)
+    for q, a in enumerate(addrs):
+        assert np.array_equal(got[q], ocur[q][0]), a
+        assert np.array_equal(signed(phases[q]) > 0, signed(table[a]) > 0), a
+
+
+def test_leveled_argument_errors(toy_ctx):
+    pkg = she()
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_cmux([0], [1], [2], [1])                # output is an input
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_cmux([0, 0], [1, 1], [2, 2], [5, 5])    # output twice
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_cmux([64], [1], [2], [3])               # selector outside its pool
+    assert e.value.code == -4
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.trlwe_read([1024])
+    assert e.value.code == -4
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.trgsw_encrypt_bits([2], 1, [0])
+    assert e.value.code == -1
+    toy_ctx.eval_cmux([], [], [], [])                        # empty level: no-op
+    fresh = pkg.Context(pkg.TOY, S.KEY_SEED, 16)
+    with pytest.raises(pkg.SheError) as e:
+        fresh.eval_cmux([0], [1], [2], [3])                  # pools not allocated
+    assert e.value.code == -1
+    fresh.close()
