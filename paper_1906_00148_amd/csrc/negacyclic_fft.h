@@ -197,20 +197,25 @@ __device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const 
         }
 #pragma unroll
     for (int s = 0; s < K; s++) {
+        // the pass's twiddles are requested ahead of its butterflies (the table is read-only, so the reads may
+        // sit before the fence): they arrive while the butterflies run instead of one round trip per product
+        double2 w[P];
+        if (s < K - 1) {
+#pragma unroll
+            for (int k = (s == 0 ? 0 : 1); k < P; k++) w[k] = lc.twiddle(s, k);
+        }
 #pragma unroll
         for (int b = 0; b < NB; b++) dft_regs<P, +1>(xr[b], xi[b]);
         if (s == K - 1) break;
         wave_lds_fence();
 #pragma unroll
         for (int k = 0; k < P; k++) {
-            double2 w = make_double2(1.0, 0.0);
-            if (k >= (s == 0 ? 0 : 1)) w = lc.twiddle(s, k);
 #pragma unroll
             for (int b = 0; b < NB; b++) {
                 if (k >= (s == 0 ? 0 : 1)) {
                     const double r = xr[b][k], i = xi[b][k];
-                    xr[b][k] = r * w.x - i * w.y;
-                    xi[b][k] = r * w.y + i * w.x;
+                    xr[b][k] = r * w[k].x - i * w[k].y;
+                    xi[b][k] = r * w[k].y + i * w[k].x;
                 }
                 xch[b][k * PL::XROW + lc.t] = make_double2(xr[b][k], xi[b][k]);   // stores overlap the remaining products
             }
@@ -229,7 +234,10 @@ __device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const 
 
 // Inverse transforms, the mirror of forward_n(); the 1/M normalisation is folded into the last
 // constant multiplication.  Out: xr/xi[b][m] = u_{t + L*m}.
-template <class PL, int NB>
+// SHARED: every set goes through the same exchange buffer, one after the other (store, load, next set's store,
+// ...); a wavefront's LDS operations execute in issue order, so a set's stores cannot overtake the previous
+// set's loads, and a set's round trip overlaps the arithmetic of the sets before it.
+template <class PL, int NB, bool SHARED = false>
 __device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
                                           double (&xi)[NB][PL::P])
 {
@@ -237,8 +245,25 @@ __device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const 
 #pragma unroll
     for (int s = K - 1; s >= 0; s--) {
         if (s < K - 1) {
-            // undo the transposition that followed pass s+1
+            // undo the transposition that followed pass s+1; the twiddles are requested first
             const int Tn = ipow(P, K - 2 - s);
+            double2 w[P];
+#pragma unroll
+            for (int k = (s == 0 ? 0 : 1); k < P; k++) w[k] = lc.twiddle(s, k);
+            if (SHARED) {
+#pragma unroll
+                for (int b = 0; b < NB; b++) {
+                    wave_lds_fence();
+#pragma unroll
+                    for (int m = 0; m < P; m++) xch[b][lc.rd_base[s] + m * Tn] = make_double2(xr[b][m], xi[b][m]);
+                    wave_lds_fence();
+#pragma unroll
+                    for (int k = 0; k < P; k++) {
+                        const double2 v = xch[b][k * PL::XROW + lc.t];
+                        xr[b][k] = v.x; xi[b][k] = v.y;
+                    }
+                }
+            } else {
             wave_lds_fence();
 #pragma unroll
             for (int b = 0; b < NB; b++)
@@ -252,14 +277,14 @@ __device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const 
                     const double2 v = xch[b][k * PL::XROW + lc.t];
                     xr[b][k] = v.x; xi[b][k] = v.y;
                 }
+            }
 #pragma unroll
             for (int k = (s == 0 ? 0 : 1); k < P; k++) {            // conjugate twiddle
-                const double2 w = lc.twiddle(s, k);
 #pragma unroll
                 for (int b = 0; b < NB; b++) {
                     const double r = xr[b][k], i = xi[b][k];
-                    xr[b][k] = r * w.x + i * w.y;
-                    xi[b][k] = i * w.x - r * w.y;
+                    xr[b][k] = r * w[k].x + i * w[k].y;
+                    xi[b][k] = i * w[k].x - r * w[k].y;
                 }
             }
         }

@@ -150,6 +150,10 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
                 }
                 forward<PL>(lc, xr, xi);
                 __builtin_amdgcn_sched_barrier(0);     // keeps the products out of the transform's schedule (measured: +4%)
+                // request the next row (of this step, or row 0 of the next one) register by register as the products
+                // free them; after the last step this reads the last row once more, which is harmless
+                const size_t nxt = std::min<size_t>((size_t)i * 2 * l + r + 1, (size_t)n * 2 * l - 1);
+                const double2 *row = bk_hat + nxt * 2 * P * L + t;
 #pragma unroll
                 for (int o = 0; o < 2; o++) {
 #pragma unroll
@@ -158,24 +162,19 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
                         // two fused multiply-adds per part (a += x*y - z*w would cost a multiply, an fma and an add)
                         sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
                         si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
+                        bv[o][k] = row[(o * P + k) * L];
                     }
-                }
-                // request the next row (of this step, or row 0 of the next one) as soon as the registers are free;
-                // after the last step this reads the last row once more, which is harmless
-                {
-                    const size_t nxt = std::min<size_t>((size_t)i * 2 * l + r + 1, (size_t)n * 2 * l - 1);
-                    const double2 *row = bk_hat + nxt * 2 * P * L + t;
-#pragma unroll
-                    for (int o = 0; o < 2; o++)
-#pragma unroll
-                        for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        {
+            // both inverse transforms side by side through the one exchange buffer (measured: 21.0 -> 20.7 ms)
+            double2 *const xch2[2] = {lc.xch, lc.xch};
+            inverse_n<PL, 2, true>(lc, xch2, sr, si);
+        }
 #pragma unroll
         for (int o = 0; o < 2; o++) {
-            inverse<PL>(lc, sr[o], si[o]);
 #pragma unroll
             for (int m = 0; m < P; m++) {
                 const double vr = sr[o][m], vi = si[o][m];
@@ -526,9 +525,12 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
         }
     }
     float worst = 0.f;
+    {
+        double2 *const xch2[2] = {lc.xch, lc.xch};
+        inverse_n<PL, 2, true>(lc, xch2, sr, si);
+    }
 #pragma unroll
     for (int o = 0; o < 2; o++) {
-        inverse<PL>(lc, sr[o], si[o]);
 #pragma unroll
         for (int m = 0; m < P; m++) {
             const double vr = sr[o][m], vi = si[o][m];
