@@ -41,6 +41,17 @@ def plain_gate(code: int, a: int, b: int) -> int:
     return _PLAIN[code](a, b)
 
 
+def plain_gate3(code: int, a: int, b: int, c: int) -> int:
+    """majority / parity of the three inputs after the complements the code's mask asks for"""
+    m = code - tfhe.GATE3_BASE
+    a, b, c = a ^ (m & 1), b ^ ((m >> 1) & 1), c ^ ((m >> 2) & 1)
+    return int(a + b + c >= 2) if (m >> 3) == 0 else a ^ b ^ c
+
+
+def is_mux(t: int) -> bool:
+    return tfhe.MUX_BASE <= t < tfhe.GATE3_BASE
+
+
 # ------------------------------------------------------------------ plain meaning
 def plain_shift_acc(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int) -> np.ndarray:
     """x[units][terms] unsigned; result sum_i sign_i * (x_i >> |e_i|), wrapped to acc_bits, as signed ints."""
@@ -119,6 +130,7 @@ class Netlist:
     n_inputs: int
     fold: bool = False
     native_mux: bool = False     # mux() emits one three-input MUX entry (two blind rotations, one key switch)
+    adder3: bool = False         # adders use full-adder cells of two three-input gates (parity + majority)
     gtype: list = field(default_factory=list)
     in0: list = field(default_factory=list)
     in1: list = field(default_factory=list)
@@ -143,7 +155,7 @@ class Netlist:
     @property
     def rotations(self) -> int:
         """blind rotations = two-input gates + 2 per native MUX"""
-        return sum(2 if t >= tfhe.MUX_BASE else 1 for t in self.gtype)
+        return sum(2 if is_mux(t) else 1 for t in self.gtype)
 
     def _resolve(self, ref: int):
         """wire reference -> (wire or None, constant or None, complemented?)"""
@@ -175,6 +187,49 @@ class Netlist:
             return var if (g0, g1) == (0, 1) else var | NEG
         table = sum(f(x, y) << (2 * x + y) for x in (0, 1) for y in (0, 1))
         return self._emit(_CODE_OF_TABLE[table], wa, wb)
+
+    def gate3(self, kind: str, a: int, b: int, c: int) -> int:
+        """kind 'MAJ' (at least two inputs true) or 'XOR' (an odd number true), ONE bootstrap.  With fold, a
+        cell with constant, repeated or complementary operands shrinks to a 2-input gate, a wire or a constant,
+        and complements of the remaining operands go into the code's mask."""
+        base = tfhe.MAJ3 if kind == "MAJ" else tfhe.XOR3
+        if not self.fold:
+            return self._emit(base, a, b, c)
+        ops = [self._resolve(r) for r in (a, b, c)]
+        wires = []
+        for w, _, _ in ops:
+            if w is not None and w not in wires:
+                wires.append(w)
+
+        def f(*vals):                         # the cell as a function of the distinct underlying wires' values
+            env = dict(zip(wires, vals))
+            bits = [cst if w is None else env[w] ^ int(ng) for w, cst, ng in ops]
+            return int(sum(bits) >= 2) if kind == "MAJ" else bits[0] ^ bits[1] ^ bits[2]
+        if len(wires) == 3:
+            mask = sum(int(ng) << i for i, (_, _, ng) in enumerate(ops))
+            if kind == "XOR":                 # a complemented input complements the parity
+                mask = bin(mask).count("1") & 1
+            return self._emit(base + mask, *wires)
+        if len(wires) == 2:
+            table = sum(f(x, y) << (2 * x + y) for x in (0, 1) for y in (0, 1))
+            if table in _CODE_OF_TABLE:
+                return self._emit(_CODE_OF_TABLE[table], wires[0], wires[1])
+            # not one of the ten gates: the function ignores one of the two wires (a pair of operands that
+            # repeat or complement each other drops out of a majority or a parity) or both
+            for k in (0, 1):
+                at = lambda v, o: f(v, o) if k == 0 else f(o, v)      # wires[k] = v, the other wire = o
+                if at(0, 0) == at(0, 1) and at(1, 0) == at(1, 1):
+                    g0, g1 = at(0, 0), at(1, 0)
+                    if g0 == g1:
+                        return self.ONE if g0 else self.ZERO
+                    return wires[k] if (g0, g1) == (0, 1) else wires[k] | NEG
+            raise AssertionError("a two-variable function that is neither a gate nor degenerate")
+        if len(wires) == 1:
+            g0, g1 = f(0), f(1)
+            if g0 == g1:
+                return self.ONE if g0 else self.ZERO
+            return wires[0] if (g0, g1) == (0, 1) else wires[0] | NEG
+        return self.ONE if f() else self.ZERO
 
     def mux(self, s: int, u: int, v: int) -> int:
         """s ? u : v.  Three 2-input gates, or with native_mux one MUX entry whose two blind
@@ -212,7 +267,7 @@ class Netlist:
     def levels(self) -> np.ndarray:
         lev = np.zeros(self.n_wires, np.int64)
         for t, a, b, c, o in zip(self.gtype, self.in0, self.in1, self.in2, self.out):
-            lev[o] = 1 + max(lev[a], lev[b], lev[c] if t >= tfhe.MUX_BASE else 0)
+            lev[o] = 1 + max(lev[a], lev[b], lev[c] if t >= tfhe.MUX_BASE else 0)      # MUX entries and 3-input gates
         return lev[np.asarray(self.out, np.int64)] if self.out else np.zeros(0, np.int64)
 
     # ---- evaluation on plaintext bits
@@ -223,6 +278,8 @@ class Netlist:
         for t, a, b, c, o in zip(self.gtype, self.in0, self.in1, self.in2, self.out):
             if t < tfhe.MUX_BASE:
                 val[o] = plain_gate(t, int(val[a]), int(val[b]))
+            elif t >= tfhe.GATE3_BASE:
+                val[o] = plain_gate3(t, int(val[a]), int(val[b]), int(val[c]))
             else:                                        # at most one of the two rotations gives 1
                 m = t - tfhe.MUX_BASE
                 val[o] = plain_gate(m >> 4, int(val[a]), int(val[b])) | plain_gate(m & 15, int(val[a]), int(val[c]))
@@ -271,6 +328,14 @@ def add_unsigned(nl: Netlist, a: list, b: list, cap: int) -> list:
     if w == 1 and cap == 1:
         return out
     c = nl.gate("AND", a[0], b[0])
+    if nl.adder3:                       # full-adder cell = parity and majority of (a_i, b_i, carry): 2w gates
+        for i in range(1, w):
+            out.append(nl.gate3("XOR", a[i], b[i], c))
+            if i == w - 1 and w >= cap:
+                return out
+            c = nl.gate3("MAJ", a[i], b[i], c)
+        out.append(c)
+        return out
     for i in range(1, w):
         t = nl.gate("XOR", a[i], b[i])
         out.append(nl.gate("XOR", t, c))
@@ -289,6 +354,13 @@ def sub_wrapped(nl: Netlist, p: list, q: list) -> list:
     w = len(p)
     assert len(q) == w
     out, c = [], nl.ONE
+    if nl.adder3:                       # the same cell on (p_i, not q_i, carry)
+        for i in range(w):
+            out.append(nl.gate3("XOR", p[i], q[i] ^ NEG, c) if nl.fold else nl._emit(tfhe.XOR3 + 1, p[i], q[i], c))
+            if i == w - 1:
+                break
+            c = nl.gate3("MAJ", p[i], q[i] ^ NEG, c) if nl.fold else nl._emit(tfhe.MAJ3 + 2, p[i], q[i], c)
+        return out
     for i in range(w):
         t = nl.gate("XNOR", p[i], q[i])
         out.append(nl.gate("XOR", t, c))
@@ -327,11 +399,12 @@ def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
     return list(x_bits[s:]) + [nl.ZERO] * min(s, w)
 
 
-def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False):
+def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
+                    adder3: bool = False):
     """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits])."""
     w_sign = np.asarray(w_sign).reshape(units, terms)
     w_exp = np.asarray(w_exp).reshape(units, terms)
-    nl = Netlist(units * terms * in_bits, fold)
+    nl = Netlist(units * terms * in_bits, fold, adder3=adder3)
     outs = []
     for u in range(units):
         pos, neg = [], []

@@ -114,6 +114,10 @@ def lib() -> C.CDLL:
         L.orc_bootstrap.argtypes = [pp, u32p, u32p, u32p, u32p]
         L.orc_gate.restype = C.c_int
         L.orc_gate.argtypes = [pp, u32p, u32p, C.c_int, u32p, u32p, u32p]
+        L.orc_gate3_lincomb.restype = C.c_int
+        L.orc_gate3_lincomb.argtypes = [C.c_uint32, C.c_int, u32p, u32p, u32p, u32p]
+        L.orc_gate3.restype = C.c_int
+        L.orc_gate3.argtypes = [pp, u32p, u32p, C.c_int, u32p, u32p, u32p, u32p]
         L.orc_mux.restype = C.c_int
         L.orc_mux.argtypes = [pp, u32p, u32p, C.c_int, C.c_int, u32p, u32p, u32p, u32p]
         L.orc_eval_netlist.restype = C.c_int
@@ -369,8 +373,31 @@ def mux(K: Keys, sel, c1, c0, code1: int = GATES["AND"], code0: int = GATES["AND
     return out
 
 
+GATE3_BASE = 176             # three-input gates: GATE3_BASE + 8*kind + negmask (bit i complements input i)
+MAJ3, XOR3 = 176, 184        # kind 0 = majority, kind 1 = parity
+
+
+def gate3_lincomb(g: int, ca, cb, cc) -> np.ndarray:
+    ca, cb, cc = _u32(ca), _u32(cb), _u32(cc)
+    out = np.zeros_like(ca)
+    if lib().orc_gate3_lincomb(ca.size - 1, g, _p32(ca), _p32(cb), _p32(cc), _p32(out)):
+        raise ValueError("unknown three-input gate")
+    return out
+
+
+def gate3(K: Keys, g: int, ca, cb, cc) -> np.ndarray:
+    """Three-input gate (majority or parity, inputs optionally complemented) with ONE bootstrap."""
+    ca, cb, cc = _u32(ca), _u32(cb), _u32(cc)
+    out = np.zeros_like(ca)
+    cp = K.params.c()
+    if lib().orc_gate3(C.byref(cp), _p32(K.bk), _p32(K.ks), g, _p32(ca), _p32(cb), _p32(cc), _p32(out)):
+        raise ValueError("orc_gate3 failed")
+    return out
+
+
 def eval_netlist(K: Keys, pool: np.ndarray, gtype, in0, in1, in2, out, threads: int = 1) -> None:
-    """Like eval_gates, with native MUX entries (type >= MUX_BASE, operands in0 = selector, in1, in2)."""
+    """Like eval_gates, with native MUX entries (MUX_BASE <= type < GATE3_BASE, operands in0 = selector, in1, in2)
+    and three-input gates (type >= GATE3_BASE)."""
     assert pool.dtype == np.uint32 and pool.flags.c_contiguous and pool.shape[1] == K.params.n + 1
     gtype, in0, in1, in2, out = (_u32(v) for v in (gtype, in0, in1, in2, out))
     for a in (in0, in1, in2, out):

@@ -52,6 +52,9 @@ typedef struct {
 
 enum { ORC_NAND, ORC_AND, ORC_OR, ORC_XOR, ORC_XNOR, ORC_NOR, ORC_ANDNY, ORC_ANDYN, ORC_ORNY, ORC_ORYN,
        ORC_NGATES };
+/* Three-input gates bootstrapped once: type = ORC_GATE3_BASE + 8*kind + negmask, kind 0 = majority,
+ * kind 1 = parity (XOR of the three); bit i of negmask complements input i. */
+enum { ORC_GATE3_BASE = 176, ORC_MAJ3 = 176, ORC_XOR3 = 184, ORC_GATE3_END = 192 };
 
 enum { TAG_LWE_KEY = 1, TAG_RING_KEY = 2, TAG_BK_ROW = 3, TAG_KS_ROW = 4, TAG_FRESH = 5, TAG_TRGSW_ROW = 6,
        TAG_TRLWE = 7 };
@@ -329,6 +332,22 @@ int orc_gate_lincomb(uint32_t n, int type, const uint32_t *ca, const uint32_t *c
     return 0;
 }
 
+/* Pre-bootstrap sample of a three-input gate (Section 3.1: the operators are built from homomorphic
+ * gates; a gate is any linear combination whose phase has the wanted sign, followed by one bootstrap).
+ * With inputs of phase +-1/8, s = sum_i (+-c_i) has phase (2k-3)/8 for k true (possibly complemented)
+ * inputs: majority is the sign of s itself (margin 1/8), parity is the sign of -2s, whose phase is
+ * +1/4 for odd k and -1/4 for even k modulo 1 (margin 1/4).  No offset is added. */
+int orc_gate3_lincomb(uint32_t n, int type, const uint32_t *ca, const uint32_t *cb, const uint32_t *cc, uint32_t *out)
+{
+    if (type < ORC_GATE3_BASE || type >= ORC_GATE3_END) return -1;
+    const int kind = (type - ORC_GATE3_BASE) >> 3, neg = (type - ORC_GATE3_BASE) & 7;
+    for (uint32_t i = 0; i <= n; i++) {
+        uint32_t x = ((neg & 1) ? 0u - ca[i] : ca[i]) + ((neg & 2) ? 0u - cb[i] : cb[i]) + ((neg & 4) ? 0u - cc[i] : cc[i]);
+        out[i] = kind == 0 ? x : 0u - 2u * x;
+    }
+    return 0;
+}
+
 /* round a torus element to the nearest multiple of 1/(2N); result in [0,2N) */
 uint32_t orc_modswitch(uint32_t N, uint32_t x)
 {
@@ -462,6 +481,17 @@ int orc_gate(const orc_params *P, const uint32_t *bk, const uint32_t *ks, int ty
     return rc;
 }
 
+int orc_gate3(const orc_params *P, const uint32_t *bk, const uint32_t *ks, int type, const uint32_t *ca,
+              const uint32_t *cb, const uint32_t *cc, uint32_t *out)
+{
+    if (!params_ok(P)) return -1;
+    uint32_t *tmp = (uint32_t *)malloc(sizeof(uint32_t) * (P->n + 1));
+    int rc = orc_gate3_lincomb(P->n, type, ca, cb, cc, tmp);
+    if (rc == 0) rc = orc_bootstrap(P, bk, ks, tmp, out);
+    free(tmp);
+    return rc;
+}
+
 /* Blind rotation and extraction only: TLWE of dimension N under the ring key's coefficients. */
 static void bootstrap_wo_keyswitch(const orc_params *P, const uint32_t *bk, const uint32_t *in, uint32_t *ext /* [N+1] */)
 {
@@ -505,12 +535,14 @@ int orc_mux(const orc_params *P, const uint32_t *bk, const uint32_t *ks, int cod
 /* A list of gates over a ciphertext pool pool[slot][n+1], evaluated in the
  * order given (so a netlist in topological order may be passed whole).  With
  * threads > 1 the gates must be mutually independent (one circuit level).
- * type[g] < ORC_NGATES: out = type(in0, in1).  type[g] = ORC_NGATES + 16*code1 + code0:
- * native MUX with selector in0, operands in1 (taken when sel = 1) and in2.    */
+ * type[g] < ORC_NGATES: out = type(in0, in1).  type[g] = ORC_NGATES + 16*code1 + code0 (< ORC_GATE3_BASE):
+ * native MUX with selector in0, operands in1 (taken when sel = 1) and in2.
+ * type[g] >= ORC_GATE3_BASE: three-input gate of in0, in1, in2.                */
 static int eval_one(const orc_params *P, const uint32_t *bk, const uint32_t *ks, uint32_t *pool, size_t w, uint32_t type,
                     uint32_t a, uint32_t b, uint32_t c, uint32_t o)
 {
     if (type < ORC_NGATES) return orc_gate(P, bk, ks, (int)type, pool + a * w, pool + b * w, pool + o * w);
+    if (type >= ORC_GATE3_BASE) return orc_gate3(P, bk, ks, (int)type, pool + a * w, pool + b * w, pool + c * w, pool + o * w);
     const uint32_t m = type - ORC_NGATES;
     return orc_mux(P, bk, ks, (int)(m >> 4), (int)(m & 15), pool + a * w, pool + b * w, pool + c * w, pool + o * w);
 }
