@@ -68,6 +68,10 @@ enum { SHE_OK = 0, SHE_EINVAL = -1, SHE_ENOMEM = -2, SHE_EDEVICE = -3, SHE_ERANG
 enum { SHE_NAND = 0, SHE_AND, SHE_OR, SHE_XOR, SHE_XNOR, SHE_NOR, SHE_ANDNY, SHE_ANDYN, SHE_ORNY, SHE_ORYN,
        SHE_NUM_GATES };
 
+/* Codes of she_eval_gates3: SHE_MAJ3 + mask (at least two of the three inputs true) and SHE_XOR3 + mask (an odd
+ * number true); bit i of mask (0..7) complements input i first. */
+enum { SHE_MAJ3 = 176, SHE_XOR3 = 184 };
+
 /* Section 2 ("Homomorphic Encryption": key pair of the client).  Generates the TLWE key,
  * the ring key, the bootstrapping key BK_i = TRGSW(s_i) and the key-switching key from
  * `seed`, uploads them, transforms BK to the kernels' spectral layout and allocates the
@@ -98,6 +102,17 @@ int she_decrypt(she_ctx *ctx, const uint32_t *ids, size_t count, uint8_t *bits_o
  * type >= SHE_NUM_GATES gives SHE_EINVAL.  ngates = 0 is a no-op. */
 int she_eval_gates(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1,
                    const uint32_t *out, size_t ngates);
+
+/* Section 3.1 (the units are built from homomorphic gates; a bootstrapped gate is a linear combination of
+ * its inputs whose phase has the wanted sign, then one bootstrap) and Section 3.3 (the accumulator's adders).
+ * ONE level of ngates three-input gates, each with a single bootstrap like a 2-input gate:
+ *   SHE_MAJ3: pre-bootstrap sample +-c0 +- c1 +- c2, phase (2k-3)/8 for k true inputs, sign = majority;
+ *   SHE_XOR3: -2 times that sample, phase +1/4 for odd k and -1/4 for even k.
+ * A full-adder cell is sum = XOR3(a, b, carry), next carry = MAJ3(a, b, carry): two bootstraps instead of
+ * five (see SHE_OPT_ADDER_CELLS).  Decision margins against the output noise of earlier bootstraps stay above
+ * 20 standard deviations at the supported parameter sets.  Same id rules and error codes as she_eval_gates. */
+int she_eval_gates3(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                    const uint32_t *out, size_t ngates);
 
 /* Section 3.2 (logarithmic quantization: sum_i binaryshift(input_i, weightQ_i)) and
  * Section 3.3 (mixed-bitwidth accumulator).  For each of `units` output neurons:
@@ -135,7 +150,7 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
  * gate becomes a constant, its other operand, or that operand's complement, and complements are
  * absorbed into the next gate's code or applied as a free word-wise negation (Section 3.2: what
  * only re-wires ciphertexts costs no gate).  Results decrypt identically; gate counts drop. */
-enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2, SHE_OPT_SPLIT_BELOW = 3 };
+enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2, SHE_OPT_SPLIT_BELOW = 3, SHE_OPT_ADDER_CELLS = 4 };
 int she_set_option(she_ctx *ctx, int option, int value);
 int she_get_option(she_ctx *ctx, int option, int *value);   /* SHE_EINVAL for an unknown option or a null pointer */
 /* SHE_OPT_SPLIT_BELOW (default: 6 x the device's compute units, 1536 on MI355X): a kernel launch of at
@@ -143,6 +158,9 @@ int she_get_option(she_ctx *ctx, int option, int *value);   /* SHE_EINVAL for an
  * which shortens the serial chain per CMux when the level is too small to fill the chip; larger launches
  * keep one wavefront per rotation.  0 never splits.  Every ciphertext comes out the same word for word
  * either way (both kernels round exact integers). */
+/* SHE_OPT_ADDER_CELLS (default 0): the adders and the subtraction of she_shift_acc use full-adder cells of two
+ * three-input gates (she_eval_gates3) above the lowest bit: a w-bit adder costs 2w gates in w levels instead of
+ * 5w-3 gates in 2w-1 levels (a 576-term 8-bit tree: 10,332 gates instead of 24,104).  Results decrypt identically. */
 /* SHE_OPT_NATIVE_MUX (default 0): she_maxpool evaluates every MUX of its comparators and selectors
  * with she_eval_mux's three-input gate instead of three 2-input gates (7w gates per max become
  * w gates + 2w MUX entries = 5w blind rotations and 3w key switches, and half the levels). */

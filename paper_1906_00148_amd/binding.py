@@ -82,6 +82,7 @@ def load_library() -> C.CDLL:
         "she_plan_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
                                        C.POINTER(C.c_uint32), u64p]),
         "she_eval_mux": (C.c_int, [ctx, u32p, u32p, u32p, u32p, C.c_size_t]),
+        "she_eval_gates3": (C.c_int, [ctx, u8p, u32p, u32p, u32p, u32p, C.c_size_t]),
         "she_leveled_init": (C.c_int, [ctx, C.c_uint32, C.c_uint32]),
         "she_trgsw_encrypt_bits": (C.c_int, [ctx, u8p, C.c_size_t, C.c_uint64, u32p]),
         "she_trlwe_encrypt": (C.c_int, [ctx, u32p, C.c_size_t, C.c_uint64, u32p]),
@@ -128,10 +129,12 @@ def _p(a, ty):
 OPT_FOLD_CONSTANTS = 1
 OPT_NATIVE_MUX = 2
 OPT_SPLIT_BELOW = 3
+OPT_ADDER_CELLS = 4
+MAJ3, XOR3 = 176, 184        # three-input gate codes; + mask (bit i complements input i)
 
 
-def _options(fold: bool, native_mux: bool) -> int:
-    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0)
+def _options(fold: bool, native_mux: bool, adder_cells: bool = False) -> int:
+    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0) | (OPT_ADDER_CELLS if adder_cells else 0)
 
 
 def _plan(rc, gates, levels):
@@ -140,12 +143,14 @@ def _plan(rc, gates, levels):
     return gates.value, levels.value
 
 
-def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False):
+def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
+                   adder_cells: bool = False):
     """(gates, levels) of she_shift_acc for these weights; runs on the host, no GPU needed."""
     w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
     g, lv = C.c_uint64(0), C.c_uint32(0)
     return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
-                                                   acc_bits, _options(fold, False), C.byref(g), C.byref(lv), None), g, lv)
+                                                   acc_bits, _options(fold, False, adder_cells), C.byref(g), C.byref(lv),
+                                                   None), g, lv)
 
 
 def plan_relu(count: int, bits: int, fold: bool = False):
@@ -241,6 +246,13 @@ class Context:
         assert sel.size == in1.size == in0.size == out.size
         self._check(self._L.she_eval_mux(self._h, _p(sel, C.c_uint32), _p(in1, C.c_uint32), _p(in0, C.c_uint32),
                                          _p(out, C.c_uint32), sel.size))
+
+    def eval_gates3(self, gtype, in0, in1, in2, out):
+        gtype = _u8(gtype).ravel()
+        in0, in1, in2, out = (_u32(v).ravel() for v in (in0, in1, in2, out))
+        assert gtype.size == in0.size == in1.size == in2.size == out.size
+        self._check(self._L.she_eval_gates3(self._h, _p(gtype, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
+                                            _p(in2, C.c_uint32), _p(out, C.c_uint32), gtype.size))
 
     def shift_acc(self, x_ids, w_sign, w_exp, acc_bits: int, out_ids) -> int:
         x_ids = _u32(x_ids)

@@ -70,12 +70,13 @@ int ensure_gate_arrays(she_ctx *c, size_t gates)
 {
     if (gates <= c->d_gate_cap) return SHE_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (c->d_type) { hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out); }
+    if (c->d_type) { hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_in2); hipFree(c->d_out); }
     c->d_type = nullptr; c->d_gate_cap = 0;
     gates += gates / 4;
     HIP_TRY(c, hipMalloc((void **)&c->d_type, gates));
     HIP_TRY(c, hipMalloc((void **)&c->d_in0, gates * sizeof(uint32_t)));
     HIP_TRY(c, hipMalloc((void **)&c->d_in1, gates * sizeof(uint32_t)));
+    HIP_TRY(c, hipMalloc((void **)&c->d_in2, gates * sizeof(uint32_t)));
     HIP_TRY(c, hipMalloc((void **)&c->d_out, gates * sizeof(uint32_t)));
     c->d_gate_cap = gates;
     return SHE_OK;
@@ -110,7 +111,7 @@ int ensure_mux_arrays(she_ctx *c, size_t muxes)
 
 // Enqueues one level (device arrays), cut into chunks of at most MAX_LEVEL_CHUNK gates.
 int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
-                  const uint32_t *d_out, size_t gates)
+                  const uint32_t *d_out, size_t gates, const uint32_t *d_in2 = nullptr)
 {
     const CtSpace cs = space(c);
     LevelTimer *timer = c->timing ? &c->timer : nullptr;
@@ -118,7 +119,8 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
     for (size_t off = 0; off < gates; off += MAX_LEVEL_CHUNK) {
         const size_t cnt = std::min<size_t>(MAX_LEVEL_CHUNK, gates - off);
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, cnt, c->work, c->stream));
+        HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, d_in2 ? d_in2 + off : nullptr, cnt, c->work,
+                                  c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream,
                                        false, cnt <= c->split_below));
@@ -140,7 +142,8 @@ int enqueue_mux_level(she_ctx *c, const uint8_t *d_jtype, const uint32_t *d_jin0
     for (size_t off = 0; off < muxes; off += step) {
         const size_t cnt = std::min<size_t>(step, muxes - off);
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_lincomb(c->P, cs, d_jtype + 2 * off, d_jin0 + 2 * off, d_jin1 + 2 * off, 2 * cnt, c->work, c->stream));
+        HIP_TRY(c, launch_lincomb(c->P, cs, d_jtype + 2 * off, d_jin0 + 2 * off, d_jin1 + 2 * off, nullptr, 2 * cnt, c->work,
+                                  c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
         HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, nullptr, 2 * cnt, c->work,
                                        c->track_round ? c->d_round_err : nullptr, c->stream, true, 2 * cnt <= c->split_below));
@@ -229,6 +232,7 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         HIP_TRY(c, hipMemcpyAsync(c->d_type, nl.type.data(), G, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_in0, nl.in0.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_in1, nl.in1.data(), G * 4, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipMemcpyAsync(c->d_in2, nl.in2.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         HIP_TRY(c, hipMemcpyAsync(c->d_out, nl.out.data(), G * 4, hipMemcpyHostToDevice, c->stream));
         if (!mo.empty()) {
             HIP_TRY(c, hipMemcpyAsync(c->d_mtype, jt.data(), jt.size(), hipMemcpyHostToDevice, c->stream));
@@ -238,7 +242,8 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         }
         for (size_t lv = 0; lv < levels; lv++) {
             const size_t a = bounds[lv], m = mux_start[lv];
-            if (m > a && (rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, m - a))) return rc;
+            if (m > a && (rc = enqueue_level(c, c->d_type + a, c->d_in0 + a, c->d_in1 + a, c->d_out + a, m - a, c->d_in2 + a)))
+                return rc;
             const size_t f = mux_first[lv], cnt = mux_first[lv + 1] - f;
             if (cnt) {
                 if (m > a) c->timer_levels--;              // gates and MUX entries of one level count once
@@ -370,7 +375,7 @@ void she_free(she_ctx *c)
     if (c->pool_owned) hipFree(c->pool);
     hipFree(c->temp);
     hipFree(c->work.bar); hipFree(c->work.ext_b); hipFree(c->work.ksd);
-    hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_out);
+    hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_in2); hipFree(c->d_out);
     hipFree(c->d_stage); hipFree(c->d_round_err); hipFree(c->work.raw_ext);
     hipFree(c->d_mtype); hipFree(c->d_min0); hipFree(c->d_min1); hipFree(c->d_mout);
     free_leveled(c);
@@ -448,6 +453,35 @@ int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const u
     c->timer.clear();
     c->timer_levels = 0;
     if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates))) return rc;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return finish_timing(c);
+}
+
+int she_eval_gates3(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                    const uint32_t *out, size_t ngates)
+{
+    if (!c) return SHE_EINVAL;
+    if (ngates == 0) return SHE_OK;
+    if (!type || !in0 || !in1 || !in2 || !out) return fail(c, SHE_EINVAL, "null argument");
+    for (size_t g = 0; g < ngates; g++)
+        if (type[g] < SHE_MAJ3 || type[g] >= SHE_XOR3 + 8) return fail(c, SHE_EINVAL, "unknown three-input gate code");
+    int rc;
+    if ((rc = check_ids(c, in0, ngates, "she_eval_gates3 in0"))) return rc;
+    if ((rc = check_ids(c, in1, ngates, "she_eval_gates3 in1"))) return rc;
+    if ((rc = check_ids(c, in2, ngates, "she_eval_gates3 in2"))) return rc;
+    if ((rc = check_ids(c, out, ngates, "she_eval_gates3 out"))) return rc;
+    if ((rc = check_disjoint(c, in0, ngates, in1, ngates, out, ngates))) return rc;
+    if ((rc = check_disjoint(c, in2, ngates, nullptr, 0, out, ngates))) return rc;
+    if ((rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK)))) return rc;
+    if ((rc = ensure_gate_arrays(c, ngates))) return rc;
+    HIP_TRY(c, hipMemcpyAsync(c->d_type, type, ngates, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_in0, in0, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_in1, in1, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_in2, in2, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipMemcpyAsync(c->d_out, out, ngates * 4, hipMemcpyHostToDevice, c->stream));
+    c->timer.clear();
+    c->timer_levels = 0;
+    if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates, c->d_in2))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return finish_timing(c);
 }
@@ -583,7 +617,7 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
     const char *why = "";
     if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return fail(c, SHE_EINVAL, why);
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
         const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -605,7 +639,7 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
         const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -628,7 +662,7 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
         const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -641,6 +675,7 @@ int she_set_option(she_ctx *c, int option, int value)
     if (!c) return SHE_EINVAL;
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
+    if (option == SHE_OPT_ADDER_CELLS) { c->adder3 = value != 0; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) {
         if (value < 0) return fail(c, SHE_EINVAL, "SHE_OPT_SPLIT_BELOW takes a gate count >= 0");
         c->split_below = (size_t)value;
@@ -655,6 +690,7 @@ int she_get_option(she_ctx *c, int option, int *value)
     if (!value) return fail(c, SHE_EINVAL, "null argument");
     if (option == SHE_OPT_FOLD_CONSTANTS) { *value = c->fold; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { *value = c->native_mux; return SHE_OK; }
+    if (option == SHE_OPT_ADDER_CELLS) { *value = c->adder3; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) { *value = (int)std::min<size_t>(c->split_below, 0x7FFFFFFF); return SHE_OK; }
     return fail(c, SHE_EINVAL, "unknown option");
 }
@@ -680,7 +716,8 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
     try {
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
+                   (options & SHE_OPT_ADDER_CELLS) != 0);
         wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -694,7 +731,8 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
     try {
         std::vector<uint32_t> ids((size_t)count * bits);
         for (size_t k = 0; k < ids.size(); k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
+        Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
+                   (options & SHE_OPT_ADDER_CELLS) != 0);
         wires_relu(nl, ids.data(), count, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -710,7 +748,8 @@ int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int opti
     try {
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
-        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0);
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
+                   (options & SHE_OPT_ADDER_CELLS) != 0);
         wires_maxpool(nl, ids.data(), H, W, C, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {

@@ -45,7 +45,7 @@ static uint32_t emit_entry(Netlist &nl, int c, uint32_t x, uint32_t y, uint32_t 
 uint64_t Netlist::rotations() const
 {
     uint64_t r = 0;
-    for (uint8_t t : type) r += t >= MUX_BASE ? 2 : 1;
+    for (uint8_t t : type) r += is_mux_type(t) ? 2 : 1;
     return r;
 }
 
@@ -117,6 +117,57 @@ uint32_t Netlist::mux(uint32_t s, uint32_t u, uint32_t v)
     return emit_entry(*this, MUX_BASE + 16 * code1 + code0, s, u & ~WIRE_NEG, v & ~WIRE_NEG);
 }
 
+// Majority or parity of three wire references with ONE bootstrap (the pre-bootstrap sample is +-a +- b +- c, or
+// -2 times it for the parity).  With folding, the cell is first written as a truth table over the distinct plain
+// wires under its operands: no wire left -> a constant; one -> that wire or its complement; two -> a 2-input gate
+// (or a single wire when the pair cancels, e.g. majority(a, not a, c) = c); three -> a three-input entry whose
+// complement mask carries the operands' flips (for the parity only their number matters: mask 0 or 1).
+uint32_t Netlist::gate3(int base, uint32_t a, uint32_t b, uint32_t c)
+{
+    if (!fold) return emit_entry(*this, base, a, b, c);
+    const uint32_t refs[3] = {a, b, c};
+    uint32_t wires[3] = {0, 0, 0};
+    int var_of[3], flips[3], consts[3], n_vars = 0;
+    for (int k = 0; k < 3; k++) {
+        const uint32_t w = refs[k] & ~WIRE_NEG, f = refs[k] >> 31;
+        flips[k] = (int)f;
+        consts[k] = -1;
+        var_of[k] = -1;
+        if (w == zero()) { consts[k] = (int)f; continue; }
+        if (w == one()) { consts[k] = 1 - (int)f; continue; }
+        for (int v = 0; v < n_vars; v++)
+            if (wires[v] == w) var_of[k] = v;
+        if (var_of[k] < 0) { wires[n_vars] = w; var_of[k] = n_vars++; }
+    }
+    // bit `assign` of tt = value of the cell when variable v takes bit v of `assign`
+    uint32_t tt = 0;
+    for (uint32_t assign = 0; assign < (1u << n_vars); assign++) {
+        int ones = 0;
+        for (int k = 0; k < 3; k++) ones += consts[k] >= 0 ? consts[k] : (int)((assign >> var_of[k]) & 1u) ^ flips[k];
+        const uint32_t val = base == SHE_MAJ3 ? (ones >= 2) : (ones & 1);
+        tt |= val << assign;
+    }
+    auto wire_or_not = [&](uint32_t w, uint32_t at0, uint32_t at1) {
+        if (at0 == at1) return at0 ? one() : zero();
+        return at0 ? (w | WIRE_NEG) : w;
+    };
+    if (n_vars == 0) return (tt & 1u) ? one() : zero();
+    if (n_vars == 1) return wire_or_not(wires[0], tt & 1u, (tt >> 1) & 1u);
+    if (n_vars == 2) {
+        const bool needs0 = ((tt ^ (tt >> 1)) & 0x5u) != 0, needs1 = ((tt ^ (tt >> 2)) & 0x3u) != 0;
+        if (!needs1) return wire_or_not(wires[0], tt & 1u, (tt >> 1) & 1u);
+        if (!needs0) return wire_or_not(wires[1], tt & 1u, (tt >> 2) & 1u);
+        // kTruth counts its first operand as the high bit of the index
+        uint8_t table = 0;
+        for (uint32_t x = 0; x < 2; x++)
+            for (uint32_t y = 0; y < 2; y++) table |= (uint8_t)(((tt >> (x + 2 * y)) & 1u) << (2 * x + y));
+        return emit_entry(*this, code_of_truth(table), wires[0], wires[1], 0);
+    }
+    int mask = flips[0] | (flips[1] << 1) | (flips[2] << 2);
+    if (base == SHE_XOR3) mask = (flips[0] + flips[1] + flips[2]) & 1;
+    return emit_entry(*this, base + mask, wires[0], wires[1], wires[2]);
+}
+
 void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst)
 {
     const uint32_t first_temp = cap + 2, unbound = 0xFFFFFFFFu;
@@ -136,7 +187,7 @@ void Netlist::bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *d
     };
     for (size_t g = 0; g < type.size(); g++) {
         fix(in0[g]); fix(in1[g]); fix(out[g]);
-        if (type[g] >= MUX_BASE) fix(in2[g]);
+        if (has_third_operand(type[g])) fix(in2[g]);
     }
     for (auto &w : copy_src) fix(w);
 }
@@ -153,14 +204,14 @@ std::vector<size_t> Netlist::levelize(std::vector<size_t> *mux_start)
     auto depth_of = [&](uint32_t w) { return w >= first_temp ? depth[w - first_temp] : 0u; };
     for (size_t g = 0; g < type.size(); g++) {
         uint32_t d = std::max(depth_of(in0[g]), depth_of(in1[g]));
-        if (type[g] >= MUX_BASE) d = std::max(d, depth_of(in2[g]));
+        if (has_third_operand(type[g])) d = std::max(d, depth_of(in2[g]));
         lev[g] = d + 1;
         depth[out[g] - first_temp] = d + 1;
         deepest = std::max(deepest, d + 1);
     }
     // bucket = 2*level + (1 for a MUX entry): gates of a level come before its MUX entries
     std::vector<size_t> start(2 * (size_t)deepest + 3, 0);
-    auto bucket = [&](size_t g) { return 2 * (size_t)lev[g] + (type[g] >= MUX_BASE ? 1 : 0); };
+    auto bucket = [&](size_t g) { return 2 * (size_t)lev[g] + (is_mux_type(type[g]) ? 1 : 0); };
     for (size_t g = 0; g < type.size(); g++) start[bucket(g) + 1]++;
     for (size_t i = 1; i < start.size(); i++) start[i] += start[i - 1];
     std::vector<size_t> cursor(start.begin(), start.end() - 1);
@@ -191,6 +242,16 @@ std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const 
     sum.push_back(nl.gate(SHE_XOR, a[0], b[0]));
     if (w == 1 && cap_bits == 1) return sum;
     uint32_t carry = nl.gate(SHE_AND, a[0], b[0]);
+    if (nl.adder3) {
+        // full-adder cell: sum = parity(a_i, b_i, carry), next carry = majority of the same three
+        for (size_t i = 1; i < w; i++) {
+            sum.push_back(nl.gate3(SHE_XOR3, a[i], b[i], carry));
+            if (i + 1 == w && w >= cap_bits) return sum;
+            carry = nl.gate3(SHE_MAJ3, a[i], b[i], carry);
+        }
+        sum.push_back(carry);
+        return sum;
+    }
     for (size_t i = 1; i < w; i++) {
         const uint32_t half = nl.gate(SHE_XOR, a[i], b[i]);
         sum.push_back(nl.gate(SHE_XOR, half, carry));
@@ -209,6 +270,16 @@ std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const 
     const size_t w = p.size();
     std::vector<uint32_t> diff;
     uint32_t carry = nl.one();
+    if (nl.adder3) {
+        // the same cell on (p_i, not q_i, carry); without folding the complement sits in the entry's mask
+        for (size_t i = 0; i < w; i++) {
+            diff.push_back(nl.fold ? nl.gate3(SHE_XOR3, p[i], q[i] ^ WIRE_NEG, carry)
+                                   : emit_entry(nl, SHE_XOR3 + 1, p[i], q[i], carry));
+            if (i + 1 == w) break;
+            carry = nl.fold ? nl.gate3(SHE_MAJ3, p[i], q[i] ^ WIRE_NEG, carry) : emit_entry(nl, SHE_MAJ3 + 2, p[i], q[i], carry);
+        }
+        return diff;
+    }
     for (size_t i = 0; i < w; i++) {
         const uint32_t half = nl.gate(SHE_XNOR, p[i], q[i]);
         diff.push_back(nl.gate(SHE_XOR, half, carry));

@@ -43,7 +43,7 @@ struct she_ctx {
     she::LevelWork work;
     // device staging for host-array calls (grown on demand)
     uint8_t *d_type = nullptr;
-    uint32_t *d_in0 = nullptr, *d_in1 = nullptr, *d_out = nullptr;
+    uint32_t *d_in0 = nullptr, *d_in1 = nullptr, *d_in2 = nullptr, *d_out = nullptr;
     size_t d_gate_cap = 0;
     uint32_t *d_stage = nullptr;         // ciphertext staging [slots][n+1] and id lists
     size_t d_stage_words = 0;
@@ -51,6 +51,7 @@ struct she_ctx {
     bool track_round = false;
     bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
     bool native_mux = false;             // SHE_OPT_NATIVE_MUX
+    bool adder3 = false;                 // SHE_OPT_ADDER_CELLS
     size_t split_below = 0;              // SHE_OPT_SPLIT_BELOW (set at creation: 6 x compute units)
     uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
     uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;

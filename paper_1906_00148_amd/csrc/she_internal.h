@@ -56,8 +56,9 @@ hipError_t launch_trgsw_transform(const she_params &P, const DeviceKeys &K, cons
 hipError_t launch_cmux(const she_params &P, const DeviceKeys &K, const double2 *trgsw_hat, uint32_t *trlwe,
                        const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
                        size_t count, unsigned *d_round_err, hipStream_t st);
+// d_in2 may be null when no type is a three-input gate
 hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
-                          const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st);
+                          const uint32_t *d_in1, const uint32_t *d_in2, size_t gates, const LevelWork &W, hipStream_t st);
 hipError_t launch_blind_rotate(const she_params &P, const DeviceKeys &K, const CtSpace &cs, const uint32_t *d_out,
                                size_t gates, const LevelWork &W, unsigned *d_round_err /* nullptr = no tracking */,
                                hipStream_t st, bool raw = false /* write W.raw_ext instead of digits and slots */,
@@ -98,7 +99,9 @@ void phases_to_bits(const she_params &P, const std::vector<uint8_t> &lwe_key, co
 
 // ---- netlists of the layer operators (she_circuits.cpp) ----
 constexpr uint32_t WIRE_NEG = 0x80000000u;   // flag on a wire reference: the complement of that wire
-constexpr int MUX_BASE = SHE_NUM_GATES;       // netlist type of a native MUX entry: MUX_BASE + 16*code1 + code0
+constexpr int MUX_BASE = SHE_NUM_GATES;       // netlist type of a native MUX entry: MUX_BASE + 16*code1 + code0 (< SHE_MAJ3)
+inline bool is_mux_type(uint8_t t) { return t >= MUX_BASE && t < SHE_MAJ3; }
+inline bool has_third_operand(uint8_t t) { return t >= MUX_BASE; }     // MUX entries and three-input gates
 
 struct Netlist {
     // wire ids: [0, cap) pool slots, cap = trivial 0, cap+1 = trivial 1, cap+2.. temporaries.
@@ -110,18 +113,21 @@ struct Netlist {
     uint32_t next_temp = 0;
     bool fold = false;
     bool native_mux = false;                    // mux() emits one three-input entry instead of three gates
+    bool adder3 = false;                        // adders use cells of two three-input gates (parity, majority)
     bool overflow = false;                      // more wires than 31-bit ids can name
     std::vector<uint8_t> type;
-    std::vector<uint32_t> in0, in1, in2, out;   // in2: third operand of MUX entries (0 otherwise)
+    std::vector<uint32_t> in0, in1, in2, out;   // in2: third operand of MUX entries and three-input gates (0 otherwise)
     std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates; copy_src may carry WIRE_NEG
 
-    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false)
-        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native) {}
+    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false, bool adder_cells = false)
+        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native), adder3(adder_cells) {}
     uint64_t rotations() const;                 // blind rotations: one per gate, two per MUX entry
     uint32_t zero() const { return cap; }
     uint32_t one() const { return cap + 1; }
     uint32_t gate(int code, uint32_t a, uint32_t b);
     uint32_t mux(uint32_t s, uint32_t u, uint32_t v);
+    // majority (base SHE_MAJ3) or parity (base SHE_XOR3) of three wires with one bootstrap
+    uint32_t gate3(int base, uint32_t a, uint32_t b, uint32_t c);
     // route the wires in `wires` to the caller's ids `dst`: gate outputs are renamed,
     // anything else (inputs, constants, a wire used twice) is copied at the end
     void bind_outputs(const std::vector<uint32_t> &wires, const uint32_t *dst);

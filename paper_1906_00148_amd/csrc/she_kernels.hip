@@ -26,12 +26,28 @@ __device__ __forceinline__ uint32_t *ct_ptr(const CtSpace &cs, uint32_t id)
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(128) void k_lincomb(CtSpace cs, const uint8_t *__restrict__ type,
                                                  const uint32_t *__restrict__ in0, const uint32_t *__restrict__ in1,
-                                                 uint32_t n, uint32_t log2_2N, uint16_t *__restrict__ bar,
-                                                 uint32_t bar_stride)
+                                                 const uint32_t *__restrict__ in2, uint32_t n, uint32_t log2_2N,
+                                                 uint16_t *__restrict__ bar, uint32_t bar_stride)
 {
     const uint32_t g = blockIdx.x;
     const uint32_t ty = type[g];
     const uint32_t e = 1u << 29;
+    const uint32_t rnd = 1u << (31 - log2_2N), sh = 32 - log2_2N;
+    uint16_t *dst = bar + (size_t)g * bar_stride;
+    if (ty >= SHE_MAJ3) {
+        // three-input gate: s = +-ca +- cb +- cc has phase (2k-3)/8 for k true inputs; majority is the sign of s,
+        // parity the sign of -2s (phase +1/4 for odd k, -1/4 for even k); no offset (in2 is non-null for these)
+        const uint32_t m = ty - SHE_MAJ3;
+        const bool parity = (m >> 3) != 0;
+        const uint32_t *ca = ct_ptr(cs, in0[g]), *cb = ct_ptr(cs, in1[g]), *cc = ct_ptr(cs, in2[g]);
+        for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) {
+            const uint32_t a = ca[i], b = cb[i], c = cc[i];
+            uint32_t x = ((m & 1) ? 0u - a : a) + ((m & 2) ? 0u - b : b) + ((m & 4) ? 0u - c : c);
+            if (parity) x = 0u - 2u * x;
+            dst[i] = (uint16_t)((x + rnd) >> sh);
+        }
+        return;
+    }
     // sign of ca, sign of cb, offset, doubling
     uint32_t off = e; bool na = false, nb = false, dbl = false;
     switch (ty) {
@@ -48,8 +64,6 @@ __global__ __launch_bounds__(128) void k_lincomb(CtSpace cs, const uint8_t *__re
     }
     const uint32_t *ca = ct_ptr(cs, in0[g]);
     const uint32_t *cb = ct_ptr(cs, in1[g]);
-    uint16_t *dst = bar + (size_t)g * bar_stride;
-    const uint32_t rnd = 1u << (31 - log2_2N), sh = 32 - log2_2N;
     for (uint32_t i = threadIdx.x; i <= n; i += blockDim.x) {
         uint32_t a = ca[i], b = cb[i];
         uint32_t x = (na ? 0u - a : a) + (nb ? 0u - b : b);
@@ -808,10 +822,10 @@ hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, co
 static uint32_t ilog2(uint32_t v) { uint32_t r = 0; while ((1u << r) < v) r++; return r; }
 
 hipError_t launch_lincomb(const she_params &P, const CtSpace &cs, const uint8_t *d_type, const uint32_t *d_in0,
-                          const uint32_t *d_in1, size_t gates, const LevelWork &W, hipStream_t st)
+                          const uint32_t *d_in1, const uint32_t *d_in2, size_t gates, const LevelWork &W, hipStream_t st)
 {
     if (!gates) return hipSuccess;
-    hipLaunchKernelGGL(k_lincomb, dim3((unsigned)gates), dim3(128), 0, st, cs, d_type, d_in0, d_in1, P.n,
+    hipLaunchKernelGGL(k_lincomb, dim3((unsigned)gates), dim3(128), 0, st, cs, d_type, d_in0, d_in1, d_in2, P.n,
                        ilog2(2 * P.N), W.bar, W.bar_stride);
     return hipGetLastError();
 }

@@ -410,3 +410,58 @@ def test_other_parameter_shapes_use_the_generic_key_switch(shape):
         ctx.eval_mux([0, 3], [1, 4], [2, 5], [60, 61])
         for m, (s, a, b) in enumerate(((0, 1, 2), (3, 4, 5))):
             assert np.array_equal(ctx.read_ct(60 + m), O.mux(K, pool[s], pool[a], pool[b]))
+
+
+# ------------------------------------------------------------------ three-input gates and full-adder cells
+def test_eval_gates3_bit_exact_toy_and_real(toy_ctx, toy_keys, real_ctx, real_keys):
+    """Majority and parity with one bootstrap: every code at toy parameters on a ragged level, four codes at real
+    parameters; ciphertext words against the oracle and decrypted bits against plain logic."""
+    pkg = she()
+    for ctx, K, codes, reps in ((toy_ctx, toy_keys, [pkg.MAJ3 + m for m in range(8)] + [pkg.XOR3 + m for m in range(8)], 5),
+                                (real_ctx, real_keys, [pkg.MAJ3, pkg.MAJ3 + 5, pkg.XOR3, pkg.XOR3 + 3], 3)):
+        rng = np.random.default_rng(61)
+        G = len(codes) * reps + 1                                  # odd count: a ragged last workgroup
+        gt = np.array((codes * reps + [codes[0]])[:G], np.uint8)
+        bits = rng.integers(0, 2, 3 * G).astype(np.uint8)
+        in_ids = np.arange(3 * G, dtype=np.uint32)
+        out_ids = np.arange(3 * G, 4 * G, dtype=np.uint32)
+        ctx.encrypt_bits(bits, 88, in_ids)
+        ctx.eval_gates3(gt, in_ids[0::3], in_ids[1::3], in_ids[2::3], out_ids)
+        pool = np.zeros((4 * G, K.params.n + 1), np.uint32)
+        pool[:3 * G] = O.encrypt_bits(K, bits, 88)
+        O.eval_netlist(K, pool, gt.astype(np.uint32), in_ids[0::3], in_ids[1::3], in_ids[2::3], out_ids, threads=8)
+        assert np.array_equal(ctx.read_cts(out_ids), pool[3 * G:])
+        want = [OC.plain_gate3(int(t), int(bits[3 * g]), int(bits[3 * g + 1]), int(bits[3 * g + 2])) for g, t in enumerate(gt)]
+        assert ctx.decrypt(out_ids).tolist() == want
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates3([3], [0], [1], [2], [9])               # a 2-input code
+    assert e.value.code == -1
+    with pytest.raises(pkg.SheError) as e:
+        toy_ctx.eval_gates3([pkg.MAJ3], [0], [1], [2], [2])        # output is the third input
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("fold", [False, True])
+def test_shift_acc_with_adder_cells_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold):
+    pkg = she()
+    toy_ctx.set_option(pkg.OPT_ADDER_CELLS, 1)
+    toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
+    try:
+        assert toy_ctx.get_option(pkg.OPT_ADDER_CELLS) == 1
+        x = np.array([[5, 7, 2, 6, 1, 4, 7], [3, 3, 0, 7, 4, 1, 6]])
+        sign = np.array([[1, -1, 1, 1, -1, 1, 1], [1, 1, 1, 1, 1, 1, 1]], np.int8)
+        exp = np.array([[0, -1, 0, -2, 0, 0, -1], [0, 0, -1, -2, -2, 0, 0]], np.int8)
+        in_bits, acc_bits = 3, 6
+        ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 71, 0)
+        out_ids = np.arange(1000, 1000 + 2 * acc_bits, dtype=np.uint32).reshape(2, acc_bits)
+        gates = toy_ctx.shift_acc(ids.reshape(2, 7, in_bits), sign, exp, acc_bits, out_ids)
+        nl, outs = OC.build_shift_acc(2, 7, in_bits, sign, exp, acc_bits, fold=fold, adder3=True)
+        plain, _ = OC.build_shift_acc(2, 7, in_bits, sign, exp, acc_bits, fold=fold)
+        assert gates == len(nl.gtype) < len(plain.gtype)
+        assert any(t >= O.GATE3_BASE for t in nl.gtype)
+        pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+        assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(out_ids), True), OC.plain_shift_acc(x, sign, exp, acc_bits))
+    finally:
+        toy_ctx.set_option(pkg.OPT_ADDER_CELLS, 0)
+        toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
