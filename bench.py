@@ -58,10 +58,11 @@ def cpu_baseline(sample_gates: int):
                       f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
 
 
-def conv_layer(ctx_factory, fold: bool, native_mux: bool = False):
+def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, adder_cells: bool = False):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
     accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
-    skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS)."""
+    skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); adder_cells: full-adder cells of
+    two three-input gates (SHE_OPT_ADDER_CELLS)."""
     import numpy as np
 
     import synth_inputs as S
@@ -77,6 +78,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False):
     ctx = ctx_factory(int(pool_ids[-1]) + 1)
     ctx.set_option(1, int(fold))
     ctx.set_option(2, int(native_mux))
+    ctx.set_option(4, int(adder_cells))
     bits = ((img[..., None] >> np.arange(8)) & 1).astype(np.uint8)
     in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, 8)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(5), in_ids.ravel())
@@ -109,7 +111,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False):
     ctx.close()
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
-            "constant_folding": bool(fold), "native_mux": bool(native_mux),
+            "constant_folding": bool(fold), "native_mux": bool(native_mux), "adder_cells": bool(adder_cells),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -117,7 +119,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False):
 
 def network(ctx_factory):
     """A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
-    network's layer sequence, shrunk), chained on the device without decrypting in between; folding and native MUX on."""
+    network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX and full-adder cells on."""
     import numpy as np
 
     import synth_inputs as S
@@ -147,6 +149,7 @@ def network(ctx_factory):
     ctx = ctx_factory(32768)
     ctx.set_option(1, 1)
     ctx.set_option(2, 1)
+    ctx.set_option(4, 1)
     bits = ((img[..., None, None] >> np.arange(8)) & 1).astype(np.uint8)
     x_ids = np.arange(bits.size, dtype=np.uint32).reshape(bits.shape)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
@@ -162,8 +165,43 @@ def network(ctx_factory):
     assert np.array_equal(got, want), "network decrypts wrongly"
     ctx.close()
     return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
-                        "constant folding and native MUX on", "latency_s": dt, "entries": int(net.gates),
+                        "constant folding, native MUX and full-adder cells on", "latency_s": dt, "entries": int(net.gates),
             "entries_per_s": net.gates / dt}
+
+
+def cmux_level(ctx_factory, count: int = 4096, reps: int = 5):
+    """Leveled mode: one level of `count` independent CMuxes (TRGSW selector x TRLWE data) at N=1024; the kernel's
+    time from the library's HIP events, and a check that every output carries the selected branch's message."""
+    import numpy as np
+
+    ctx = ctx_factory(16)
+    N = ctx.params.N
+    nsel, ndat = 64, 256
+    ctx.leveled_init(nsel, ndat + count)
+    rng = np.random.default_rng(2024)
+    sel_bits = rng.integers(0, 2, nsel).astype(np.uint8)
+    ctx.trgsw_encrypt_bits(sel_bits, 1, np.arange(nsel, dtype=np.uint32))
+    mu = np.where(rng.integers(0, 2, (ndat, N)) == 1, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
+    ctx.trlwe_encrypt(mu, 2, np.arange(ndat, dtype=np.uint32))
+    s, i1, i0 = rng.integers(0, nsel, count), rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+    out = (ndat + np.arange(count)).astype(np.uint32)
+    ms = []
+    for _ in range(reps):
+        ctx.eval_cmux(s, i1, i0, out)
+        ms.append(ctx.last_timing()["blind_rotate_ms"])
+    phases = ctx.trlwe_phase(out[:64]).astype(np.int32)
+    for m in range(64):
+        want = mu[i1[m]] if sel_bits[s[m]] else mu[i0[m]]
+        assert np.array_equal(phases[m] > 0, want.astype(np.int32) > 0), "CMux selected the wrong branch"
+    ctx.close()
+    best = float(np.median(ms))
+    flop = 0.258e6 * count                      # the same count per CMux as one step of the blind rotation
+    # bytes that must move: two TRLWE operands in, one out (8 KiB each) per CMux, every distinct selector (96 KiB) once
+    moved = count * 3 * 2 * N * 4 + nsel * 2 * 3 * 2 * (N // 2) * 16
+    return {"workload": f"one level of {count} CMuxes over {nsel} distinct selectors, N=1024 l=3 Bgbit=7 "
+                        "(leveled mode: no bootstrap)",
+            "kernel_ms": best, "cmux_per_s": count / (best * 1e-3), "achieved_tflops": flop / (best * 1e-3) / 1e12,
+            "algorithmic_bytes": moved, "achieved_gb_per_s": moved / (best * 1e-3) / 1e9}
 
 
 def main():
@@ -250,8 +288,10 @@ def main():
         del src, dst
     if not args.no_conv_layer:
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
-        out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True)
+        out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True,
+                                            adder_cells=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
+        out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))
