@@ -28,11 +28,11 @@ GATES_PER_LEVEL = 4096
 FLOP_PER_CMUX = 8 * (5 * 512 * 9 + 6 * 512) + 12 * 512 * 8
 FLOP_PER_GATE = 630 * FLOP_PER_CMUX
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop/FMA x 2.4 GHz
-# HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 959,072 KiB scaled by 2.00,
-# WRITE_SIZE 108,893 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
+# HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 960,333 KiB scaled by 2.00,
+# WRITE_SIZE 95,433 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
 # profiles/k_blind_rotate_level4096_n630_N1024_counters.txt.  Algorithmic bytes are ~75 MB: the excess is the
 # key spectra streamed once per XCD L2 and per resident batch (8 x 2 x 61.9 MB), served by the Infinity Cache.
-MEASURED_TRAFFIC_BYTES = 2.08e9
+MEASURED_TRAFFIC_BYTES = 2.06e9
 
 
 def cpu_baseline(sample_gates: int):
