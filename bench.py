@@ -58,11 +58,11 @@ def cpu_baseline(sample_gates: int):
                       f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
 
 
-def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, adder_cells: bool = False):
+def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
     accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
-    skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); adder_cells: full-adder cells of
-    two three-input gates (SHE_OPT_ADDER_CELLS)."""
+    skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); cells3: full-adder cells of
+    two three-input gates (SHE_OPT_GATE3_CELLS)."""
     import numpy as np
 
     import synth_inputs as S
@@ -78,7 +78,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, adder_cells: b
     ctx = ctx_factory(int(pool_ids[-1]) + 1)
     ctx.set_option(1, int(fold))
     ctx.set_option(2, int(native_mux))
-    ctx.set_option(4, int(adder_cells))
+    ctx.set_option(4, int(cells3))
     bits = ((img[..., None] >> np.arange(8)) & 1).astype(np.uint8)
     in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, 8)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(5), in_ids.ravel())
@@ -111,7 +111,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, adder_cells: b
     ctx.close()
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
-            "constant_folding": bool(fold), "native_mux": bool(native_mux), "adder_cells": bool(adder_cells),
+            "constant_folding": bool(fold), "native_mux": bool(native_mux), "cells3": bool(cells3),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -289,7 +289,7 @@ def main():
     if not args.no_conv_layer:
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
         out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True,
-                                            adder_cells=True)
+                                            cells3=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:

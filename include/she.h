@@ -109,7 +109,7 @@ int she_eval_gates(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const
  *   SHE_MAJ3: pre-bootstrap sample +-c0 +- c1 +- c2, phase (2k-3)/8 for k true inputs, sign = majority;
  *   SHE_XOR3: -2 times that sample, phase +1/4 for odd k and -1/4 for even k.
  * A full-adder cell is sum = XOR3(a, b, carry), next carry = MAJ3(a, b, carry): two bootstraps instead of
- * five (see SHE_OPT_ADDER_CELLS).  Decision margins against the output noise of earlier bootstraps stay above
+ * five (see SHE_OPT_GATE3_CELLS).  Decision margins against the output noise of earlier bootstraps stay above
  * 20 standard deviations at the supported parameter sets.  Same id rules and error codes as she_eval_gates. */
 int she_eval_gates3(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                     const uint32_t *out, size_t ngates);
@@ -150,7 +150,7 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
  * gate becomes a constant, its other operand, or that operand's complement, and complements are
  * absorbed into the next gate's code or applied as a free word-wise negation (Section 3.2: what
  * only re-wires ciphertexts costs no gate).  Results decrypt identically; gate counts drop. */
-enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2, SHE_OPT_SPLIT_BELOW = 3, SHE_OPT_ADDER_CELLS = 4 };
+enum { SHE_OPT_FOLD_CONSTANTS = 1, SHE_OPT_NATIVE_MUX = 2, SHE_OPT_SPLIT_BELOW = 3, SHE_OPT_GATE3_CELLS = 4 };
 int she_set_option(she_ctx *ctx, int option, int value);
 int she_get_option(she_ctx *ctx, int option, int *value);   /* SHE_EINVAL for an unknown option or a null pointer */
 /* SHE_OPT_SPLIT_BELOW (default: 6 x the device's compute units, 1536 on MI355X): a kernel launch of at
@@ -158,9 +158,11 @@ int she_get_option(she_ctx *ctx, int option, int *value);   /* SHE_EINVAL for an
  * which shortens the serial chain per CMux when the level is too small to fill the chip; larger launches
  * keep one wavefront per rotation.  0 never splits.  Every ciphertext comes out the same word for word
  * either way (both kernels round exact integers). */
-/* SHE_OPT_ADDER_CELLS (default 0): the adders and the subtraction of she_shift_acc use full-adder cells of two
- * three-input gates (she_eval_gates3) above the lowest bit: a w-bit adder costs 2w gates in w levels instead of
- * 5w-3 gates in 2w-1 levels (a 576-term 8-bit tree: 10,332 gates instead of 24,104).  Results decrypt identically. */
+/* SHE_OPT_GATE3_CELLS (default 0): the operators use three-input gates (she_eval_gates3).  The adders and the
+ * subtraction of she_shift_acc become full-adder cells of two gates above the lowest bit: a w-bit adder costs 2w gates
+ * in w levels instead of 5w-3 gates in 2w-1 levels (a 576-term 8-bit tree: 10,332 gates instead of 24,104).  The
+ * comparator of she_maxpool becomes one majority gate per bit, majority(x_i, not y_i, greater-so-far), instead of an
+ * equality gate and a MUX per bit.  Results decrypt identically. */
 /* SHE_OPT_NATIVE_MUX (default 0): she_maxpool evaluates every MUX of its comparators and selectors
  * with she_eval_mux's three-input gate instead of three 2-input gates (7w gates per max become
  * w gates + 2w MUX entries = 5w blind rotations and 3w key switches, and half the levels). */

@@ -130,7 +130,8 @@ class Netlist:
     n_inputs: int
     fold: bool = False
     native_mux: bool = False     # mux() emits one three-input MUX entry (two blind rotations, one key switch)
-    adder3: bool = False         # adders use full-adder cells of two three-input gates (parity + majority)
+    cells3: bool = False         # adders use full-adder cells of two three-input gates (parity + majority),
+                                 # comparators one majority gate per bit
     gtype: list = field(default_factory=list)
     in0: list = field(default_factory=list)
     in1: list = field(default_factory=list)
@@ -328,7 +329,7 @@ def add_unsigned(nl: Netlist, a: list, b: list, cap: int) -> list:
     if w == 1 and cap == 1:
         return out
     c = nl.gate("AND", a[0], b[0])
-    if nl.adder3:                       # full-adder cell = parity and majority of (a_i, b_i, carry): 2w gates
+    if nl.cells3:                       # full-adder cell = parity and majority of (a_i, b_i, carry): 2w gates
         for i in range(1, w):
             out.append(nl.gate3("XOR", a[i], b[i], c))
             if i == w - 1 and w >= cap:
@@ -354,7 +355,7 @@ def sub_wrapped(nl: Netlist, p: list, q: list) -> list:
     w = len(p)
     assert len(q) == w
     out, c = [], nl.ONE
-    if nl.adder3:                       # the same cell on (p_i, not q_i, carry)
+    if nl.cells3:                       # the same cell on (p_i, not q_i, carry)
         for i in range(w):
             out.append(nl.gate3("XOR", p[i], q[i] ^ NEG, c) if nl.fold else nl._emit(tfhe.XOR3 + 1, p[i], q[i], c))
             if i == w - 1:
@@ -400,11 +401,11 @@ def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
 
 
 def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                    adder3: bool = False):
+                    cells3: bool = False):
     """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits])."""
     w_sign = np.asarray(w_sign).reshape(units, terms)
     w_exp = np.asarray(w_exp).reshape(units, terms)
-    nl = Netlist(units * terms * in_bits, fold, adder3=adder3)
+    nl = Netlist(units * terms * in_bits, fold, cells3=cells3)
     outs = []
     for u in range(units):
         pos, neg = [], []
@@ -436,6 +437,13 @@ def max_signed(nl: Netlist, x: list, y: list) -> list:
     (gt = "x > y on the bits seen so far"), sign bits compared the other way
     round, then one MUX per bit."""
     w = len(x)
+    if nl.cells3:
+        # one majority gate per bit: MAJ(x_i, not y_i, gt) is 1 for (1, 0), 0 for (0, 1) and gt for equal bits
+        gt = nl.ZERO
+        for i in range(w):
+            a, b = (x[i], y[i]) if i < w - 1 else (y[i], x[i])       # the sign position decides the other way round
+            gt = nl.gate3("MAJ", a, b ^ NEG, gt) if nl.fold else nl._emit(tfhe.MAJ3 + 2, a, b, gt)
+        return [nl.mux(gt, x[i], y[i]) for i in range(w)]
     e = [nl.gate("XNOR", x[i], y[i]) for i in range(w)]
     gt = nl.ZERO
     for i in range(w - 1):
@@ -444,8 +452,8 @@ def max_signed(nl: Netlist, x: list, y: list) -> list:
     return [nl.mux(gt, x[i], y[i]) for i in range(w)]
 
 
-def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False):
-    nl = Netlist(H * W * Cn * bits, fold, native_mux)
+def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False, cells3: bool = False):
+    nl = Netlist(H * W * Cn * bits, fold, native_mux, cells3)
 
     def px(h, w, c):
         base = ((h * W + w) * Cn + c) * bits

@@ -129,12 +129,12 @@ def _p(a, ty):
 OPT_FOLD_CONSTANTS = 1
 OPT_NATIVE_MUX = 2
 OPT_SPLIT_BELOW = 3
-OPT_ADDER_CELLS = 4
+OPT_GATE3_CELLS = 4
 MAJ3, XOR3 = 176, 184        # three-input gate codes; + mask (bit i complements input i)
 
 
-def _options(fold: bool, native_mux: bool, adder_cells: bool = False) -> int:
-    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0) | (OPT_ADDER_CELLS if adder_cells else 0)
+def _options(fold: bool, native_mux: bool, cells3: bool = False) -> int:
+    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0) | (OPT_GATE3_CELLS if cells3 else 0)
 
 
 def _plan(rc, gates, levels):
@@ -144,12 +144,12 @@ def _plan(rc, gates, levels):
 
 
 def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                   adder_cells: bool = False):
+                   cells3: bool = False):
     """(gates, levels) of she_shift_acc for these weights; runs on the host, no GPU needed."""
     w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
     g, lv = C.c_uint64(0), C.c_uint32(0)
     return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
-                                                   acc_bits, _options(fold, False, adder_cells), C.byref(g), C.byref(lv),
+                                                   acc_bits, _options(fold, False, cells3), C.byref(g), C.byref(lv),
                                                    None), g, lv)
 
 
@@ -159,10 +159,11 @@ def plan_relu(count: int, bits: int, fold: bool = False):
 
 
 def plan_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False,
-                 with_rotations: bool = False):
+                 with_rotations: bool = False, cells3: bool = False):
     """(entries, levels) or, with_rotations, (entries, levels, blind rotations)."""
     g, lv, rot = C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
-    rc = load_library().she_plan_maxpool(H, W, Cn, bits, _options(fold, native_mux), C.byref(g), C.byref(lv), C.byref(rot))
+    rc = load_library().she_plan_maxpool(H, W, Cn, bits, _options(fold, native_mux, cells3), C.byref(g), C.byref(lv),
+                                         C.byref(rot))
     out = _plan(rc, g, lv)
     return out + (rot.value,) if with_rotations else out
 

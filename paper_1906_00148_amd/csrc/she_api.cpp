@@ -617,7 +617,7 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
     const char *why = "";
     if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return fail(c, SHE_EINVAL, why);
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
         const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -639,7 +639,7 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
         const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -662,7 +662,7 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->adder3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
         const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -675,7 +675,7 @@ int she_set_option(she_ctx *c, int option, int value)
     if (!c) return SHE_EINVAL;
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
-    if (option == SHE_OPT_ADDER_CELLS) { c->adder3 = value != 0; return SHE_OK; }
+    if (option == SHE_OPT_GATE3_CELLS) { c->cells3 = value != 0; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) {
         if (value < 0) return fail(c, SHE_EINVAL, "SHE_OPT_SPLIT_BELOW takes a gate count >= 0");
         c->split_below = (size_t)value;
@@ -690,7 +690,7 @@ int she_get_option(she_ctx *c, int option, int *value)
     if (!value) return fail(c, SHE_EINVAL, "null argument");
     if (option == SHE_OPT_FOLD_CONSTANTS) { *value = c->fold; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { *value = c->native_mux; return SHE_OK; }
-    if (option == SHE_OPT_ADDER_CELLS) { *value = c->adder3; return SHE_OK; }
+    if (option == SHE_OPT_GATE3_CELLS) { *value = c->cells3; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) { *value = (int)std::min<size_t>(c->split_below, 0x7FFFFFFF); return SHE_OK; }
     return fail(c, SHE_EINVAL, "unknown option");
 }
@@ -717,7 +717,7 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_ADDER_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0);
         wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -732,7 +732,7 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
         std::vector<uint32_t> ids((size_t)count * bits);
         for (size_t k = 0; k < ids.size(); k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_ADDER_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0);
         wires_relu(nl, ids.data(), count, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -749,7 +749,7 @@ int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int opti
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_ADDER_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0);
         wires_maxpool(nl, ids.data(), H, W, C, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {

@@ -242,7 +242,7 @@ std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const 
     sum.push_back(nl.gate(SHE_XOR, a[0], b[0]));
     if (w == 1 && cap_bits == 1) return sum;
     uint32_t carry = nl.gate(SHE_AND, a[0], b[0]);
-    if (nl.adder3) {
+    if (nl.cells3) {
         // full-adder cell: sum = parity(a_i, b_i, carry), next carry = majority of the same three
         for (size_t i = 1; i < w; i++) {
             sum.push_back(nl.gate3(SHE_XOR3, a[i], b[i], carry));
@@ -270,7 +270,7 @@ std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const 
     const size_t w = p.size();
     std::vector<uint32_t> diff;
     uint32_t carry = nl.one();
-    if (nl.adder3) {
+    if (nl.cells3) {
         // the same cell on (p_i, not q_i, carry); without folding the complement sits in the entry's mask
         for (size_t i = 0; i < w; i++) {
             diff.push_back(nl.fold ? nl.gate3(SHE_XOR3, p[i], q[i] ^ WIRE_NEG, carry)
@@ -318,6 +318,18 @@ std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> te
 std::vector<uint32_t> nl_max(Netlist &nl, const std::vector<uint32_t> &x, const std::vector<uint32_t> &y)
 {
     const size_t w = x.size();
+    if (nl.cells3) {
+        // "x > y so far" from one majority gate per bit: majority(x_i, not y_i, gt) is 1 where x has the 1, 0 where y
+        // has it, and gt where the bits agree; at the sign position the operands swap roles
+        uint32_t above = nl.zero();
+        for (size_t i = 0; i < w; i++) {
+            const uint32_t hi = i + 1 < w ? x[i] : y[i], lo = i + 1 < w ? y[i] : x[i];
+            above = nl.fold ? nl.gate3(SHE_MAJ3, hi, lo ^ WIRE_NEG, above) : emit_entry(nl, SHE_MAJ3 + 2, hi, lo, above);
+        }
+        std::vector<uint32_t> best(w);
+        for (size_t i = 0; i < w; i++) best[i] = nl.mux(above, x[i], y[i]);
+        return best;
+    }
     std::vector<uint32_t> eq(w);
     for (size_t i = 0; i < w; i++) eq[i] = nl.gate(SHE_XNOR, x[i], y[i]);
     uint32_t gt = nl.zero();

@@ -113,14 +113,14 @@ struct Netlist {
     uint32_t next_temp = 0;
     bool fold = false;
     bool native_mux = false;                    // mux() emits one three-input entry instead of three gates
-    bool adder3 = false;                        // adders use cells of two three-input gates (parity, majority)
+    bool cells3 = false;                        // adders use cells of two three-input gates (parity, majority)
     bool overflow = false;                      // more wires than 31-bit ids can name
     std::vector<uint8_t> type;
     std::vector<uint32_t> in0, in1, in2, out;   // in2: third operand of MUX entries and three-input gates (0 otherwise)
     std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates; copy_src may carry WIRE_NEG
 
-    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false, bool adder_cells = false)
-        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native), adder3(adder_cells) {}
+    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false, bool cells3 = false)
+        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native), cells3(cells3) {}
     uint64_t rotations() const;                 // blind rotations: one per gate, two per MUX entry
     uint32_t zero() const { return cap; }
     uint32_t one() const { return cap + 1; }

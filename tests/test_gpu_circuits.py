@@ -114,7 +114,7 @@ def test_cfg5_conv_layer_full(fold, cells):
     n_pool = (oh // 2) * (ow // 2) * oc * 16
     with pkg.Context(pkg.REAL, S.KEY_SEED, n_in + 2 * n_conv + n_pool) as c:
         c.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
-        c.set_option(pkg.OPT_ADDER_CELLS, int(cells))
+        c.set_option(pkg.OPT_GATE3_CELLS, int(cells))
         c.set_option(pkg.OPT_NATIVE_MUX, int(cells))
         in_ids = encrypt_values(c, img, 8, S.data_seed(5))                       # [H][W][8]
         x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)

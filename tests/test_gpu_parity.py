@@ -442,12 +442,12 @@ def test_eval_gates3_bit_exact_toy_and_real(toy_ctx, toy_keys, real_ctx, real_ke
 
 
 @pytest.mark.parametrize("fold", [False, True])
-def test_shift_acc_with_adder_cells_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold):
+def test_shift_acc_with_cells3_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold):
     pkg = she()
-    toy_ctx.set_option(pkg.OPT_ADDER_CELLS, 1)
+    toy_ctx.set_option(pkg.OPT_GATE3_CELLS, 1)
     toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
     try:
-        assert toy_ctx.get_option(pkg.OPT_ADDER_CELLS) == 1
+        assert toy_ctx.get_option(pkg.OPT_GATE3_CELLS) == 1
         x = np.array([[5, 7, 2, 6, 1, 4, 7], [3, 3, 0, 7, 4, 1, 6]])
         sign = np.array([[1, -1, 1, 1, -1, 1, 1], [1, 1, 1, 1, 1, 1, 1]], np.int8)
         exp = np.array([[0, -1, 0, -2, 0, 0, -1], [0, 0, -1, -2, -2, 0, 0]], np.int8)
@@ -455,7 +455,7 @@ def test_shift_acc_with_adder_cells_matches_oracle_netlist_toy(toy_ctx, toy_keys
         ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 71, 0)
         out_ids = np.arange(1000, 1000 + 2 * acc_bits, dtype=np.uint32).reshape(2, acc_bits)
         gates = toy_ctx.shift_acc(ids.reshape(2, 7, in_bits), sign, exp, acc_bits, out_ids)
-        nl, outs = OC.build_shift_acc(2, 7, in_bits, sign, exp, acc_bits, fold=fold, adder3=True)
+        nl, outs = OC.build_shift_acc(2, 7, in_bits, sign, exp, acc_bits, fold=fold, cells3=True)
         plain, _ = OC.build_shift_acc(2, 7, in_bits, sign, exp, acc_bits, fold=fold)
         assert gates == len(nl.gtype) < len(plain.gtype)
         assert any(t >= O.GATE3_BASE for t in nl.gtype)
@@ -463,5 +463,25 @@ def test_shift_acc_with_adder_cells_matches_oracle_netlist_toy(toy_ctx, toy_keys
         assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
         assert np.array_equal(OC.from_bits(toy_ctx.decrypt(out_ids), True), OC.plain_shift_acc(x, sign, exp, acc_bits))
     finally:
-        toy_ctx.set_option(pkg.OPT_ADDER_CELLS, 0)
+        toy_ctx.set_option(pkg.OPT_GATE3_CELLS, 0)
         toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
+
+
+@pytest.mark.parametrize("fold,native", [(False, False), (True, True)])
+def test_maxpool_with_majority_comparator_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold, native):
+    pkg = she()
+    for opt, v in ((pkg.OPT_GATE3_CELLS, 1), (pkg.OPT_FOLD_CONSTANTS, int(fold)), (pkg.OPT_NATIVE_MUX, int(native))):
+        toy_ctx.set_option(opt, v)
+    try:
+        vals = np.array([[[-3, 7], [2, -8]], [[1, 7], [-4, 6]]])                  # H=2, W=2, C=2, 4-bit
+        ids, fresh = _encrypt_values(toy_ctx, toy_keys, vals, 4, 91, 0)
+        pool_ids = np.arange(3000, 3008, dtype=np.uint32)
+        entries = toy_ctx.maxpool(ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
+        nl, outs = OC.build_maxpool(2, 2, 2, 4, fold=fold, native_mux=native, cells3=True)
+        assert entries == len(nl.gtype)
+        pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+        assert np.array_equal(toy_ctx.read_cts(pool_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+        assert OC.from_bits(toy_ctx.decrypt(pool_ids.reshape(2, 4)), True).tolist() == [2, 7]
+    finally:
+        for opt in (pkg.OPT_GATE3_CELLS, pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX):
+            toy_ctx.set_option(opt, 0)

@@ -91,23 +91,26 @@ def test_planning_calls_match_the_oracle_netlists():
             nl, _ = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold)
             want = (len(nl.gtype), int(nl.levels().max(initial=0)))
             assert she.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold) == want, (units, terms, in_bits, acc, fold)
-            nl3, _ = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold, adder3=True)
+            nl3, _ = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold, cells3=True)
             want3 = (len(nl3.gtype), int(nl3.levels().max(initial=0)))
-            assert she.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold, adder_cells=True) == want3, (units, terms, in_bits, acc, fold)
+            assert she.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold, cells3=True) == want3, (units, terms, in_bits, acc, fold)
     for fold in (False, True):
         nl, _ = OC.build_relu(7, 16, fold=fold)
         assert she.plan_relu(7, 16, fold) == (len(nl.gtype), 1)
         for native in (False, True):
             nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold, native_mux=native)
             assert she.plan_maxpool(5, 4, 3, 6, fold, native, True) == (len(nl.gtype), int(nl.levels().max()), nl.rotations)
+            nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold, native_mux=native, cells3=True)
+            assert she.plan_maxpool(5, 4, 3, 6, fold, native, True, cells3=True) == (len(nl.gtype), int(nl.levels().max()),
+                                                                                    nl.rotations)
     # the benchmark's conv layer: 26x26 pixels x 8 channels of 9-term neurons
     import synth_inputs as S
     _, sign, exp = S.cfg5_conv_layer()
     per_pixel = [she.plan_shift_acc(8, 9, 8, sign.reshape(8, 9), exp.reshape(8, 9), 16, f)[0] for f in (False, True)]
     assert per_pixel[0] * 676 == 1925248 and per_pixel[1] < 0.6 * per_pixel[0]
     # full-adder cells: the 576-term tree of the single-neuron benchmark, closed form 10,332 gates
-    assert she.plan_shift_acc(1, 576, 8, np.ones((1, 576)), np.zeros((1, 576)), 16, adder_cells=True)[0] == 10332
-    cells = she.plan_shift_acc(8, 9, 8, sign.reshape(8, 9), exp.reshape(8, 9), 16, adder_cells=True)[0]
+    assert she.plan_shift_acc(1, 576, 8, np.ones((1, 576)), np.zeros((1, 576)), 16, cells3=True)[0] == 10332
+    cells = she.plan_shift_acc(8, 9, 8, sign.reshape(8, 9), exp.reshape(8, 9), 16, cells3=True)[0]
     assert cells < 0.45 * per_pixel[0]
     with pytest.raises(she.SheError):
         she.plan_shift_acc(1, 2, 8, [[1, 2]], [[0, 0]], 16)                      # bad sign

@@ -128,7 +128,7 @@ def test_gate3_on_bootstrapped_inputs_chain_toy(toy_keys):
     w = 8
     for trial in range(3):
         x, y = (int(v) for v in rng.integers(0, 1 << w, 2))
-        nl = OC.Netlist(2 * w, adder3=True)
+        nl = OC.Netlist(2 * w, cells3=True)
         out = OC.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), 99)
         assert len(nl.gtype) == 2 * w and int(nl.levels().max()) == w
         bits = np.concatenate([OC.to_bits(np.array(x), w), OC.to_bits(np.array(y), w)])
@@ -139,16 +139,16 @@ def test_gate3_on_bootstrapped_inputs_chain_toy(toy_keys):
 
 @pytest.mark.parametrize("fold", [False, True])
 @pytest.mark.parametrize("w", [1, 2, 3, 4])
-def test_adder3_and_subtractor3_exhaustive(w, fold):
+def test_cells3_and_subtractor3_exhaustive(w, fold):
     for cap in (w, 99):
-        nl = OC.Netlist(2 * w, fold, adder3=True)
+        nl = OC.Netlist(2 * w, fold, cells3=True)
         out = OC.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), cap)
         for x in range(1 << w):
             for y in range(1 << w):
                 val = nl.run_plain(np.concatenate([OC.to_bits(np.array(x), w), OC.to_bits(np.array(y), w)]))
                 got = int(OC.from_bits(OC.Netlist.read_plain(val, out), False))
                 assert got == ((x + y) % (1 << w) if cap == w else x + y)
-    nl = OC.Netlist(2 * w, fold, adder3=True)
+    nl = OC.Netlist(2 * w, fold, cells3=True)
     out = OC.sub_wrapped(nl, list(range(w)), list(range(w, 2 * w)))
     for x in range(1 << w):
         for y in range(1 << w):
@@ -179,20 +179,20 @@ def test_gate3_folding_rules_exhaustive():
 def test_closed_form_gate_counts_with_three_input_cells():
     # w-bit + w-bit -> w+1 bits: XOR, AND, then (w-1) cells of two gates = 2w; capped: no last majority = 2w-1
     for w in (2, 5, 8, 16):
-        nl = OC.Netlist(2 * w, adder3=True)
+        nl = OC.Netlist(2 * w, cells3=True)
         OC.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), 99)
         assert len(nl.gtype) == 2 * w and int(nl.levels().max()) == w
-        nl = OC.Netlist(2 * w, adder3=True)
+        nl = OC.Netlist(2 * w, cells3=True)
         OC.add_unsigned(nl, list(range(w)), list(range(w, 2 * w)), w)
         assert len(nl.gtype) == 2 * w - 1
-        nl = OC.Netlist(2 * w, adder3=True)
+        nl = OC.Netlist(2 * w, cells3=True)
         OC.sub_wrapped(nl, list(range(w)), list(range(w, 2 * w)))
         assert len(nl.gtype) == 2 * w - 1
     # 576 same-sign 8-bit terms into 16 bits: levels of 288, 144, ..., 1, 1 adders of width 8, 9, ..., 16, 16
     counts, widths = [288, 144, 72, 36, 18, 9, 4, 2, 1, 1], [8, 9, 10, 11, 12, 13, 14, 15, 16, 16]
     want = sum(c * (2 * w if w < 16 else 2 * w - 1) for c, w in zip(counts, widths))
     assert want == 10332
-    nl, _ = OC.build_shift_acc(1, 576, 8, np.ones(576), np.zeros(576), 16, adder3=True)
+    nl, _ = OC.build_shift_acc(1, 576, 8, np.ones(576), np.zeros(576), 16, cells3=True)
     assert len(nl.gtype) == want and nl.rotations == want
     plain, _ = OC.build_shift_acc(1, 576, 8, np.ones(576), np.zeros(576), 16)
     assert len(plain.gtype) == 24104 and int(nl.levels().max()) < int(plain.levels().max())
@@ -205,7 +205,44 @@ def test_shift_acc_with_three_input_cells_equals_integer_sum():
         x = rng.integers(0, 256, (units, terms))
         sign = rng.choice([-1, 1], (units, terms))
         exp = -rng.integers(0, 8, (units, terms))
-        nl, outs = OC.build_shift_acc(units, terms, 8, sign, exp, 16, fold=fold, adder3=True)
+        nl, outs = OC.build_shift_acc(units, terms, 8, sign, exp, 16, fold=fold, cells3=True)
         val = nl.run_plain(OC.to_bits(x, 8).ravel())
         got = OC.from_bits(np.array([OC.Netlist.read_plain(val, o) for o in outs]), True)
         assert np.array_equal(got, OC.plain_shift_acc(x, sign, exp, 16))
+
+
+@pytest.mark.parametrize("fold", [False, True])
+@pytest.mark.parametrize("native", [False, True])
+def test_comparator_of_majority_gates_exhaustive_4bit(fold, native):
+    # greater-so-far = MAJ(x_i, not y_i, greater-so-far) from the least significant bit up; sign position swapped
+    nl = OC.Netlist(8, fold, native, True)
+    z = OC.max_signed(nl, list(range(4)), list(range(4, 8)))
+    for x in range(-8, 8):
+        for y in range(-8, 8):
+            val = nl.run_plain(np.concatenate([OC.to_bits(np.array(x), 4), OC.to_bits(np.array(y), 4)]))
+            assert int(OC.from_bits(OC.Netlist.read_plain(val, z), True)) == max(x, y), (x, y)
+    if not fold:
+        # w majority gates + w MUX (3 gates each, or one native entry of two rotations)
+        assert len(nl.gtype) == (8 if native else 16) and nl.rotations == (12 if native else 16)
+
+
+def test_max_with_cells_random_16bit_and_counts():
+    rng = np.random.default_rng(31)
+    nl = OC.Netlist(32, False, True, True)
+    z = OC.max_signed(nl, list(range(16)), list(range(16, 32)))
+    assert len(nl.gtype) == 32 and nl.rotations == 48            # against 48 entries / 80 rotations without the cells
+    ref = OC.Netlist(32, False, True)
+    OC.max_signed(ref, list(range(16)), list(range(16, 32)))
+    assert len(ref.gtype) == 48 and ref.rotations == 80
+    vals = list(rng.integers(-32768, 32768, (40, 2))) + [(-32768, 32767), (32767, -32768), (-1, 0), (0, -1), (5, 5)]
+    for x, y in vals:
+        val = nl.run_plain(np.concatenate([OC.to_bits(np.array(int(x)), 16), OC.to_bits(np.array(int(y)), 16)]))
+        assert int(OC.from_bits(OC.Netlist.read_plain(val, z), True)) == max(int(x), int(y))
+
+
+def test_maxpool_with_cells_on_ciphertexts_toy(toy_keys):
+    vals = np.array([[[-3], [2]], [[1], [-4]]])
+    nl, outs = OC.build_maxpool(2, 2, 1, 4, native_mux=True, cells3=True)
+    pool = nl.run_encrypted(toy_keys, tfhe.encrypt_bits(toy_keys, OC.to_bits(vals, 4).ravel(), 17), threads=8)
+    got = tfhe.decrypt_bits(toy_keys, OC.Netlist.read_encrypted(pool, np.array(outs)))
+    assert int(OC.from_bits(got, True)) == 2
