@@ -119,7 +119,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
 
 def network(ctx_factory):
     """A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
-    network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX and full-adder cells on."""
+    network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX and three-input cells on."""
     import numpy as np
 
     import synth_inputs as S
@@ -165,7 +165,7 @@ def network(ctx_factory):
     assert np.array_equal(got, want), "network decrypts wrongly"
     ctx.close()
     return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
-                        "constant folding, native MUX and full-adder cells on", "latency_s": dt, "entries": int(net.gates),
+                        "constant folding, native MUX and three-input cells on", "latency_s": dt, "entries": int(net.gates),
             "entries_per_s": net.gates / dt}
 
 
@@ -212,6 +212,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-gates", type=int, default=64)
     ap.add_argument("--no-conv-layer", action="store_true", help="skip config 5 (one conv layer, ~2.5M gates, ~15 s)")
+    ap.add_argument("--leveled-only", action="store_true",
+                    help="run only the leveled-mode CMux level and print its entry (for profiling k_cmux)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device-to-device copy (reference kernel for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -229,6 +231,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     torch.cuda.set_device(0)
+    if args.leveled_only:
+        print(json.dumps({"cmux_level": cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), reps=args.steps)}))
+        return
     G = GATES_PER_LEVEL
     bits, codes = S.cfg2_real_level(G)
     ctx = she.Context(she.REAL, S.KEY_SEED, 3 * G)
