@@ -28,6 +28,14 @@ def compute() -> dict:
            "fresh": digest(cts), "stream_word_1_3_7_0": int(tfhe.stream_word(tfhe.stream_key(1, 3, 7), 0))}
     for name in ("NAND", "XOR", "ANDNY"):
         out["gate_" + name] = digest(tfhe.gate(K, tfhe.GATES[name], cts[1], cts[3]))
+    out["gate3_MAJ3_mask2"] = digest(tfhe.gate3(K, tfhe.MAJ3 + 2, cts[1], cts[3], cts[4]))
+    out["gate3_XOR3"] = digest(tfhe.gate3(K, tfhe.XOR3, cts[1], cts[3], cts[4]))
+    mu = np.where(np.arange(2 * K.params.N).reshape(2, -1) % 3 == 0, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
+    d = tfhe.trlwe_encrypt(K, mu, 1002)
+    sel = tfhe.trgsw_encrypt_bits(K, [1], 1003)[0]
+    out["trlwe_fresh"] = digest(d)
+    out["trgsw_fresh"] = digest(sel)
+    out["cmux"] = digest(tfhe.cmux(K.params, sel, d[1], d[0]))
     return out
 
 
