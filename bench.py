@@ -283,6 +283,12 @@ def main():
         "paper_context": {"value": 77, "unit": "gates/s", "note": "implied by the paper's projected fully-homomorphic "
                           "latency / gate count (about 13 ms per gate), Xeon E7-4850, different parameter set"},
     }
+    # what the FP64 pipes of this box issue at (2 wavefronts per SIMD, sustained): the published peak assumes one FMA per
+    # lane and cycle at 2.4 GHz (1.67 ns per wave64 instruction and SIMD)
+    probe = {name: ctx.probe_fp64_rate(form) for form, name in ((0, "fma_scalar_operands"), (1, "fma_three_registers"),
+                                                               (2, "add_two_registers"))}
+    out["roofline"]["measured_fp64_issue"] = probe
+    out["roofline"]["frac_of_measured_fma_rate"] = achieved / probe["fma_scalar_operands"]["tflops_as_fma"]
     ctx.close()
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda")

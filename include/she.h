@@ -265,6 +265,12 @@ int she_get_round_error(she_ctx *ctx, double *max_abs_frac, int reset);
 int she_set_timing(she_ctx *ctx, int on);
 int she_last_timing(she_ctx *ctx, double ms[4]);
 
+/* Issue rate of one FP64 vector instruction form on this device, measured with 2 wavefronts per SIMD like the
+ * blind rotation (form 0: fma with scalar multiplier and addend, 1: fma with three vector-register operands, 2: add
+ * of two vector registers).  ns_per_instruction is per SIMD; tflops_as_fma prices every instruction as an FMA over
+ * the whole chip, the figure to hold against the published FP64 vector peak.  Either pointer may be NULL. */
+int she_probe_fp64_rate(she_ctx *ctx, int form, double *ns_per_instruction, double *tflops_as_fma);
+
 /* Text of the last error of this context ("" if none).  ctx may be NULL: then the text
  * of the last failed she_keygen of the calling thread. */
 const char *she_last_error(const she_ctx *ctx);

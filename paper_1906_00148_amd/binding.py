@@ -99,6 +99,7 @@ def load_library() -> C.CDLL:
         "she_eval_gates_device": (C.c_int, [ctx, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
         "she_set_round_tracking": (C.c_int, [ctx, C.c_int]),
         "she_get_round_error": (C.c_int, [ctx, C.POINTER(C.c_double), C.c_int]),
+        "she_probe_fp64_rate": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "she_set_timing": (C.c_int, [ctx, C.c_int]),
         "she_last_timing": (C.c_int, [ctx, C.POINTER(C.c_double)]),
         "she_last_error": (C.c_char_p, [ctx]),
@@ -355,6 +356,11 @@ class Context:
         v = C.c_double(0)
         self._check(self._L.she_get_round_error(self._h, C.byref(v), int(reset)))
         return v.value
+
+    def probe_fp64_rate(self, form: int) -> dict:
+        ns, tf = C.c_double(0), C.c_double(0)
+        self._check(self._L.she_probe_fp64_rate(self._h, form, C.byref(ns), C.byref(tf)))
+        return {"ns_per_instruction_per_simd": ns.value, "tflops_as_fma": tf.value}
 
     def set_timing(self, on: bool):
         self._check(self._L.she_set_timing(self._h, int(on)))

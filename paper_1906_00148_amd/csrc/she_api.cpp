@@ -829,6 +829,35 @@ int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
     return SHE_OK;
 }
 
+int she_probe_fp64_rate(she_ctx *c, int form, double *ns_per_instruction, double *tflops_as_fma)
+{
+    if (!c) return SHE_EINVAL;
+    if (form < 0 || form > 2 || (!ns_per_instruction && !tflops_as_fma)) return fail(c, SHE_EINVAL, "form must be 0, 1 or 2");
+    const uint32_t blocks = 2 * c->dk.cus;                    // 8 wavefronts per compute unit = 2 per SIMD
+    const int iters = 30000;                                  // 64 instructions each: ~8 ms
+    double *d_out = nullptr;
+    HIP_TRY(c, hipMalloc((void **)&d_out, (size_t)blocks * 256 * sizeof(double)));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t rc = hipEventCreate(&e0);
+    if (rc == hipSuccess) rc = hipEventCreate(&e1);
+    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, 200, c->stream);           // warm-up
+    if (rc == hipSuccess) rc = hipEventRecord(e0, c->stream);
+    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, iters, c->stream);
+    if (rc == hipSuccess) rc = hipEventRecord(e1, c->stream);
+    if (rc == hipSuccess) rc = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (rc == hipSuccess) rc = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) hipEventDestroy(e0);
+    if (e1) hipEventDestroy(e1);
+    hipFree(d_out);
+    if (rc != hipSuccess) return fail(c, SHE_EDEVICE, std::string("FP64 probe: ") + hipGetErrorString(rc));
+    const double inst_per_simd = 2.0 * 64.0 * iters;          // 2 wavefronts per SIMD
+    const double ns = (double)ms * 1e6 / inst_per_simd;
+    if (ns_per_instruction) *ns_per_instruction = ns;
+    if (tflops_as_fma) *tflops_as_fma = 128.0 * 4.0 * c->dk.cus / ns / 1e3;   // 64 lanes x 2 flop, 4 SIMDs per compute unit
+    return SHE_OK;
+}
+
 int she_set_timing(she_ctx *c, int on)
 {
     if (!c) return SHE_EINVAL;

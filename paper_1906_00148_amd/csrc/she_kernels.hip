@@ -930,4 +930,42 @@ hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const ui
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// FP64 issue-rate probe (diagnostic): independent chains of one instruction form, 2 wavefronts per SIMD
+// like the blind rotation.  form 0: fma with scalar multiplier and addend (the best case), 1: fma with
+// three vector-register operands (the form of the pointwise products), 2: add of two vector registers
+// (the butterflies).  out receives one value per thread so that the chains stay alive.
+// ------------------------------------------------------------------------------------------
+template <int FORM> __global__ __launch_bounds__(256) void k_fp64_probe(double *out, int iters, double mul, double add)
+{
+    double a[8], b = mul + threadIdx.x * 1e-12, c = add + threadIdx.x * 1e-15;
+#pragma unroll
+    for (int k = 0; k < 8; k++) a[k] = threadIdx.x * 1e-3 + k;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int rep = 0; rep < 8; rep++)
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                if (FORM == 0) a[k] = __builtin_fma(a[k], mul, add);
+                if (FORM == 1) a[k] = __builtin_fma(a[k], b, c);
+                if (FORM == 2) a[k] = a[k] + c;
+            }
+    }
+    double sum = 0;
+#pragma unroll
+    for (int k = 0; k < 8; k++) sum += a[k];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
+}
+
+hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters, hipStream_t st)
+{
+    switch (form) {
+    case 0: hipLaunchKernelGGL(k_fp64_probe<0>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
+    case 1: hipLaunchKernelGGL(k_fp64_probe<1>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
+    case 2: hipLaunchKernelGGL(k_fp64_probe<2>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace she

@@ -485,3 +485,13 @@ def test_maxpool_with_majority_comparator_matches_oracle_netlist_toy(toy_ctx, to
     finally:
         for opt in (pkg.OPT_GATE3_CELLS, pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX):
             toy_ctx.set_option(opt, 0)
+
+
+def test_fp64_issue_rate_probe_is_plausible(toy_ctx):
+    # the diagnostic behind bench.py's "measured_fp64_issue": between a quarter of and the whole published FP64 peak
+    for form in (0, 1, 2):
+        r = toy_ctx.probe_fp64_rate(form)
+        assert 20.0 < r["tflops_as_fma"] < 80.0 and 1.6 < r["ns_per_instruction_per_simd"] < 6.5, (form, r)
+    pkg = she()
+    with pytest.raises(pkg.SheError):
+        toy_ctx.probe_fp64_rate(3)
