@@ -628,7 +628,7 @@ constexpr int KSM_WAVES = 4, KSM_TILES = 2;
 
 __device__ __forceinline__ int onehot_byte(uint32_t d) { return (int)((1u << (d << 3)) & 0xFFFFFF00u); }
 
-__global__ __launch_bounds__(64 * KSM_WAVES) void k_key_switch_mfma(CtSpace cs, const int8_t *__restrict__ ksb,
+__global__ __launch_bounds__(64 * KSM_WAVES, 3) void k_key_switch_mfma(CtSpace cs, const int8_t *__restrict__ ksb,
                                                                      uint32_t cols_p, const uint16_t *__restrict__ ksd,
                                                                      const uint32_t *__restrict__ out_ids, uint32_t N,
                                                                      uint32_t n, uint32_t gates, uint32_t i_per_block)
@@ -657,13 +657,29 @@ __global__ __launch_bounds__(64 * KSM_WAVES) void k_key_switch_mfma(CtSpace cs, 
     const int8_t *bbase = ksb + ((size_t)col * 32 + 16 * half);
     const uint32_t ysh = 8 * (1 - half);
 
+    // the key bytes and digits of step i+1 are requested before the products of step i (one wavefront per SIMD:
+    // nothing else hides the loads); past the end the last step is read again, which is harmless
+    v4i b_next[4];
+    uint32_t y_next[KSM_TILES];
+#pragma unroll
+    for (int p = 0; p < 4; p++) b_next[p] = *(const v4i *)(bbase + ((size_t)i0 * 4 + p) * cols_p * 32);
+#pragma unroll
+    for (int t = 0; t < KSM_TILES; t++) y_next[t] = yp[t][(size_t)i0 * KS_GROUP];
     for (uint32_t i = i0; i < i1; i++) {
         v4i b[4];
+        uint32_t yv[KSM_TILES];
 #pragma unroll
-        for (int p = 0; p < 4; p++) b[p] = *(const v4i *)(bbase + ((size_t)i * 4 + p) * cols_p * 32);
+        for (int p = 0; p < 4; p++) b[p] = b_next[p];
+#pragma unroll
+        for (int t = 0; t < KSM_TILES; t++) yv[t] = y_next[t];
+        const uint32_t in = min(i + 1, i1 - 1);
+#pragma unroll
+        for (int p = 0; p < 4; p++) b_next[p] = *(const v4i *)(bbase + ((size_t)in * 4 + p) * cols_p * 32);
+#pragma unroll
+        for (int t = 0; t < KSM_TILES; t++) y_next[t] = yp[t][(size_t)in * KS_GROUP];
 #pragma unroll
         for (int t = 0; t < KSM_TILES; t++) {
-            const uint32_t y = ((uint32_t)yp[t][(size_t)i * KS_GROUP] >> ysh) & 0xffu;   // this half's four digits
+            const uint32_t y = (yv[t] >> ysh) & 0xffu;                                    // this half's four digits
             v4i a;
             a.x = onehot_byte((y >> 6) & 3);
             a.y = onehot_byte((y >> 4) & 3);
