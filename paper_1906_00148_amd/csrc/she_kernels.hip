@@ -624,7 +624,7 @@ __global__ __launch_bounds__(KS_COLS) void k_key_switch(CtSpace cs, const uint32
 // ------------------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
-constexpr int KSM_WAVES = 4, KSM_TILES = 2;
+constexpr int KSM_WAVES = 4, KSM_TILES = 2;   // measured: 1 tile (4 or 6 waves per SIMD), 3 and 4 tiles are slower
 
 __device__ __forceinline__ int onehot_byte(uint32_t d) { return (int)((1u << (d << 3)) & 0xFFFFFF00u); }
 
@@ -908,7 +908,8 @@ hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtS
 {
     if (!gates) return hipSuccess;
     if (K.ks_bytes) {
-        const unsigned gate_blocks = (unsigned)((gates + 64 * KSM_WAVES - 1) / (64 * KSM_WAVES));
+        const unsigned per_block = 32 * KSM_TILES * KSM_WAVES;                 // gates per workgroup
+        const unsigned gate_blocks = (unsigned)((gates + per_block - 1) / per_block);
         const unsigned col_tiles = K.ks_cols / 32;
         // split the i range until about a thousand blocks are in flight
         unsigned split = 1;
