@@ -301,6 +301,23 @@ def test_ring_degree_512(toy_keys):
         pool[:48] = O.encrypt_bits(K, bits, 11)
         O.eval_gates(K, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
         assert np.array_equal(ctx.read_cts(out_ids), pool[48:])
+        # three-input gates and a leveled-mode CMux at this ring degree (four points per lane, four passes)
+        g3 = np.array([pkg.MAJ3, pkg.XOR3 + 1, pkg.MAJ3 + 6, pkg.XOR3, pkg.MAJ3 + 1], np.uint8)
+        o3 = np.arange(100, 105, dtype=np.uint32)
+        ctx.eval_gates3(g3, in_ids[0:15:3], in_ids[1:15:3], in_ids[2:15:3], o3)
+        pool3 = np.zeros((105, 97), np.uint32)
+        pool3[:48] = pool[:48]
+        O.eval_netlist(K, pool3, g3.astype(np.uint32), in_ids[0:15:3], in_ids[1:15:3], in_ids[2:15:3], o3, threads=5)
+        assert np.array_equal(ctx.read_cts(o3), pool3[100:])
+        ctx.leveled_init(4, 16)
+        rng = np.random.default_rng(5)
+        mu = np.where(rng.integers(0, 2, (3, 512)) == 1, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
+        ctx.trlwe_encrypt(mu, 12, [0, 1, 2])
+        ctx.trgsw_encrypt_bits([1, 0], 13, [0, 1])
+        ctx.eval_cmux([0, 1, 0], [0, 1, 2], [1, 2, 2], [5, 6, 7])
+        data, sels = O.trlwe_encrypt(K, mu, 12), O.trgsw_encrypt_bits(K, [1, 0], 13)
+        want = [O.cmux(K.params, sels[s_], data[a], data[b]) for s_, a, b in ((0, 0, 1), (1, 1, 2), (0, 2, 2))]
+        assert np.array_equal(ctx.trlwe_read([5, 6, 7]), np.stack(want))
 
 
 # ------------------------------------------------------------------ constant folding, ciphertext level
