@@ -58,7 +58,7 @@ def cpu_baseline(sample_gates: int):
                       f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
 
 
-def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False):
+def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False, fused_pool: bool = False):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
     accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
     skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); cells3: full-adder cells of
@@ -92,9 +92,13 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     t0 = time.perf_counter()
     g1 = ctx.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, 16, conv_ids.reshape(-1, 16))
     t1 = time.perf_counter()
-    g2 = ctx.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
-    t2 = time.perf_counter()
-    g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
+    if fused_pool:                       # ReLU and pooling as one operator (she_relu_maxpool)
+        g2, t2 = 0, t1
+        g3 = ctx.relu_maxpool(conv_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
+    else:
+        g2 = ctx.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+        t2 = time.perf_counter()
+        g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
     t3 = time.perf_counter()
     # all 13x13x8 outputs against plain integer arithmetic
     dec = ctx.decrypt(pool_ids.reshape(-1, 16)).astype(np.int64)
@@ -111,7 +115,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     ctx.close()
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
-            "constant_folding": bool(fold), "native_mux": bool(native_mux), "cells3": bool(cells3),
+            "constant_folding": bool(fold), "native_mux": bool(native_mux), "cells3": bool(cells3), "relu_and_pool_fused": bool(fused_pool),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -155,8 +159,8 @@ def network(ctx_factory):
     ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
     net = Chain(ctx, x_ids.size)
     t0 = time.perf_counter()
-    a = net.maxpool(net.relu(net.conv(x_ids, w1[0], w1[1], 16)))
-    b = net.maxpool(net.relu(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16)))
+    a = net.relu_maxpool(net.conv(x_ids, w1[0], w1[1], 16))
+    b = net.relu_maxpool(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))
     scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
     dt = time.perf_counter() - t0
     dec = ctx.decrypt(scores).astype(np.int64)
@@ -300,7 +304,7 @@ def main():
     if not args.no_conv_layer:
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
         out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True,
-                                            cells3=True)
+                                            cells3=True, fused_pool=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:

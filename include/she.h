@@ -144,6 +144,14 @@ int she_relu(she_ctx *ctx, const uint32_t *x_ids, uint32_t count, uint32_t bits,
 int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                 const uint32_t *out_ids, uint64_t *gates_out);
 
+/* Section 3.1 (activation followed by pooling, the A-P pair of the layer sequences in Section 5): ReLU then 2x2
+ * stride-2 max pooling in one call, same shapes as she_maxpool.  max(x, 0) is monotone, so the result equals the
+ * ReLU of the window's maximum: the window is pooled on the signed values and one sign mask is applied to the pooled
+ * value, a quarter of the masking gates of she_relu on every input.  Decrypts to the same values as she_relu followed
+ * by she_maxpool. */
+int she_relu_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
+                     const uint32_t *out_ids, uint64_t *gates_out);
+
 /* Options.  SHE_OPT_FOLD_CONSTANTS (default 0): the layer operators stop spending a bootstrap on
  * gates whose result is fixed by a trivial-constant or repeated operand (the zeros that a shift
  * leaves on top of a term, the carry-in of the subtraction, the comparator's first stage): such a
@@ -183,6 +191,8 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
 int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
 int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
                      uint64_t *rotations);
+int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
+                          uint64_t *rotations);
 
 /* ---- leveled mode (Section 4, "TFHE setting": the three sample levels TLWE / TRLWE / TRGSW used
  * without bootstrapping) ----

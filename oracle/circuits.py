@@ -452,6 +452,16 @@ def max_signed(nl: Netlist, x: list, y: list) -> list:
     return [nl.mux(gt, x[i], y[i]) for i in range(w)]
 
 
+def build_relu_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False,
+                       cells3: bool = False):
+    """ReLU then 2x2 max pooling (Section 3.1) in one netlist.  max(., 0) is monotone, so pooling the ReLUs of a window
+    equals the ReLU of its maximum: the window is pooled on the signed values and ONE sign mask is applied to the
+    result, a quarter of the masking gates of ReLU on every input."""
+    nl, pooled = build_maxpool(H, W, Cn, bits, fold, native_mux, cells3)
+    outs = [[nl.gate("ANDNY", z[-1], z[i]) for i in range(bits - 1)] + [nl.ZERO] for z in pooled]
+    return nl, outs
+
+
 def build_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False, cells3: bool = False):
     nl = Netlist(H * W * Cn * bits, fold, native_mux, cells3)
 

@@ -74,6 +74,9 @@ def load_library() -> C.CDLL:
         "she_shift_acc": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, u32p, u64p]),
         "she_relu": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
+        "she_relu_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
+        "she_plan_relu_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
+                                            C.POINTER(C.c_uint32), u64p]),
         "she_set_option": (C.c_int, [ctx, C.c_int, C.c_int]),
         "she_get_option": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_int)]),
         "she_plan_shift_acc": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, C.c_int, u64p,
@@ -167,6 +170,15 @@ def plan_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_
                                          C.byref(rot))
     out = _plan(rc, g, lv)
     return out + (rot.value,) if with_rotations else out
+
+
+def plan_relu_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, native_mux: bool = False,
+                      cells3: bool = False):
+    """(entries, levels, blind rotations) of she_relu_maxpool."""
+    g, lv, rot = C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
+    rc = load_library().she_plan_relu_maxpool(H, W, Cn, bits, _options(fold, native_mux, cells3), C.byref(g), C.byref(lv),
+                                              C.byref(rot))
+    return _plan(rc, g, lv) + (rot.value,)
 
 
 class Context:
@@ -282,6 +294,15 @@ class Context:
         gates = C.c_uint64(0)
         self._check(self._L.she_maxpool(self._h, _p(x_ids, C.c_uint32), H, W, Cn, bits, _p(out_ids, C.c_uint32),
                                         C.byref(gates)))
+        return gates.value
+
+    def relu_maxpool(self, x_ids, out_ids) -> int:
+        x_ids, out_ids = _u32(x_ids), _u32(out_ids)
+        H, W, Cn, bits = x_ids.shape
+        assert out_ids.shape == (H // 2, W // 2, Cn, bits)
+        gates = C.c_uint64(0)
+        self._check(self._L.she_relu_maxpool(self._h, _p(x_ids, C.c_uint32), H, W, Cn, bits, _p(out_ids, C.c_uint32),
+                                             C.byref(gates)))
         return gates.value
 
     # ---- leveled mode

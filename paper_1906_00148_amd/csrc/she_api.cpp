@@ -591,6 +591,19 @@ static std::vector<uint32_t> wires_maxpool(Netlist &nl, const uint32_t *x_ids, u
     return wires;
 }
 
+// ReLU of every pooled value: max(., 0) is monotone, so this equals pooling the ReLUs of the window
+static std::vector<uint32_t> wires_relu_maxpool(Netlist &nl, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C,
+                                                uint32_t bits)
+{
+    std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
+    for (size_t v = 0; v + bits <= wires.size(); v += bits) {
+        const uint32_t sign = wires[v + bits - 1];
+        for (uint32_t i = 0; i + 1 < bits; i++) wires[v + i] = nl.gate(SHE_ANDNY, sign, wires[v + i]);
+        wires[v + bits - 1] = nl.zero();
+    }
+    return wires;
+}
+
 static bool weights_ok(const int8_t *w_sign, const int8_t *w_exp, size_t count, uint32_t in_bits, const char **why)
 {
     for (size_t k = 0; k < count; k++) {
@@ -670,6 +683,29 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     }
 }
 
+int she_relu_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
+                     const uint32_t *out_ids, uint64_t *gates_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (gates_out) *gates_out = 0;
+    const uint32_t Ho = H / 2, Wo = W / 2;
+    if (Ho == 0 || Wo == 0 || C == 0) return SHE_OK;
+    if (!x_ids || !out_ids) return fail(c, SHE_EINVAL, "null argument");
+    if (bits < 2 || bits > 64) return fail(c, SHE_EINVAL, "need 2 <= bits <= 64");
+    const size_t n_in = (size_t)H * W * C * bits, n_out = (size_t)Ho * Wo * C * bits;
+    int rc;
+    if ((rc = check_ids(c, x_ids, n_in, "she_relu_maxpool x_ids"))) return rc;
+    if ((rc = check_ids(c, out_ids, n_out, "she_relu_maxpool out_ids"))) return rc;
+    if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
+    try {
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        const std::vector<uint32_t> wires = wires_relu_maxpool(nl, x_ids, H, W, C, bits);
+        return run_netlist(c, nl, wires, out_ids, gates_out);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
 int she_set_option(she_ctx *c, int option, int value)
 {
     if (!c) return SHE_EINVAL;
@@ -734,6 +770,23 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
         Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
                    (options & SHE_OPT_GATE3_CELLS) != 0);
         wires_relu(nl, ids.data(), count, bits);
+        return plan_finish(nl, gates, levels, rotations);
+    } catch (const std::bad_alloc &) {
+        return SHE_ENOMEM;
+    }
+}
+
+int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
+                          uint64_t *rotations)
+{
+    const size_t n_in = (size_t)H * W * C * bits;
+    if (bits < 2 || bits > 64 || n_in > 0x40000000u) return SHE_EINVAL;
+    try {
+        std::vector<uint32_t> ids(n_in);
+        for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
+        Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
+                   (options & SHE_OPT_GATE3_CELLS) != 0);
+        wires_relu_maxpool(nl, ids.data(), H, W, C, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;

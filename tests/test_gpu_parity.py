@@ -512,3 +512,23 @@ def test_fp64_issue_rate_probe_is_plausible(toy_ctx):
     pkg = she()
     with pytest.raises(pkg.SheError):
         toy_ctx.probe_fp64_rate(3)
+
+
+def test_relu_maxpool_fused_matches_oracle_netlist_and_the_two_operators_toy(toy_ctx, toy_keys):
+    pkg = she()
+    vals = np.array([[[-3, 7], [2, -8]], [[1, -7], [-4, -6]]])                  # H=2, W=2, C=2, 4-bit: maxima 2 and 7... -6 -> 0
+    vals[0, 0, 1] = -5
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, vals, 4, 93, 0)
+    out_ids = np.arange(3000, 3008, dtype=np.uint32)
+    entries = toy_ctx.relu_maxpool(ids.reshape(2, 2, 2, 4), out_ids.reshape(1, 1, 2, 4))
+    nl, outs = OC.build_relu_maxpool(2, 2, 2, 4)
+    assert entries == len(nl.gtype)
+    pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+    assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+    want = OC.plain_maxpool2x2(OC.plain_relu(vals)).reshape(-1)
+    assert OC.from_bits(toy_ctx.decrypt(out_ids.reshape(2, 4)), True).tolist() == want.tolist() == [2, 0]
+    # the two separate operators decrypt to the same values
+    relu_ids, pool_ids = np.arange(3100, 3116, dtype=np.uint32), np.arange(3200, 3208, dtype=np.uint32)
+    toy_ctx.relu(ids.reshape(-1, 4), relu_ids.reshape(-1, 4))
+    toy_ctx.maxpool(relu_ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
+    assert OC.from_bits(toy_ctx.decrypt(pool_ids.reshape(2, 4)), True).tolist() == want.tolist()

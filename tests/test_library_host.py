@@ -103,6 +103,9 @@ def test_planning_calls_match_the_oracle_netlists():
             nl, _ = OC.build_maxpool(5, 4, 3, 6, fold=fold, native_mux=native, cells3=True)
             assert she.plan_maxpool(5, 4, 3, 6, fold, native, True, cells3=True) == (len(nl.gtype), int(nl.levels().max()),
                                                                                     nl.rotations)
+    for fold, native, cells in ((False, False, False), (True, True, True)):
+        nl, _ = OC.build_relu_maxpool(5, 4, 3, 6, fold, native, cells)
+        assert she.plan_relu_maxpool(5, 4, 3, 6, fold, native, cells) == (len(nl.gtype), int(nl.levels().max()), nl.rotations)
     # the benchmark's conv layer: 26x26 pixels x 8 channels of 9-term neurons
     import synth_inputs as S
     _, sign, exp = S.cfg5_conv_layer()

@@ -274,3 +274,25 @@ def test_plain_conv_against_scipy_correlation_and_network_shapes():
     img, w1, w2, w3 = S.cfg6_network()
     scores = C.plain_network(img, w1, w2, w3)
     assert scores.shape == (10,) and w3[0].shape == (10, 2 * 2 * 4)
+
+
+def test_relu_then_pool_as_one_netlist_equals_the_two_operators():
+    # max(., 0) is monotone: pool(relu(x)) == relu(pool(x)); the fused netlist masks only the pooled values
+    rng = np.random.default_rng(17)
+    for fold in (False, True):
+        for native in (False, True):
+            for cells in (False, True):
+                nl, outs = C.build_relu_maxpool(4, 6, 2, 5, fold, native, cells)
+                for _ in range(6):
+                    x = rng.integers(-16, 16, (4, 6, 2))
+                    val = nl.run_plain(C.to_bits(x, 5).ravel())
+                    got = C.from_bits(np.array([C.Netlist.read_plain(val, o) for o in outs]), True).reshape(2, 3, 2)
+                    assert np.array_equal(got, C.plain_maxpool2x2(C.plain_relu(x)))
+    # all-negative and all-zero windows, extreme values
+    nl, outs = C.build_relu_maxpool(2, 2, 1, 4)
+    for window in ([-8, -1, -3, -2], [0, 0, 0, 0], [7, -8, 7, -8], [-1, 0, -1, 0]):
+        val = nl.run_plain(C.to_bits(np.array(window).reshape(2, 2, 1), 4).ravel())
+        assert int(C.from_bits(C.Netlist.read_plain(val, outs[0]), True)) == max(max(window), 0)
+    # a quarter of the masking gates: 3 maxes of 7w gates + (w - 1) masks per window against 4 (w - 1) + 3 * 7w
+    fused, _ = C.build_relu_maxpool(2, 2, 1, 16)
+    assert len(fused.gtype) == 3 * 112 + 15
