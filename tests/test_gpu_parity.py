@@ -528,7 +528,7 @@ def test_relu_maxpool_fused_matches_oracle_netlist_and_the_two_operators_toy(toy
     want = OC.plain_maxpool2x2(OC.plain_relu(vals)).reshape(-1)
     assert OC.from_bits(toy_ctx.decrypt(out_ids.reshape(2, 4)), True).tolist() == want.tolist() == [2, 0]
     # the two separate operators decrypt to the same values
-    relu_ids, pool_ids = np.arange(3100, 3116, dtype=np.uint32), np.arange(3200, 3208, dtype=np.uint32)
+    relu_ids, pool_ids = np.arange(3100, 3132, dtype=np.uint32), np.arange(3200, 3208, dtype=np.uint32)
     toy_ctx.relu(ids.reshape(-1, 4), relu_ids.reshape(-1, 4))
     toy_ctx.maxpool(relu_ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
     assert OC.from_bits(toy_ctx.decrypt(pool_ids.reshape(2, 4)), True).tolist() == want.tolist()
