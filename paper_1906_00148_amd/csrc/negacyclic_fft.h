@@ -268,6 +268,58 @@ __device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const 
     }
 }
 
+// Forward transforms of NB polynomials through ONE exchange buffer, software-pipelined: within a pass, set b's
+// butterflies are followed at once by its exchange (twiddle products, stores, loads), then set b+1's butterflies
+// and exchange, and so on.  A wavefront's LDS operations execute in issue order, so a set's stores cannot overtake
+// the previous set's loads, and the values a set loaded are first needed one round later, in the next pass, after
+// the other sets' arithmetic: no round trip is waited for with nothing to do.  It pays where a wavefront has a
+// SIMD to itself (nothing else covers its round trips) and costs NB register sets.
+template <class PL, int NB>
+__device__ __forceinline__ void forward_pipelined(const LaneCtx<PL> &lc, double (&xr)[NB][PL::P], double (&xi)[NB][PL::P])
+{
+    constexpr int P = PL::P, K = PL::K;
+#pragma unroll
+    for (int b = 0; b < NB; b++)
+#pragma unroll
+        for (int m = 1; m < P; m++) {                               // register-dependent part of the twist
+            const double cr = cos_pi64(32 * m / P), ci = sin_pi64(32 * m / P);
+            const double r = xr[b][m], i = xi[b][m];
+            xr[b][m] = r * cr - i * ci;
+            xi[b][m] = r * ci + i * cr;
+        }
+#pragma unroll
+    for (int s = 0; s < K; s++) {
+        double2 w[P];
+        if (s < K - 1) {
+#pragma unroll
+            for (int k = (s == 0 ? 0 : 1); k < P; k++) w[k] = lc.twiddle(s, k);
+        }
+        const int Tn = s < K - 1 ? ipow(P, K - 2 - s) : 1;
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            dft_regs<P, +1>(xr[b], xi[b]);
+            if (s < K - 1) {
+                wave_lds_fence();
+#pragma unroll
+                for (int k = 0; k < P; k++) {
+                    if (k >= (s == 0 ? 0 : 1)) {
+                        const double r = xr[b][k], i = xi[b][k];
+                        xr[b][k] = r * w[k].x - i * w[k].y;
+                        xi[b][k] = r * w[k].y + i * w[k].x;
+                    }
+                    lc.xch[k * PL::XROW + lc.t] = make_double2(xr[b][k], xi[b][k]);
+                }
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < P; m++) {
+                    const double2 v = lc.xch[lc.rd_base[s] + m * Tn];
+                    xr[b][m] = v.x; xi[b][m] = v.y;
+                }
+            }
+        }
+    }
+}
+
 // Inverse transforms, the mirror of forward_n(); the 1/M normalisation is folded into the last
 // constant multiplication.  Out: xr/xi[b][m] = u_{t + L*m}.
 // SHARED: every set goes through the same exchange buffer, one after the other (store, load, next set's store,

@@ -257,7 +257,13 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <class PL, bool TRACK, int GB>
+constexpr int largest_divisor_up_to(int v, int cap) { int d = cap < v ? cap : v; while (d > 1 && v % d) d--; return d < 1 ? 1 : d; }
+#ifndef SHE_SPLIT_KD
+#define SHE_SPLIT_KD 16
+#endif
+// LR > 0: the gadget has LR levels (l == LR) and a wavefront transforms its LR digit polynomials side by side
+// (forward_pipelined), streaming the key rows through SHE_SPLIT_KD values in flight; LR == 0: any l, one at a time.
+template <class PL, bool TRACK, int GB, int LR>
 __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
     const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
     const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
@@ -301,10 +307,19 @@ __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
     const size_t row_elems = (size_t)2 * P * L;
     const int mine_off = c * P * L + t, other_off = (c ^ 1) * P * L + t;
     double2 bm[P], bo[P];
-    {
+    if constexpr (LR == 0) {
         const double2 *row = bk_hat + (size_t)(c * l) * row_elems;
 #pragma unroll
         for (int k = 0; k < P; k++) { bm[k] = row[mine_off + k * L]; bo[k] = row[other_off + k * L]; }
+    }
+    // LR > 0: key value j = (p*2 + o)*P + k of this component's LR rows sits at rows[j*L]
+    // (KD divides NV, so that a value keeps its place in the ring from one step to the next)
+    constexpr int NV = LR * 2 * P, KD = LR > 0 ? largest_divisor_up_to(NV, SHE_SPLIT_KD) : 1;
+    double2 kv[KD];
+    if constexpr (LR > 0) {
+        const double2 *rows = bk_hat + (size_t)(c * LR) * row_elems + t;
+#pragma unroll
+        for (int j = 0; j < KD; j++) kv[j] = rows[j * L];
     }
     uint32_t abar_next = mybar[0];
     for (uint32_t i = 0; i < n; i++) {
@@ -312,8 +327,10 @@ __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
         abar_next = mybar[i + 1];                                          // i+1 == n reads bbar: harmless
 
         double mr[P], mi[P], orr[P], oi[P];                                // partial spectra: own component, the other one
+        if constexpr (LR == 0) {
 #pragma unroll
-        for (int k = 0; k < P; k++) { mr[k] = mi[k] = orr[k] = oi[k] = 0.0; }
+            for (int k = 0; k < P; k++) { mr[k] = mi[k] = orr[k] = oi[k] = 0.0; }
+        }
 
         // D_c = X^abar * ACC_c - ACC_c at this lane's 2P coefficients
         uint32_t dlo[P], dhi[P];
@@ -327,7 +344,39 @@ __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
             dlo[m] = (v0 - acc[j0] + dec_off) ^ flip;
             dhi[m] = (v1 - acc[j1] + dec_off) ^ flip;
         }
-        for (uint32_t p = 0; p < l; p++) {
+        if constexpr (LR > 0) {
+            double xr[LR][P], xi[LR][P];
+#pragma unroll
+            for (int p = 0; p < LR; p++)
+#pragma unroll
+                for (int m = 0; m < P; m++) {
+                    xr[p][m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], 32 - (p + 1) * bg_bit, bg_bit);
+                    xi[p][m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], 32 - (p + 1) * bg_bit, bg_bit);
+                }
+            forward_pipelined<PL, LR>(lc, xr, xi);
+            __builtin_amdgcn_sched_barrier(0);
+            // this step's remaining key values, then the first KD of the next step (the last step's again at the end)
+            const double2 *rows = bk_hat + ((size_t)i * 2 * LR + c * LR) * row_elems + t;
+            const double2 *rows_next = bk_hat + ((size_t)std::min(i + 1, n - 1) * 2 * LR + c * LR) * row_elems + t;
+#pragma unroll
+            for (int j = 0; j < NV; j++) {
+                const int p = j / (2 * P), o = (j / P) % 2, k = j % P;
+                const double2 b = kv[j % KD];
+                // output component o of the key row; o == c is this wavefront's own
+                double &ar = (o == c) ? mr[k] : orr[k];
+                double &ai = (o == c) ? mi[k] : oi[k];
+                if (p == 0) {
+                    ar = __builtin_fma(-xi[p][k], b.y, xr[p][k] * b.x);
+                    ai = __builtin_fma(xi[p][k], b.x, xr[p][k] * b.y);
+                } else {
+                    ar = __builtin_fma(-xi[p][k], b.y, __builtin_fma(xr[p][k], b.x, ar));
+                    ai = __builtin_fma(xi[p][k], b.x, __builtin_fma(xr[p][k], b.y, ai));
+                }
+                kv[j % KD] = (j + KD < NV) ? rows[(j + KD) * L] : rows_next[(j + KD - NV) * L];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        for (uint32_t p = 0; LR == 0 && p < l; p++) {
             const uint32_t sh = 32 - (p + 1) * bg_bit;
             double xr[P], xi[P];
 #pragma unroll
@@ -864,12 +913,22 @@ static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_
         const size_t per_cu = (gates + K.cus - 1) / std::max<uint32_t>(K.cus, 1);
         const bool two = per_cu == 2 || per_cu == 6;
         const dim3 grid((unsigned)(two ? (gates + 1) / 2 : gates)), block(two ? 256 : 128);
-#define SHE_LAUNCH_SPLIT(TRACK, GB)                                                                                   \
-    hipLaunchKernelGGL((k_blind_rotate_split<PL, TRACK, GB>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l,      \
+#define SHE_LAUNCH_SPLIT(TRACK, GB, LR)                                                                               \
+    hipLaunchKernelGGL((k_blind_rotate_split<PL, TRACK, GB, LR>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l,  \
                        P.bg_bit, K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs,     \
                        d_out, raw_ext)
-        if (d_round_err) { if (two) SHE_LAUNCH_SPLIT(true, 2); else SHE_LAUNCH_SPLIT(true, 1); }
-        else { if (two) SHE_LAUNCH_SPLIT(false, 2); else SHE_LAUNCH_SPLIT(false, 1); }
+#ifdef SHE_NO_TRIPLE
+        const bool triple = false;
+#else
+        const bool triple = P.l == 3;
+#endif
+        if (triple) {
+            if (d_round_err) { if (two) SHE_LAUNCH_SPLIT(true, 2, 3); else SHE_LAUNCH_SPLIT(true, 1, 3); }
+            else { if (two) SHE_LAUNCH_SPLIT(false, 2, 3); else SHE_LAUNCH_SPLIT(false, 1, 3); }
+        } else {
+            if (d_round_err) { if (two) SHE_LAUNCH_SPLIT(true, 2, 0); else SHE_LAUNCH_SPLIT(true, 1, 0); }
+            else { if (two) SHE_LAUNCH_SPLIT(false, 2, 0); else SHE_LAUNCH_SPLIT(false, 1, 0); }
+        }
 #undef SHE_LAUNCH_SPLIT
         return hipGetLastError();
     }
