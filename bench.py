@@ -28,6 +28,10 @@ GATES_PER_LEVEL = 4096
 FLOP_PER_CMUX = 8 * (5 * 512 * 9 + 6 * 512) + 12 * 512 * 8
 FLOP_PER_GATE = 630 * FLOP_PER_CMUX
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop/FMA x 2.4 GHz
+# FP64 vector instructions one wavefront executes per CMux in k_blind_rotate at N=1024, l=3, counted in the kernel's
+# ISA: 6 forward rows x 323 + 518 (inverse transforms, rounding); beside them 443 LDS, 97 global-load and about 535
+# integer vector instructions
+FP64_INSTR_PER_CMUX = 2456
 # HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 960,333 KiB scaled by 2.00,
 # WRITE_SIZE 95,433 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
 # profiles/k_blind_rotate_level4096_n630_N1024_counters.txt.  Algorithmic bytes are ~75 MB: the excess is the
@@ -290,9 +294,17 @@ def main():
     # what the FP64 pipes of this box issue at (2 wavefronts per SIMD, sustained): the published peak assumes one FMA per
     # lane and cycle at 2.4 GHz (1.67 ns per wave64 instruction and SIMD)
     probe = {name: ctx.probe_fp64_rate(form) for form, name in ((0, "fma_scalar_operands"), (1, "fma_three_registers"),
-                                                               (2, "add_two_registers"))}
+                                                               (2, "add_two_registers"),
+                                                               (3, "add_with_the_kernels_lds_and_key_loads"))}
     out["roofline"]["measured_fp64_issue"] = probe
     out["roofline"]["frac_of_measured_fma_rate"] = achieved / probe["fma_scalar_operands"]["tflops_as_fma"]
+    # the blind rotation's own FP64 instruction rate (2456 per CMux and wavefront, counted in its ISA) against the rate
+    # at which plain additions issue with the kernel's LDS and key-load instructions beside them
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    br_ns = br_ms * 1e6 / (G * 630 * FP64_INSTR_PER_CMUX / (4.0 * cus))
+    out["roofline"]["blind_rotate_ns_per_fp64_instruction_per_simd"] = br_ns
+    out["roofline"]["frac_of_measured_mixed_issue_rate"] = probe["add_with_the_kernels_lds_and_key_loads"][
+        "ns_per_instruction_per_simd"] / br_ns
     ctx.close()
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda")

@@ -885,7 +885,9 @@ int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
 int she_probe_fp64_rate(she_ctx *c, int form, double *ns_per_instruction, double *tflops_as_fma)
 {
     if (!c) return SHE_EINVAL;
-    if (form < 0 || form > 2 || (!ns_per_instruction && !tflops_as_fma)) return fail(c, SHE_EINVAL, "form must be 0, 1 or 2");
+    if (form < 0 || form > 3 || (!ns_per_instruction && !tflops_as_fma)) return fail(c, SHE_EINVAL, "form must be 0, 1, 2 or 3");
+    // form 3 streams the spectral bootstrapping key in rows of 64 x 16 bytes
+    const uint32_t src_rows = (uint32_t)std::min<size_t>(bk_hat_elems(c->P) / 64, 1u << 30);
     const uint32_t blocks = 2 * c->dk.cus;                    // 8 wavefronts per compute unit = 2 per SIMD
     const int iters = 30000;                                  // 64 instructions each: ~8 ms
     double *d_out = nullptr;
@@ -893,9 +895,9 @@ int she_probe_fp64_rate(she_ctx *c, int form, double *ns_per_instruction, double
     hipEvent_t e0 = nullptr, e1 = nullptr;
     hipError_t rc = hipEventCreate(&e0);
     if (rc == hipSuccess) rc = hipEventCreate(&e1);
-    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, 200, c->stream);           // warm-up
+    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, 200, c->dk.bk_hat, src_rows, c->stream);           // warm-up
     if (rc == hipSuccess) rc = hipEventRecord(e0, c->stream);
-    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, iters, c->stream);
+    if (rc == hipSuccess) rc = launch_fp64_probe(form, d_out, blocks, iters, c->dk.bk_hat, src_rows, c->stream);
     if (rc == hipSuccess) rc = hipEventRecord(e1, c->stream);
     if (rc == hipSuccess) rc = hipEventSynchronize(e1);
     float ms = 0.f;

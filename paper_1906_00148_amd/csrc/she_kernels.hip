@@ -1014,22 +1014,65 @@ hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const ui
 // FP64 issue-rate probe (diagnostic): independent chains of one instruction form, 2 wavefronts per SIMD
 // like the blind rotation.  form 0: fma with scalar multiplier and addend (the best case), 1: fma with
 // three vector-register operands (the form of the pointwise products), 2: add of two vector registers
-// (the butterflies).  out receives one value per thread so that the chains stay alive.
+// (the butterflies).  form 3: the add stream of form 2 with the blind rotation's memory instructions
+// beside it, per 64 additions 6 LDS reads and 3 LDS writes of 16 bytes per lane in the exchange buffer's
+// layout and 2 global loads of 16 bytes per lane that stream `src` the way the key rows are streamed
+// (the kernel has 6.5, 3.3 and 2.5 per 64 FP64 instructions); every loaded value is consumed by one of
+// the 64 additions.  out receives one value per thread so that the chains stay alive.
 // ------------------------------------------------------------------------------------------
-template <int FORM> __global__ __launch_bounds__(256) void k_fp64_probe(double *out, int iters, double mul, double add)
+template <int FORM> __global__ __launch_bounds__(256) void k_fp64_probe(double *out, int iters, double mul, double add,
+                                                                        const double2 *__restrict__ src, uint32_t src_rows)
 {
     double a[8], b = mul + threadIdx.x * 1e-12, c = add + threadIdx.x * 1e-15;
 #pragma unroll
     for (int k = 0; k < 8; k++) a[k] = threadIdx.x * 1e-3 + k;
-    for (int it = 0; it < iters; it++) {
+    if (FORM == 3) {
+        __shared__ double2 s_buf[4][8 * 65];
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        double2 *buf = s_buf[wave];
+        for (int e = lane; e < 8 * 65; e += 64) buf[e] = make_double2(0.0, 0.0);
+        wave_lds_fence();
+        const int rd = (lane & 7) * 65 + (lane >> 3);                      // the transposing read of an exchange
+        uint32_t row = (blockIdx.x * 4 + wave) % src_rows;                  // rows of 64 x 16 bytes
+        // global loads run four iterations (256 additions) ahead, about as far as the kernel requests its key rows
+        double2 g[4][2];
 #pragma unroll
-        for (int rep = 0; rep < 8; rep++)
+        for (int j = 0; j < 4; j++) { g[j][0] = src[(size_t)row * 64 + lane]; g[j][1] = g[j][0]; }
+        for (int it = 0; it < iters; it += 4) {
 #pragma unroll
-            for (int k = 0; k < 8; k++) {
-                if (FORM == 0) a[k] = __builtin_fma(a[k], mul, add);
-                if (FORM == 1) a[k] = __builtin_fma(a[k], b, c);
-                if (FORM == 2) a[k] = a[k] + c;
+            for (int j = 0; j < 4; j++) {
+                // 3 stores, 6 loads, 64 additions; loaded values replace c in 16 of the additions
+                buf[0 * 65 + lane] = make_double2(a[0], a[1]);
+                buf[3 * 65 + lane] = make_double2(a[2], a[3]);
+                buf[6 * 65 + lane] = make_double2(a[4], a[5]);
+                wave_lds_fence();
+                double2 v[6];
+#pragma unroll
+                for (int q = 0; q < 6; q++) v[q] = buf[rd + q * 8];
+#pragma unroll
+                for (int rep = 0; rep < 6; rep++)
+#pragma unroll
+                    for (int k = 0; k < 8; k++) a[k] = a[k] + c;
+                wave_lds_fence();
+#pragma unroll
+                for (int q = 0; q < 6; q++) { a[q] = a[q] + v[q].x; a[q + 2] = a[q + 2] + v[q].y; }
+                a[0] = a[0] + g[j][0].x; a[1] = a[1] + g[j][0].y; a[2] = a[2] + g[j][1].x; a[3] = a[3] + g[j][1].y;
+                row = row + 2 < src_rows ? row + 2 : 0;
+                g[j][0] = src[(size_t)row * 64 + lane];
+                g[j][1] = src[(size_t)(row + 1) * 64 + lane];
             }
+        }
+    } else {
+        for (int it = 0; it < iters; it++) {
+#pragma unroll
+            for (int rep = 0; rep < 8; rep++)
+#pragma unroll
+                for (int k = 0; k < 8; k++) {
+                    if (FORM == 0) a[k] = __builtin_fma(a[k], mul, add);
+                    if (FORM == 1) a[k] = __builtin_fma(a[k], b, c);
+                    if (FORM == 2) a[k] = a[k] + c;
+                }
+        }
     }
     double sum = 0;
 #pragma unroll
@@ -1037,14 +1080,18 @@ template <int FORM> __global__ __launch_bounds__(256) void k_fp64_probe(double *
     out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
 }
 
-hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters, hipStream_t st)
+hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters, const double2 *src, uint32_t src_rows,
+                             hipStream_t st)
 {
+#define SHE_LAUNCH_PROBE(F) hipLaunchKernelGGL(k_fp64_probe<F>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9, src, src_rows)
     switch (form) {
-    case 0: hipLaunchKernelGGL(k_fp64_probe<0>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
-    case 1: hipLaunchKernelGGL(k_fp64_probe<1>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
-    case 2: hipLaunchKernelGGL(k_fp64_probe<2>, dim3(blocks), dim3(256), 0, st, d_out, iters, 1.0000001, 1e-9); break;
+    case 0: SHE_LAUNCH_PROBE(0); break;
+    case 1: SHE_LAUNCH_PROBE(1); break;
+    case 2: SHE_LAUNCH_PROBE(2); break;
+    case 3: if (!src || src_rows < 4) return hipErrorInvalidValue; SHE_LAUNCH_PROBE(3); break;
     default: return hipErrorInvalidValue;
     }
+#undef SHE_LAUNCH_PROBE
     return hipGetLastError();
 }
 

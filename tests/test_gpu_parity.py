@@ -506,12 +506,15 @@ def test_maxpool_with_majority_comparator_matches_oracle_netlist_toy(toy_ctx, to
 
 def test_fp64_issue_rate_probe_is_plausible(toy_ctx):
     # the diagnostic behind bench.py's "measured_fp64_issue": between a quarter of and the whole published FP64 peak
-    for form in (0, 1, 2):
-        r = toy_ctx.probe_fp64_rate(form)
+    rates = {}
+    for form in (0, 1, 2, 3):
+        r = rates[form] = toy_ctx.probe_fp64_rate(form)
         assert 20.0 < r["tflops_as_fma"] < 80.0 and 1.6 < r["ns_per_instruction_per_simd"] < 6.5, (form, r)
+    # the additions with the blind rotation's LDS and global loads beside them cannot issue faster than alone
+    assert rates[3]["ns_per_instruction_per_simd"] > 0.98 * rates[2]["ns_per_instruction_per_simd"], rates
     pkg = she()
     with pytest.raises(pkg.SheError):
-        toy_ctx.probe_fp64_rate(3)
+        toy_ctx.probe_fp64_rate(4)
 
 
 def test_relu_maxpool_fused_matches_oracle_netlist_and_the_two_operators_toy(toy_ctx, toy_keys):
