@@ -319,6 +319,7 @@ def main():
                                             cells3=True, fused_pool=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
+        out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))

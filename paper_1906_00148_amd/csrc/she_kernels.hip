@@ -531,20 +531,22 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     __shared__ double2 s_xch[BR_WAVES][PL::XSLOTS];
     __shared__ double2 s_tw[TwTable<PL>::COUNT];
     const int wave = threadIdx.x >> 6, t = threadIdx.x & 63;
-    const uint32_t g = blockIdx.x * BR_WAVES + wave;
-    load_twiddles<PL>(s_tw, tw_table);
-    if (g >= count) return;
+    load_twiddles<PL>(s_tw, tw_table);                                    // once per workgroup: the grid is persistent
 
     LaneCtx<PL> lc;
     lc.init(t, s_xch[wave], s_tw);
-    const uint32_t *d1 = trlwe + (size_t)in1[g] * 2 * N, *d0 = trlwe + (size_t)in0[g] * 2 * N;
-    uint32_t *dst = trlwe + (size_t)out[g] * 2 * N;
-    const double2 *rows = trgsw_hat + (size_t)sel[g] * 2 * l * 2 * P * L + t;
-
     const uint32_t Bg = 1u << bg_bit, half_bg = Bg >> 1;
     uint32_t dec_off = 1u << (31 - l * bg_bit);
     uint32_t flip = 0;
     for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
+    float worst = 0.f;
+
+    // a wavefront takes CMux g, g + (wavefronts in the grid), ...; g is uniform, so the four ids are scalar loads
+    const uint32_t stride = gridDim.x * BR_WAVES;
+    for (uint32_t g = __builtin_amdgcn_readfirstlane(blockIdx.x * BR_WAVES + wave); g < count; g += stride) {
+    const uint32_t *d1 = trlwe + (size_t)in1[g] * 2 * N, *d0 = trlwe + (size_t)in0[g] * 2 * N;
+    uint32_t *dst = trlwe + (size_t)out[g] * 2 * N;
+    const double2 *rows = trgsw_hat + (size_t)sel[g] * 2 * l * 2 * P * L + t;
 
     double2 bv[2][P];
 #pragma unroll
@@ -557,12 +559,17 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     for (int k = 0; k < P; k++) { sr[0][k] = si[0][k] = sr[1][k] = si[1][k] = 0.0; }
 
     for (int c = 0; c < 2; c++) {
+        // TRLWE samples are stored in transform order: the 16-byte word (q, t) of a component holds the coefficients
+        // t + L*2q, t + L*2q + M, t + L*(2q+1), t + L*(2q+1) + M, the ones lane t works on
         uint32_t dlo[P], dhi[P];
+        const uint4 *a1 = reinterpret_cast<const uint4 *>(d1 + c * N) + t, *a0 = reinterpret_cast<const uint4 *>(d0 + c * N) + t;
 #pragma unroll
-        for (int m = 0; m < P; m++) {
-            const uint32_t j0 = c * N + t + L * m, j1 = j0 + M;
-            dlo[m] = (d1[j0] - d0[j0] + dec_off) ^ flip;
-            dhi[m] = (d1[j1] - d0[j1] + dec_off) ^ flip;
+        for (int q = 0; q < P / 2; q++) {
+            const uint4 u = a1[q * L], v = a0[q * L];
+            dlo[2 * q] = (u.x - v.x + dec_off) ^ flip;
+            dhi[2 * q] = (u.y - v.y + dec_off) ^ flip;
+            dlo[2 * q + 1] = (u.z - v.z + dec_off) ^ flip;
+            dhi[2 * q + 1] = (u.w - v.w + dec_off) ^ flip;
         }
         for (uint32_t p = 0; p < l; p++) {
             const uint32_t sh = 32 - (p + 1) * bg_bit;
@@ -591,24 +598,32 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
             }
         }
     }
-    float worst = 0.f;
     {
         double2 *const xch2[2] = {lc.xch, lc.xch};
         inverse_n<PL, 2, true>(lc, xch2, sr, si);
     }
 #pragma unroll
     for (int o = 0; o < 2; o++) {
+        const uint4 *a0 = reinterpret_cast<const uint4 *>(d0 + o * N) + t;
+        uint4 *ao = reinterpret_cast<uint4 *>(dst + o * N) + t;
 #pragma unroll
-        for (int m = 0; m < P; m++) {
-            const double vr = sr[o][m], vi = si[o][m];
+        for (int q = 0; q < P / 2; q++) {
             if (TRACK) {
-                worst = fmaxf(worst, (float)fabs(vr - rint(vr)));
-                worst = fmaxf(worst, (float)fabs(vi - rint(vi)));
+#pragma unroll
+                for (int m = 2 * q; m < 2 * q + 2; m++) {
+                    worst = fmaxf(worst, (float)fabs(sr[o][m] - rint(sr[o][m])));
+                    worst = fmaxf(worst, (float)fabs(si[o][m] - rint(si[o][m])));
+                }
             }
-            const uint32_t j0 = o * N + t + L * m, j1 = j0 + M;
-            dst[j0] = d0[j0] + (uint32_t)__double2loint(vr + 6755399441055744.0);
-            dst[j1] = d0[j1] + (uint32_t)__double2loint(vi + 6755399441055744.0);
+            uint4 v = a0[q * L];
+            v.x += (uint32_t)__double2loint(sr[o][2 * q] + 6755399441055744.0);
+            v.y += (uint32_t)__double2loint(si[o][2 * q] + 6755399441055744.0);
+            v.z += (uint32_t)__double2loint(sr[o][2 * q + 1] + 6755399441055744.0);
+            v.w += (uint32_t)__double2loint(si[o][2 * q + 1] + 6755399441055744.0);
+            ao[q * L] = v;
         }
+    }
+    wave_lds_fence();                                                     // the exchange buffer is reused by the next CMux
     }
     if (TRACK && round_err) atomicMax(round_err, __float_as_uint(worst));
 }
@@ -843,7 +858,9 @@ static hipError_t cmux_t(const she_params &P, const DeviceKeys &K, const double2
                          const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
                          size_t count, unsigned *d_round_err, hipStream_t st)
 {
-    const dim3 grid((unsigned)((count + BR_WAVES - 1) / BR_WAVES)), block(64 * BR_WAVES);
+    // persistent: at most the two workgroups per compute unit that fit, each wavefront loops over its share
+    const size_t wgs = (count + BR_WAVES - 1) / BR_WAVES;
+    const dim3 grid((unsigned)std::min<size_t>(wgs, (size_t)2 * std::max<uint32_t>(K.cus, 1))), block(64 * BR_WAVES);
     if (d_round_err)
         hipLaunchKernelGGL((k_cmux<PL, true>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
                            (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);

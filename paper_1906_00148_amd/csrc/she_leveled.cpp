@@ -92,11 +92,26 @@ int she_trgsw_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t count, uint64
     return SHE_OK;
 }
 
+// Device order of a TRLWE component (the order the CMux kernel's lanes read it in): lane t of a transform works on
+// the coefficients t + 64 m and t + 64 m + N/2 (m < N/128), and the 16-byte word (q, t) holds those of m = 2q and
+// m = 2q + 1, so that one load per lane fetches four of them and a wavefront's load is one contiguous KiB.
+static inline size_t device_pos(uint32_t N, uint32_t j)
+{
+    const uint32_t M = N / 2, h = j / M, r = j % M, t = r % 64, m = r / 64;
+    return ((size_t)(m >> 1) * 64 + t) * 4 + (m & 1) * 2 + h;
+}
+
 static int upload_trlwe(she_ctx *c, const uint32_t *host, size_t count, const uint32_t *dst_ids)
 {
-    const size_t words = (size_t)2 * c->P.N;
+    const uint32_t N = c->P.N;
+    const size_t words = (size_t)2 * N;
+    std::vector<uint32_t> dev(count * words);
     for (size_t k = 0; k < count; k++)
-        HIP_TRY(c, hipMemcpyAsync(c->lev.trlwe + dst_ids[k] * words, host + k * words, words * 4, hipMemcpyHostToDevice,
+        for (uint32_t comp = 0; comp < 2; comp++)
+            for (uint32_t j = 0; j < N; j++)
+                dev[k * words + comp * N + device_pos(N, j)] = host[k * words + comp * N + j];
+    for (size_t k = 0; k < count; k++)
+        HIP_TRY(c, hipMemcpyAsync(c->lev.trlwe + dst_ids[k] * words, dev.data() + k * words, words * 4, hipMemcpyHostToDevice,
                                   c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return SHE_OK;
@@ -135,11 +150,17 @@ int she_trlwe_read(she_ctx *c, const uint32_t *ids, size_t count, uint32_t *samp
     if (count == 0) return SHE_OK;
     if (!samples || !ids) return fail(c, SHE_EINVAL, "null argument");
     if ((rc = check_range(c, ids, count, c->lev.trlwe_cap, "she_trlwe_read"))) return rc;
-    const size_t words = (size_t)2 * c->P.N;
+    const uint32_t N = c->P.N;
+    const size_t words = (size_t)2 * N;
+    std::vector<uint32_t> dev(count * words);
     for (size_t k = 0; k < count; k++)
-        HIP_TRY(c, hipMemcpyAsync(samples + k * words, c->lev.trlwe + ids[k] * words, words * 4, hipMemcpyDeviceToHost,
+        HIP_TRY(c, hipMemcpyAsync(dev.data() + k * words, c->lev.trlwe + ids[k] * words, words * 4, hipMemcpyDeviceToHost,
                                   c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (size_t k = 0; k < count; k++)
+        for (uint32_t comp = 0; comp < 2; comp++)
+            for (uint32_t j = 0; j < N; j++)
+                samples[k * words + comp * N + j] = dev[k * words + comp * N + device_pos(N, j)];
     return SHE_OK;
 }
 
