@@ -92,6 +92,35 @@ def test_cmux_level_bit_exact_toy(toy_ctx, toy_keys, count):
     assert np.array_equal(toy_ctx.trlwe_read(out_ids), got)
 
 
+def test_cmux_level_longer_than_the_grid_toy(toy_keys):
+    """More CMuxes than the persistent grid has wavefronts (2 workgroups of 4 per compute unit): every wavefront
+    loops, some once more than others.  A sample spread over all rounds against the oracle word for word, every
+    output's selected branch by its phase."""
+    pkg = she()
+    P = toy_keys.params
+    count, nsel, ndat = 4999, 16, 64
+    rng = np.random.default_rng(4999)
+    with pkg.Context(pkg.TOY, S.KEY_SEED, 16) as ctx:
+        ctx.leveled_init(nsel, ndat + count)
+        bits = rng.integers(0, 2, nsel).astype(np.uint8)
+        sel_ids = np.arange(nsel, dtype=np.uint32)
+        ctx.trgsw_encrypt_bits(bits, 91, sel_ids)
+        sels = O.trgsw_encrypt_bits(toy_keys, bits, 91)
+        mu = messages(rng, ndat, P.N)
+        ctx.trlwe_encrypt(mu, 92, np.arange(ndat, dtype=np.uint32))
+        data = O.trlwe_encrypt(toy_keys, mu, 92)
+        s, i1, i0 = rng.integers(0, nsel, count), rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+        out_ids = (ndat + np.arange(count)).astype(np.uint32)
+        ctx.eval_cmux(s, i1, i0, out_ids)
+        phases = ctx.trlwe_phase(out_ids)
+        chosen = np.where(bits[s][:, None] == 1, mu[i1], mu[i0])
+        assert np.array_equal(signed(phases) > 0, signed(chosen) > 0)
+        sample = np.unique(np.concatenate([np.arange(0, count, 83), [2047, 2048, 4095, 4096, count - 1]]))
+        got = ctx.trlwe_read(out_ids[sample])
+        for k, m in enumerate(sample):
+            assert np.array_equal(got[k], O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])), m
+
+
 def test_cmux_bit_exact_real_parameters(real_ctx, real_keys):
     P = real_keys.params
     rng = np.random.default_rng(7)
