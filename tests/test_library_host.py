@@ -119,3 +119,37 @@ def test_planning_calls_match_the_oracle_netlists():
         she.plan_shift_acc(1, 2, 8, [[1, 2]], [[0, 0]], 16)                      # bad sign
     with pytest.raises(she.SheError):
         she.plan_shift_acc(1, 1, 8, [[1]], [[-8]], 16)                           # shift out of range
+
+
+def test_fp64_products_round_to_the_exact_integers_under_the_parameter_rule():
+    """The library multiplies in Z[X]/(X^N+1) with FP64 transforms and rounds; she_keygen admits a parameter set only
+    if 2*l*N*Bg^2 <= 2^30.  The same arithmetic on the CPU (numpy's FP64 FFT on the folded, twisted polynomial, no code
+    of the library), on digits and key coefficients of the admitted sizes with every digit at full magnitude: the sums
+    of 2*l products land within a small fraction of 1/2 of the exact integers, which Python integers give."""
+    import numpy as np
+    rng = np.random.default_rng(2030)
+    for N, l, bg_bit in ((1024, 3, 7), (256, 3, 7), (512, 2, 9)):
+        assert 2 * l * N * 4 ** bg_bit <= 1 << 30
+        M, half = N // 2, 1 << (bg_bit - 1)
+        twist = np.exp(1j * np.pi * np.arange(M) / N)
+
+        def spectrum(a):
+            return np.fft.ifft((a[:M] + 1j * a[M:]) * twist) * M          # kernel exp(+2 pi i jk/M)
+
+        worst = 0.0
+        for trial in range(3):
+            digits = rng.choice([-half, half - 1], size=(2 * l, N)).astype(np.int64)      # worst-case magnitudes
+            keys = rng.integers(-(1 << 31), 1 << 31, size=(2 * l, N), dtype=np.int64)
+            acc = sum(spectrum(digits[r].astype(np.float64)) * spectrum(keys[r].astype(np.float64)) for r in range(2 * l))
+            u = np.fft.fft(acc) / M * np.conj(twist)
+            got = np.concatenate([u.real, u.imag])
+            # exact negacyclic sum in Python integers (schoolbook on a few output coefficients is enough to pin the
+            # order and sign conventions; the rounding distance is checked on all of them)
+            for j in (0, 1, M - 1, M, N - 1):
+                exact = 0
+                for r in range(2 * l):
+                    d, k = digits[r].tolist(), keys[r].tolist()
+                    exact += sum(d[i] * k[j - i] for i in range(j + 1)) - sum(d[i] * k[N + j - i] for i in range(j + 1, N))
+                assert round(got[j]) == exact, (N, j)
+            worst = max(worst, float(np.abs(got - np.rint(got)).max()))
+        assert worst < 0.1, (N, l, bg_bit, worst)
