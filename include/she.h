@@ -45,7 +45,7 @@ typedef struct she_ctx she_ctx; /* opaque: keys (secret ones too), device buffer
 /* TFHE parameter set (Section 4, "TFHE setting", names the three sample levels; the
  * gate-bootstrapping values used by the benchmarks are n=630, N=1024, k=1, bg_bit=7,
  * l=3, ks_t=8, ks_basebit=2, lwe_std=2^-15, bk_std=2^-25).  Supported: k = 1;
- * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8 and 2*l*N*Bg^2 <= 2^30 (so that the
+ * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8 and 2*l*N*Bg^2 <= 2^32 (so that the
  * FP64 polynomial products round to the exact integers); ks_t*ks_basebit <= 16 with ks_basebit <= 4. */
 typedef struct {
     uint32_t n;          /* TLWE dimension */

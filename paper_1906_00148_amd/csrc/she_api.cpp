@@ -180,9 +180,10 @@ bool params_supported(const she_params &P, std::string &why)
     if (P.n < 1 || P.n > 4096) { why = "n must be in [1, 4096]"; return false; }
     if (P.l < 1 || P.l > 8 || P.bg_bit < 1 || P.l * P.bg_bit > 31) { why = "need 1 <= l <= 8 and l*bg_bit <= 31"; return false; }
     // the FP64 transforms stay exact after rounding only while the products are small enough:
-    // typical magnitude ~ sqrt(2 l N) * Bg/2 * 2^31 must leave a wide margin below 2^53
-    if ((uint64_t)2 * P.l * P.N * ((uint64_t)1 << (2 * P.bg_bit)) > ((uint64_t)1 << 30)) {
-        why = "need 2*l*N*Bg^2 <= 2^30 (exactness of the FP64 polynomial products)"; return false;
+    // typical magnitude ~ sqrt(2 l N) * Bg/2 * 2^31 must leave a wide margin below 2^53.  At the bound (N = 1024,
+    // l = 2, Bg = 2^10) sums of products with every digit at full magnitude land within 0.07 of an integer.
+    if ((uint64_t)2 * P.l * P.N * ((uint64_t)1 << (2 * P.bg_bit)) > ((uint64_t)1 << 32)) {
+        why = "need 2*l*N*Bg^2 <= 2^32 (exactness of the FP64 polynomial products)"; return false;
     }
     if (P.ks_t < 1 || P.ks_basebit < 1 || P.ks_basebit > 4 || P.ks_t * P.ks_basebit > 16) {
         why = "need ks_basebit <= 4 and ks_t*ks_basebit <= 16"; return false;

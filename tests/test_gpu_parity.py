@@ -407,10 +407,12 @@ def test_maxpool_with_native_mux_matches_oracle_netlist_toy(toy_ctx, toy_keys):
 # ------------------------------------------------------------------ other gadget and key-switch shapes
 @pytest.mark.parametrize("shape", [dict(n=64, N=256, l=2, bg_bit=10, ks_t=5, ks_basebit=3),
                                    dict(n=80, N=512, l=4, bg_bit=6, ks_t=4, ks_basebit=4),
-                                   dict(n=48, N=1024, l=2, bg_bit=8, ks_t=16, ks_basebit=1)])
+                                   dict(n=48, N=1024, l=2, bg_bit=8, ks_t=16, ks_basebit=1),
+                                   dict(n=40, N=1024, l=2, bg_bit=10, ks_t=8, ks_basebit=2)])
 def test_other_parameter_shapes_use_the_generic_key_switch(shape):
     """Gadget lengths 1..4 and key-switch bases other than 4 (these take the select-and-subtract
-    key-switch kernel, not the MFMA one): gates and a native MUX, every word against the oracle."""
+    key-switch kernel, not the MFMA one; the last shape has the MFMA one's base and the largest gadget base the
+    parameter rule admits at N = 1024): gates and a native MUX, every word against the oracle."""
     pkg = she()
     K = O.keygen(O.Params(**shape), 77)
     with pkg.Context(pkg.Params(**shape), 77, 256) as ctx:
@@ -418,7 +420,11 @@ def test_other_parameter_shapes_use_the_generic_key_switch(shape):
         in_ids = np.arange(40, dtype=np.uint32)
         out_ids = np.arange(40, 60, dtype=np.uint32)
         ctx.encrypt_bits(bits, 17, in_ids)
+        ctx.set_round_tracking(True)
+        ctx.get_round_error(reset=True)
         ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
+        assert ctx.get_round_error() < 0.2          # the last shape sits on the bound 2*l*N*Bg^2 = 2^32
+        ctx.set_round_tracking(False)
         pool = np.zeros((64, shape["n"] + 1), np.uint32)
         pool[:40] = O.encrypt_bits(K, bits, 17)
         O.eval_gates(K, pool, codes, in_ids[0::2], in_ids[1::2], out_ids, threads=8)
