@@ -152,6 +152,32 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
 int she_relu_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                      const uint32_t *out_ids, uint64_t *gates_out);
 
+/* Section 3.1 (every operator of the network is a circuit of homomorphic gates; "Homomorphic Operations" names the
+ * 2-input operations and the MUX).  A whole circuit in one call: ngates entries in topological order, entry g of
+ * code type[g] reading the references in0[g], in1[g] (and in2[g] for three-input codes and SHE_CIRCUIT_MUX).  A
+ * reference is a pool id, SHE_WIRE_GATE | h for the result of entry h < g of the same call, SHE_WIRE_ZERO /
+ * SHE_WIRE_ONE for the noiseless trivial ciphertexts, each optionally with SHE_WIRE_NOT (the complement, a free
+ * word-wise negation; accepted only under SHE_OPT_FOLD_CONSTANTS, which absorbs it into the gate codes).
+ * Codes: the ten 2-input codes, SHE_MAJ3 + mask, SHE_XOR3 + mask, and SHE_CIRCUIT_MUX (in0 ? in1 : in2, three gates
+ * or one native entry under SHE_OPT_NATIVE_MUX).  The library schedules every entry at its earliest depth level,
+ * evaluates each level as one batch (as she_eval_gates / she_eval_gates3 / she_eval_mux do), keeps intermediate
+ * results in its own temporaries, and leaves the results named by out_refs[0..nout) in the pool slots out_ids;
+ * the options fold entries exactly as they do inside the layer operators.  out_ids must be distinct and disjoint
+ * from every pool id the circuit reads.  *entries_out (may be NULL) receives the number of entries evaluated.
+ * Errors: SHE_EINVAL (unknown code, forward reference, SHE_WIRE_NOT without folding, null pointers, clashing ids),
+ * SHE_ERANGE (id outside the pool). */
+#define SHE_WIRE_GATE 0x40000000u
+#define SHE_WIRE_NOT 0x80000000u
+#define SHE_WIRE_ZERO 0x3FFFFFFEu
+#define SHE_WIRE_ONE 0x3FFFFFFFu
+#define SHE_CIRCUIT_MUX 255
+int she_eval_circuit(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                     size_t ngates, const uint32_t *out_refs, const uint32_t *out_ids, size_t nout, uint64_t *entries_out);
+/* The same circuit without a GPU: entries left after folding under `options` (bitwise OR of SHE_OPT_* values), depth
+ * levels and blind rotations; pool ids in the references must be below `capacity`. */
+int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                     size_t ngates, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
+
 /* Options.  SHE_OPT_FOLD_CONSTANTS (default 0): the layer operators stop spending a bootstrap on
  * gates whose result is fixed by a trivial-constant or repeated operand (the zeros that a shift
  * leaves on top of a term, the carry-in of the subtraction, the comparator's first stage): such a

@@ -85,6 +85,9 @@ def load_library() -> C.CDLL:
         "she_plan_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
                                        C.POINTER(C.c_uint32), u64p]),
         "she_eval_mux": (C.c_int, [ctx, u32p, u32p, u32p, u32p, C.c_size_t]),
+        "she_eval_circuit": (C.c_int, [ctx, u8p, u32p, u32p, u32p, C.c_size_t, u32p, u32p, C.c_size_t, u64p]),
+        "she_plan_circuit": (C.c_int, [C.c_uint32, u8p, u32p, u32p, u32p, C.c_size_t, C.c_int, u64p,
+                                       C.POINTER(C.c_uint32), u64p]),
         "she_eval_gates3": (C.c_int, [ctx, u8p, u32p, u32p, u32p, u32p, C.c_size_t]),
         "she_leveled_init": (C.c_int, [ctx, C.c_uint32, C.c_uint32]),
         "she_trgsw_encrypt_bits": (C.c_int, [ctx, u8p, C.c_size_t, C.c_uint64, u32p]),
@@ -178,6 +181,25 @@ def plan_relu_maxpool(H: int, W: int, Cn: int, bits: int, fold: bool = False, na
     g, lv, rot = C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
     rc = load_library().she_plan_relu_maxpool(H, W, Cn, bits, _options(fold, native_mux, cells3), C.byref(g), C.byref(lv),
                                               C.byref(rot))
+    return _plan(rc, g, lv) + (rot.value,)
+
+
+# operand references of eval_circuit / plan_circuit (include/she.h)
+WIRE_GATE = 0x40000000
+WIRE_NOT = 0x80000000
+WIRE_ZERO = 0x3FFFFFFE
+WIRE_ONE = 0x3FFFFFFF
+CIRCUIT_MUX = 255
+
+
+def plan_circuit(capacity: int, types, in0, in1, in2, fold: bool = False, native_mux: bool = False):
+    """(entries, levels, blind rotations) of she_eval_circuit for this circuit; runs on the host, no GPU needed."""
+    types, in0, in1, in2 = _u8(types).ravel(), _u32(in0).ravel(), _u32(in1).ravel(), _u32(in2).ravel()
+    assert types.size == in0.size == in1.size == in2.size
+    g, lv, rot = C.c_uint64(0), C.c_uint32(0), C.c_uint64(0)
+    rc = load_library().she_plan_circuit(capacity, _p(types, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
+                                         _p(in2, C.c_uint32), types.size, _options(fold, native_mux), C.byref(g),
+                                         C.byref(lv), C.byref(rot))
     return _plan(rc, g, lv) + (rot.value,)
 
 
@@ -295,6 +317,17 @@ class Context:
         self._check(self._L.she_maxpool(self._h, _p(x_ids, C.c_uint32), H, W, Cn, bits, _p(out_ids, C.c_uint32),
                                         C.byref(gates)))
         return gates.value
+
+    def eval_circuit(self, types, in0, in1, in2, out_refs, out_ids) -> int:
+        """A whole circuit in one call (references as in include/she.h); returns the entries evaluated."""
+        types, in0, in1, in2 = _u8(types).ravel(), _u32(in0).ravel(), _u32(in1).ravel(), _u32(in2).ravel()
+        out_refs, out_ids = _u32(out_refs).ravel(), _u32(out_ids).ravel()
+        assert types.size == in0.size == in1.size == in2.size and out_refs.size == out_ids.size
+        n = C.c_uint64(0)
+        self._check(self._L.she_eval_circuit(self._h, _p(types, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
+                                             _p(in2, C.c_uint32), types.size, _p(out_refs, C.c_uint32),
+                                             _p(out_ids, C.c_uint32), out_ids.size, C.byref(n)))
+        return n.value
 
     def relu_maxpool(self, x_ids, out_ids) -> int:
         x_ids, out_ids = _u32(x_ids), _u32(out_ids)

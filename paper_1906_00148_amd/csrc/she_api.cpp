@@ -732,6 +732,129 @@ int she_get_option(she_ctx *c, int option, int *value)
     return fail(c, SHE_EINVAL, "unknown option");
 }
 
+static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
+
+// ---- a caller's own circuit ----
+// Appends the entries of a circuit given as reference arrays to `nl`; wires[g] receives the wire of entry g
+// (under folding possibly a constant, an earlier wire or a complement).  Returns "" or what is wrong.
+static std::string circuit_to_netlist(Netlist &nl, const uint8_t *type, const uint32_t *in0, const uint32_t *in1,
+                                      const uint32_t *in2, size_t ngates, std::vector<uint32_t> &wires, bool *range_error)
+{
+    wires.assign(ngates, 0);
+    *range_error = false;
+    std::string why;
+    auto wire_of = [&](uint32_t ref, size_t g, uint32_t &w) {
+        const bool neg = (ref & SHE_WIRE_NOT) != 0;
+        const uint32_t r = ref & ~SHE_WIRE_NOT;
+        if (neg && !nl.fold) { why = "SHE_WIRE_NOT needs SHE_OPT_FOLD_CONSTANTS"; return false; }
+        if (r == SHE_WIRE_ZERO) w = nl.zero();
+        else if (r == SHE_WIRE_ONE) w = nl.one();
+        else if (r & SHE_WIRE_GATE) {
+            const uint32_t h = r & ~SHE_WIRE_GATE;
+            if (h >= g) { why = "an entry refers to itself or to a later entry"; return false; }
+            w = wires[h];
+        } else {
+            if (r >= nl.cap) { why = "id outside the pool"; *range_error = true; return false; }
+            w = r;
+        }
+        if (neg) w ^= WIRE_NEG;
+        return true;
+    };
+    for (size_t g = 0; g < ngates; g++) {
+        const uint8_t t = type[g];
+        uint32_t a = 0, b = 0, c = 0;
+        if (!wire_of(in0[g], g, a) || !wire_of(in1[g], g, b)) return why;
+        if (t < SHE_NUM_GATES) {
+            wires[g] = nl.gate(t, a, b);
+        } else if (t == SHE_CIRCUIT_MUX || (t >= SHE_MAJ3 && t < SHE_XOR3 + 8)) {
+            if (!in2) return "three-input entries need in2";
+            if (!wire_of(in2[g], g, c)) return why;
+            if (t == SHE_CIRCUIT_MUX) {
+                wires[g] = nl.mux(a, b, c);
+            } else if (!nl.fold) {
+                wires[g] = nl.gate3(t, a, b, c);                     // the code carries its complement mask as it is
+            } else {
+                const int base = t >= SHE_XOR3 ? SHE_XOR3 : SHE_MAJ3, mask = t - base;
+                wires[g] = nl.gate3(base, a ^ ((mask & 1) ? WIRE_NEG : 0u), b ^ ((mask & 2) ? WIRE_NEG : 0u),
+                                    c ^ ((mask & 4) ? WIRE_NEG : 0u));
+            }
+        } else {
+            return "unknown gate code";
+        }
+        if (nl.overflow) return "circuit too large for 31-bit wire ids";
+    }
+    return "";
+}
+
+int she_eval_circuit(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                     size_t ngates, const uint32_t *out_refs, const uint32_t *out_ids, size_t nout, uint64_t *entries_out)
+{
+    if (!c) return SHE_EINVAL;
+    if (entries_out) *entries_out = 0;
+    if (nout == 0) return SHE_OK;                                      // nothing asked for: nothing to evaluate
+    if ((ngates && (!type || !in0 || !in1)) || !out_refs || !out_ids) return fail(c, SHE_EINVAL, "null argument");
+    if (ngates >= SHE_WIRE_GATE - 2) return fail(c, SHE_EINVAL, "too many entries for one call");
+    int rc;
+    if ((rc = check_ids(c, out_ids, nout, "she_eval_circuit out_ids"))) return rc;
+    try {
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        std::vector<uint32_t> wires;
+        bool range_error = false;
+        const std::string why = circuit_to_netlist(nl, type, in0, in1, in2, ngates, wires, &range_error);
+        if (!why.empty()) return fail(c, range_error ? SHE_ERANGE : SHE_EINVAL, "she_eval_circuit: " + why);
+        // pool ids the circuit reads (operands and outputs that name an input directly)
+        std::vector<uint32_t> reads;
+        auto note = [&](uint32_t ref) {
+            const uint32_t r = ref & ~SHE_WIRE_NOT;
+            if (!(r & SHE_WIRE_GATE) && r != SHE_WIRE_ZERO && r != SHE_WIRE_ONE) reads.push_back(r);
+        };
+        for (size_t g = 0; g < ngates; g++) {
+            note(in0[g]); note(in1[g]);
+            if (type[g] >= SHE_NUM_GATES) note(in2[g]);
+        }
+        std::vector<uint32_t> out_wires(nout);
+        for (size_t k = 0; k < nout; k++) {
+            const bool neg = (out_refs[k] & SHE_WIRE_NOT) != 0;
+            const uint32_t r = out_refs[k] & ~SHE_WIRE_NOT;
+            uint32_t w;
+            if (neg && !nl.fold) return fail(c, SHE_EINVAL, "she_eval_circuit: SHE_WIRE_NOT needs SHE_OPT_FOLD_CONSTANTS");
+            if (r == SHE_WIRE_ZERO) w = nl.zero();
+            else if (r == SHE_WIRE_ONE) w = nl.one();
+            else if (r & SHE_WIRE_GATE) {
+                if ((r & ~SHE_WIRE_GATE) >= ngates) return fail(c, SHE_EINVAL, "she_eval_circuit: output refers to a missing entry");
+                w = wires[r & ~SHE_WIRE_GATE];
+            } else {
+                if (r >= c->cap) return fail(c, SHE_ERANGE, "she_eval_circuit: id outside the pool");
+                w = r;
+                reads.push_back(r);
+            }
+            out_wires[k] = neg ? (w ^ WIRE_NEG) : w;
+        }
+        if ((rc = check_disjoint(c, reads.data(), reads.size(), nullptr, 0, out_ids, nout))) return rc;
+        return run_netlist(c, nl, out_wires, out_ids, entries_out);
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation for the netlist");
+    }
+}
+
+int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
+                     size_t ngates, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
+{
+    if (ngates && (!type || !in0 || !in1)) return SHE_EINVAL;
+    if (capacity == 0 || capacity > 0x3FFFFFF0u || ngates >= SHE_WIRE_GATE - 2) return SHE_EINVAL;
+    try {
+        Netlist nl(capacity, (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
+                   (options & SHE_OPT_GATE3_CELLS) != 0);
+        std::vector<uint32_t> wires;
+        bool range_error = false;
+        const std::string why = circuit_to_netlist(nl, type, in0, in1, in2, ngates, wires, &range_error);
+        if (!why.empty()) return range_error ? SHE_ERANGE : SHE_EINVAL;
+        return plan_finish(nl, gates, levels, rotations);
+    } catch (const std::bad_alloc &) {
+        return SHE_ENOMEM;
+    }
+}
+
 // ---- planning: the operators' netlists without a GPU (inputs are wires 0, 1, 2, ... in argument order) ----
 static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
 {

@@ -81,3 +81,38 @@ def subset(total: int, count: int, seed: int) -> np.ndarray:
     """Sorted seeded sample of `count` indices out of `total` (for spot checks)."""
     rng = np.random.default_rng(seed)
     return np.sort(rng.choice(total, size=min(count, total), replace=False))
+
+
+def random_circuit(n_inputs: int, n_gates: int, seed: int, with_not: bool = False):
+    """A random acyclic circuit for the whole-circuit call: entry g has a kind (one of the five common 2-input gate
+    names, "MAJ", "XOR3" or "MUX"), three operands (only two used by 2-input gates) and a complement flag per operand
+    (all False unless with_not).  An operand v means: 0 <= v < n_inputs an input, n_inputs + h the result of entry
+    h < g, -1 the constant 0, -2 the constant 1.  Operands favour recent entries so that the circuit gets deep, and
+    a few repeat an operand or name a constant so that folding has something to do.  Returns (kinds, ops, neg, outs):
+    outs are the operands-style references of the results to keep (every entry nobody reads, plus one input and one
+    constant)."""
+    rng = np.random.default_rng(seed)
+    kinds, ops, neg = [], np.zeros((n_gates, 3), np.int64), np.zeros((n_gates, 3), bool)
+    names = GATE_NAMES_5 + ("MAJ", "XOR3", "MUX")
+    used = np.zeros(n_gates, bool)
+    for g in range(n_gates):
+        kinds.append(names[int(rng.integers(0, len(names)))])
+        for k in range(3):
+            r = rng.random()
+            if r < 0.04:
+                v = -1 - int(rng.integers(0, 2))
+            elif g > 0 and r < 0.70:
+                v = n_inputs + int(max(0, g - 1 - rng.integers(0, min(g, 12))))
+            else:
+                v = int(rng.integers(0, n_inputs))
+            ops[g, k] = v
+        if rng.random() < 0.05:
+            ops[g, 1] = ops[g, 0]
+        if with_not:
+            neg[g] = rng.random(3) < 0.2
+        arity = 2 if kinds[-1] in GATE_NAMES_5 else 3
+        for k in range(arity):
+            if ops[g, k] >= n_inputs:
+                used[ops[g, k] - n_inputs] = True
+    outs = [n_inputs + g for g in range(n_gates) if not used[g]] + [0, -2]
+    return kinds, ops, neg, np.asarray(outs, np.int64)

@@ -541,3 +541,55 @@ def test_relu_maxpool_fused_matches_oracle_netlist_and_the_two_operators_toy(toy
     toy_ctx.relu(ids.reshape(-1, 4), relu_ids.reshape(-1, 4))
     toy_ctx.maxpool(relu_ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
     assert OC.from_bits(toy_ctx.decrypt(pool_ids.reshape(2, 4)), True).tolist() == want.tolist()
+
+
+# ------------------------------------------------------------------ whole circuits in one call
+@pytest.mark.parametrize("fold,native", [(False, False), (True, True)])
+def test_eval_circuit_random_circuit_matches_the_oracle_netlist_toy(toy_ctx, toy_keys, fold, native):
+    """A random acyclic circuit of 2-input gates, majority / parity gates and MUXes (constants, repeated operands and,
+    under folding, complements) through she_eval_circuit: every kept result word for word against the oracle's
+    netlist of the same circuit, the decrypted bits against the circuit's plain definition, a real-parameter run
+    against the plain definition."""
+    from tests import circuit_cases as CC
+    pkg = she()
+    n_inputs = 24
+    kinds, ops, neg, outs = S.random_circuit(n_inputs, 160, 77, with_not=fold)
+    rng = np.random.default_rng(78)
+    bits = rng.integers(0, 2, n_inputs).astype(np.uint8)
+    in_ids = (40 + rng.permutation(60)[:n_inputs]).astype(np.uint32)          # scattered pool slots
+    out_ids = np.arange(300, 300 + outs.size, dtype=np.uint32)
+    types, in0, in1, in2, out_refs = CC.to_she_arrays(pkg, kinds, ops, neg, outs, n_inputs, in_ids)
+    nl, out_wires = CC.to_oracle_netlist(kinds, ops, neg, outs, n_inputs, fold=fold, native_mux=native)
+    toy_ctx.encrypt_bits(bits, 79, in_ids)
+    toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
+    toy_ctx.set_option(pkg.OPT_NATIVE_MUX, int(native))
+    try:
+        entries = toy_ctx.eval_circuit(types, in0, in1, in2, out_refs, out_ids)
+        assert entries == len(nl.gtype)
+        assert toy_ctx.last_timing()["levels"] == int(nl.levels().max())
+        pool = nl.run_encrypted(toy_keys, O.encrypt_bits(toy_keys, bits, 79), threads=8)
+        assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, out_wires))
+        assert np.array_equal(toy_ctx.decrypt(out_ids), CC.plain_circuit(kinds, ops, neg, outs, n_inputs, bits))
+        # argument errors: an output slot that the circuit reads, a reference to a later entry
+        with pytest.raises(pkg.SheError):
+            toy_ctx.eval_circuit(types, in0, in1, in2, out_refs[:1], in_ids[:1])
+        with pytest.raises(pkg.SheError):
+            toy_ctx.eval_circuit([1], [pkg.WIRE_GATE | 0], [int(in_ids[0])], [0], [pkg.WIRE_GATE | 0], [300])
+    finally:
+        toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
+        toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
+
+
+def test_eval_circuit_real_parameters_decrypts_to_the_plain_circuit(real_ctx):
+    from tests import circuit_cases as CC
+    pkg = she()
+    n_inputs = 32
+    kinds, ops, neg, outs = S.random_circuit(n_inputs, 1500, 81)
+    rng = np.random.default_rng(82)
+    bits = rng.integers(0, 2, n_inputs).astype(np.uint8)
+    in_ids = np.arange(n_inputs, dtype=np.uint32)
+    out_ids = np.arange(1000, 1000 + outs.size, dtype=np.uint32)
+    real_ctx.encrypt_bits(bits, 83, in_ids)
+    types, in0, in1, in2, out_refs = CC.to_she_arrays(pkg, kinds, ops, neg, outs, n_inputs, in_ids)
+    real_ctx.eval_circuit(types, in0, in1, in2, out_refs, out_ids)
+    assert np.array_equal(real_ctx.decrypt(out_ids), CC.plain_circuit(kinds, ops, neg, outs, n_inputs, bits))

@@ -296,3 +296,39 @@ def test_relu_then_pool_as_one_netlist_equals_the_two_operators():
     # a quarter of the masking gates: 3 maxes of 7w gates + (w - 1) masks per window against 4 (w - 1) + 3 * 7w
     fused, _ = C.build_relu_maxpool(2, 2, 1, 16)
     assert len(fused.gtype) == 3 * 112 + 15
+
+
+# ------------------------------------------------------------------ whole circuits (she_eval_circuit's host side)
+@pytest.mark.parametrize("fold,native", [(False, False), (False, True), (True, False), (True, True)])
+def test_random_circuits_plan_like_the_oracle_netlist_and_evaluate_to_the_plain_circuit(fold, native):
+    """The library's planning call (its own folding rules, levelizer and rotation count, no GPU) against the oracle's
+    netlist builder on random acyclic circuits with constants, repeated operands and complements, and the oracle's
+    netlist evaluated on plaintext bits against the circuit's plain definition."""
+    import paper_1906_00148_amd as pkg
+    import synth_inputs as S
+    from tests import circuit_cases as CC
+    n_inputs = 24
+    for seed in (1, 2, 3):
+        kinds, ops, neg, outs = S.random_circuit(n_inputs, 400, seed, with_not=fold)
+        nl, out_wires = CC.to_oracle_netlist(kinds, ops, neg, outs, n_inputs, fold=fold, native_mux=native)
+        types, in0, in1, in2, _ = CC.to_she_arrays(pkg, kinds, ops, neg, outs, n_inputs, np.arange(n_inputs))
+        entries, levels, rotations = pkg.plan_circuit(n_inputs, types, in0, in1, in2, fold=fold, native_mux=native)
+        lev = nl.levels()
+        assert entries == len(nl.gtype) and rotations == nl.rotations
+        assert levels == (int(lev.max()) if lev.size else 0)
+        rng = np.random.default_rng(seed)
+        for _ in range(4):
+            bits = rng.integers(0, 2, n_inputs).astype(np.uint8)
+            got = C.Netlist.read_plain(nl.run_plain(bits), out_wires)
+            assert np.array_equal(got, CC.plain_circuit(kinds, ops, neg, outs, n_inputs, bits))
+    if not fold:
+        types, in0, in1, in2, _ = CC.to_she_arrays(pkg, ["AND"], np.zeros((1, 3), np.int64), np.array([[True, False, False]]),
+                                                   np.array([n_inputs]), n_inputs, np.arange(n_inputs))
+        with pytest.raises(pkg.SheError):                      # a complement needs folding
+            pkg.plan_circuit(n_inputs, types, in0, in1, in2)
+    with pytest.raises(pkg.SheError):                          # forward reference
+        pkg.plan_circuit(8, [1], [pkg.WIRE_GATE | 0], [0], [0])
+    with pytest.raises(pkg.SheError):                          # id outside the pool
+        pkg.plan_circuit(8, [1], [8], [0], [0])
+    with pytest.raises(pkg.SheError):                          # unknown code
+        pkg.plan_circuit(8, [99], [0], [1], [0])
