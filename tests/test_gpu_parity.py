@@ -178,6 +178,18 @@ def test_cfg2_real_level(real_ctx, real_keys):
     O.eval_gates(real_keys, pool, codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub], threads=16)
     got = real_ctx.read_cts(out_ids[sub])
     assert np.array_equal(got, pool[out_ids[sub]])
+    # the launch bench.py times: all 4096 gates in one call on device-resident id arrays, tracking off
+    import torch
+    for i in out_ids[sub]:                                   # forget the sampled results first
+        real_ctx.write_ct(int(i), np.zeros(real_keys.params.n + 1, np.uint32))
+    d_type = torch.from_numpy(codes.copy()).cuda()
+    d_in0 = torch.from_numpy(in_ids[0::2].astype(np.int32)).cuda()
+    d_in1 = torch.from_numpy(in_ids[1::2].astype(np.int32)).cuda()
+    d_out = torch.from_numpy(out_ids.astype(np.int32)).cuda()
+    real_ctx.eval_gates_device(d_type.data_ptr(), d_in0.data_ptr(), d_in1.data_ptr(), d_out.data_ptr(), G)
+    torch.cuda.synchronize()
+    assert np.array_equal(real_ctx.read_cts(out_ids[sub]), pool[out_ids[sub]])
+    assert np.array_equal(real_ctx.decrypt(out_ids), want_bits)
     # the production kernels (tracking off) give the same words: one wavefront per gate, then two
     pkg = she()
     default_split = real_ctx.get_option(pkg.OPT_SPLIT_BELOW)
