@@ -32,8 +32,8 @@ FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop/FMA 
 # ISA: 6 forward rows x 323 + 518 (inverse transforms, rounding); beside them 443 LDS, 97 global-load and about 535
 # integer vector instructions
 FP64_INSTR_PER_CMUX = 2456
-# HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 960,333 KiB scaled by 2.00,
-# WRITE_SIZE 95,433 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
+# HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 948,610 KiB scaled by 2.00,
+# WRITE_SIZE 110,478 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
 # profiles/k_blind_rotate_level4096_n630_N1024_counters.txt.  Algorithmic bytes are ~75 MB: the excess is the
 # key spectra streamed once per XCD L2 and per resident batch (8 x 2 x 61.9 MB), served by the Infinity Cache.
 MEASURED_TRAFFIC_BYTES = 2.06e9
@@ -219,7 +219,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-gates", type=int, default=64)
+    ap.add_argument("--cpu-sample-gates", type=int, default=32)
     ap.add_argument("--no-conv-layer", action="store_true", help="skip config 5 (one conv layer, ~2.5M gates, ~15 s)")
     ap.add_argument("--leveled-only", action="store_true",
                     help="run only the leveled-mode CMux level and print its entry (for profiling k_cmux)")
