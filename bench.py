@@ -62,23 +62,27 @@ def cpu_baseline(sample_gates: int):
                       f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
 
 
-def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False, fused_pool: bool = False):
+def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False, fused_pool: bool = False,
+               narrow: bool = False):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
     accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
     skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); cells3: full-adder cells of
-    two three-input gates (SHE_OPT_GATE3_CELLS)."""
+    two three-input gates (SHE_OPT_GATE3_CELLS); narrow: the accumulators, the ReLU and the pooling
+    get the width that the layer's plaintext weights can fill (the same integers come out)."""
     import numpy as np
 
     import synth_inputs as S
+    from paper_1906_00148_amd.layers import accumulator_bits
 
     img, sign, exp = S.cfg5_conv_layer()
     H, W = img.shape
     oc, k = sign.shape[0], sign.shape[1]
     oh, ow = H - k + 1, W - k + 1
     n_in = H * W * 8
-    conv_ids = n_in + np.arange(oh * ow * oc * 16, dtype=np.uint32)
-    relu_ids = conv_ids[-1] + 1 + np.arange(oh * ow * oc * 16, dtype=np.uint32)
-    pool_ids = relu_ids[-1] + 1 + np.arange((oh // 2) * (ow // 2) * oc * 16, dtype=np.uint32)
+    AB = min(16, accumulator_bits(sign.reshape(oc, -1), exp.reshape(oc, -1), 8)) if narrow else 16
+    conv_ids = n_in + np.arange(oh * ow * oc * AB, dtype=np.uint32)
+    relu_ids = conv_ids[-1] + 1 + np.arange(oh * ow * oc * AB, dtype=np.uint32)
+    pool_ids = relu_ids[-1] + 1 + np.arange((oh // 2) * (ow // 2) * oc * AB, dtype=np.uint32)
     ctx = ctx_factory(int(pool_ids[-1]) + 1)
     ctx.set_option(1, int(fold))
     ctx.set_option(2, int(native_mux))
@@ -94,20 +98,20 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     w_sign = np.broadcast_to(sign.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
     w_exp = np.broadcast_to(exp.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(-1, k * k)
     t0 = time.perf_counter()
-    g1 = ctx.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, 16, conv_ids.reshape(-1, 16))
+    g1 = ctx.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, AB, conv_ids.reshape(-1, AB))
     t1 = time.perf_counter()
     if fused_pool:                       # ReLU and pooling as one operator (she_relu_maxpool)
         g2, t2 = 0, t1
-        g3 = ctx.relu_maxpool(conv_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
+        g3 = ctx.relu_maxpool(conv_ids.reshape(oh, ow, oc, AB), pool_ids.reshape(oh // 2, ow // 2, oc, AB))
     else:
-        g2 = ctx.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+        g2 = ctx.relu(conv_ids.reshape(-1, AB), relu_ids.reshape(-1, AB))
         t2 = time.perf_counter()
-        g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, 16), pool_ids.reshape(oh // 2, ow // 2, oc, 16))
+        g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, AB), pool_ids.reshape(oh // 2, ow // 2, oc, AB))
     t3 = time.perf_counter()
-    # all 13x13x8 outputs against plain integer arithmetic
-    dec = ctx.decrypt(pool_ids.reshape(-1, 16)).astype(np.int64)
-    got = (dec << np.arange(16)).sum(axis=1)
-    got = np.where(got >= 32768, got - 65536, got).reshape(oh // 2, ow // 2, oc)
+    # all 13x13x8 outputs against plain integer arithmetic (16-bit accumulators: the narrow widths hold the same values)
+    dec = ctx.decrypt(pool_ids.reshape(-1, AB)).astype(np.int64)
+    got = (dec << np.arange(AB)).sum(axis=1)
+    got = np.where(got >= (1 << (AB - 1)), got - (1 << AB), got).reshape(oh // 2, ow // 2, oc)
     conv = np.zeros((oh, ow, oc), np.int64)
     for dy in range(k):
         for dx in range(k):
@@ -120,6 +124,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
             "constant_folding": bool(fold), "native_mux": bool(native_mux), "cells3": bool(cells3), "relu_and_pool_fused": bool(fused_pool),
+            "accumulator_bits": int(AB),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -318,6 +323,8 @@ def main():
         out["conv_layer"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=False)
         out["conv_layer_lean"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True, native_mux=True,
                                             cells3=True, fused_pool=True)
+        out["conv_layer_lean_narrow"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True,
+                                                   native_mux=True, cells3=True, fused_pool=True, narrow=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)

@@ -12,6 +12,22 @@ from __future__ import annotations
 import numpy as np
 
 
+def accumulator_bits(w_sign, w_exp, in_bits: int) -> int:
+    """Smallest two's-complement width that holds every sum  sum_i sign_i * (x_i >> |exp_i|)  over unsigned in_bits-bit
+    inputs, for weights [units][terms] (the weights are plaintext, so the server knows the range; Section 3.3 sizes
+    the accumulator's adders by the bits they can receive).  A layer run at this width gives the same integers as at
+    any larger one."""
+    w_sign, w_exp = np.asarray(w_sign, np.int64), np.asarray(w_exp, np.int64)
+    w_sign, w_exp = w_sign.reshape(-1, w_sign.shape[-1]), w_exp.reshape(-1, w_exp.shape[-1])
+    top = ((1 << in_bits) - 1) >> (-w_exp)
+    hi = int(np.where(w_sign > 0, top, 0).sum(axis=1).max(initial=0))
+    lo = int(np.where(w_sign < 0, top, 0).sum(axis=1).max(initial=0))
+    bits = 1
+    while not (lo <= (1 << (bits - 1)) and hi <= (1 << (bits - 1)) - 1):
+        bits += 1
+    return max(bits, in_bits)
+
+
 class Chain:
     """Hands out fresh pool ids from `first_free` upwards and counts the gates spent."""
 

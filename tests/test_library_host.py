@@ -153,3 +153,21 @@ def test_fp64_products_round_to_the_exact_integers_under_the_parameter_rule():
                 assert round(got[j]) == exact, (N, j)
             worst = max(worst, float(np.abs(got - np.rint(got)).max()))
         assert worst < 0.1, (N, l, bg_bit, worst)
+
+
+def test_accumulator_bits_is_the_smallest_width_that_holds_every_sum():
+    """layers.accumulator_bits against the extreme sums written out: all positive-weight inputs at their maximum and the
+    others at zero, and the other way round."""
+    import numpy as np
+    from paper_1906_00148_amd.layers import accumulator_bits
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        units, terms, in_bits = int(rng.integers(1, 5)), int(rng.integers(1, 40)), int(rng.integers(1, 9))
+        sign = rng.choice([-1, 1], (units, terms))
+        exp = -rng.integers(0, in_bits, (units, terms))
+        bits = accumulator_bits(sign, exp, in_bits)
+        top = (1 << in_bits) - 1
+        hi = max(sum(top >> -e for s, e in zip(sign[u], exp[u]) if s > 0) for u in range(units))
+        lo = max(sum(top >> -e for s, e in zip(sign[u], exp[u]) if s < 0) for u in range(units))
+        fits = lambda b: -(1 << (b - 1)) <= -lo and hi <= (1 << (b - 1)) - 1
+        assert fits(bits) and bits >= in_bits and (bits == in_bits or not fits(bits - 1))
