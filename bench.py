@@ -63,7 +63,7 @@ def cpu_baseline(sample_gates: int):
 
 
 def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False, fused_pool: bool = False,
-               narrow: bool = False):
+               narrow: bool = False, columns: bool = False):
     """Config 5: 28x28x1 8-bit image, 3x3 conv to 8 channels (log-quantized weights, 16-bit
     accumulators), ReLU, 2x2 max pool; returns latency and gate counts.  fold: let the operators
     skip gates fixed by constant operands (SHE_OPT_FOLD_CONSTANTS); cells3: full-adder cells of
@@ -87,6 +87,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     ctx.set_option(1, int(fold))
     ctx.set_option(2, int(native_mux))
     ctx.set_option(4, int(cells3))
+    ctx.set_option(8, int(columns))      # SHE_OPT_COLUMN_ADDER: the sums by column compression
     bits = ((img[..., None] >> np.arange(8)) & 1).astype(np.uint8)
     in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, 8)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(5), in_ids.ravel())
@@ -124,7 +125,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     total = g1 + g2 + g3
     return {"workload": "28x28x1 -> conv3x3x8 (shift-accumulate) -> ReLU -> maxpool2x2, n=630 N=1024",
             "constant_folding": bool(fold), "native_mux": bool(native_mux), "cells3": bool(cells3), "relu_and_pool_fused": bool(fused_pool),
-            "accumulator_bits": int(AB),
+            "accumulator_bits": int(AB), "column_adder": bool(columns),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
@@ -325,6 +326,8 @@ def main():
                                             cells3=True, fused_pool=True)
         out["conv_layer_lean_narrow"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True,
                                                    native_mux=True, cells3=True, fused_pool=True, narrow=True)
+        out["conv_layer_lean_columns"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True,
+                                                    native_mux=True, cells3=True, fused_pool=True, narrow=True, columns=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)

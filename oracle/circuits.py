@@ -400,13 +400,82 @@ def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
     return list(x_bits[s:]) + [nl.ZERO] * min(s, w)
 
 
+def column_accumulate(nl: Netlist, terms: list, acc_bits: int) -> list:
+    """Sum of signed terms mod 2^acc_bits by column compression (Section 3.3 asks for an accumulator whose adders are
+    only as wide as the bits they receive; here every bit is placed in the column of its weight and columns are
+    compressed with full-adder cells).  terms: (wires of an unsigned value, LSB first, no padding; sign).  A negative
+    term enters as the complements of its w wires plus the constant 1 - 2^w (since -t = not(t) - 2^w + 1 on w bits);
+    the constants of all negative terms are added up in plain arithmetic and enter as ONE wires.  Stages: in every
+    column, left to right, each run of three wires becomes a parity wire in the same column and a majority wire in the
+    next (dropped beyond the top column), leftovers stay; a stage's column holds the carries from the column below
+    first, then its own parities, then its leftovers; wires that folding proves ZERO are dropped.  When no column holds
+    more than two wires, one ripple adder of cells finishes.  Needs fold (complements, constants) and cells3."""
+    assert nl.fold and nl.cells3
+    cols = [[] for _ in range(acc_bits)]
+    const = 0
+    for bits, sign in terms:
+        for b, wire in enumerate(bits[:acc_bits]):
+            cols[b].append(wire if sign > 0 else wire ^ NEG)
+        if sign < 0:
+            const += 1 - (1 << len(bits))
+    const %= 1 << acc_bits
+    for j in range(acc_bits):
+        if (const >> j) & 1:
+            cols[j].append(nl.ONE)
+    while max((len(c) for c in cols), default=0) > 2:
+        new = [[] for _ in range(acc_bits)]
+        for j in range(acc_bits):
+            bits, k = cols[j], 0
+            while len(bits) - k >= 3:
+                a, b, c = bits[k:k + 3]
+                k += 3
+                s = nl.gate3("XOR", a, b, c)
+                if s != nl.ZERO:
+                    new[j].append(s)
+                if j + 1 < acc_bits:
+                    m = nl.gate3("MAJ", a, b, c)
+                    if m != nl.ZERO:
+                        new[j + 1].append(m)
+            new[j].extend(bits[k:])
+        cols = new
+    out, carry = [], None
+    for j in range(acc_bits):
+        ops = cols[j] + ([carry] if carry is not None else [])
+        last = j == acc_bits - 1
+        if not ops:
+            out.append(nl.ZERO)
+            carry = None
+        elif len(ops) == 1:
+            out.append(ops[0])
+            carry = None
+        elif len(ops) == 2:
+            out.append(nl.gate("XOR", ops[0], ops[1]))
+            carry = None if last else nl.gate("AND", ops[0], ops[1])
+        else:
+            out.append(nl.gate3("XOR", ops[0], ops[1], ops[2]))
+            carry = None if last else nl.gate3("MAJ", ops[0], ops[1], ops[2])
+        if carry == nl.ZERO:
+            carry = None
+    return out
+
+
 def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                    cells3: bool = False):
-    """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits])."""
+                    cells3: bool = False, columns: bool = False):
+    """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits]).  columns: the sum
+    by column compression (column_accumulate) instead of the adder trees and the subtraction."""
     w_sign = np.asarray(w_sign).reshape(units, terms)
     w_exp = np.asarray(w_exp).reshape(units, terms)
     nl = Netlist(units * terms * in_bits, fold, cells3=cells3)
     outs = []
+    if columns:
+        for u in range(units):
+            vecs = []
+            for t in range(terms):
+                base = (u * terms + t) * in_bits
+                drop = abs(int(w_exp[u, t]))
+                vecs.append((list(range(base + drop, base + in_bits)), int(w_sign[u, t])))
+            outs.append(column_accumulate(nl, vecs, acc_bits))
+        return nl, outs
     for u in range(units):
         pos, neg = [], []
         for t in range(terms):

@@ -137,11 +137,13 @@ OPT_FOLD_CONSTANTS = 1
 OPT_NATIVE_MUX = 2
 OPT_SPLIT_BELOW = 3
 OPT_GATE3_CELLS = 4
+OPT_COLUMN_ADDER = 8
 MAJ3, XOR3 = 176, 184        # three-input gate codes; + mask (bit i complements input i)
 
 
-def _options(fold: bool, native_mux: bool, cells3: bool = False) -> int:
-    return (OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0) | (OPT_GATE3_CELLS if cells3 else 0)
+def _options(fold: bool, native_mux: bool, cells3: bool = False, columns: bool = False) -> int:
+    return ((OPT_FOLD_CONSTANTS if fold else 0) | (OPT_NATIVE_MUX if native_mux else 0) | (OPT_GATE3_CELLS if cells3 else 0)
+            | (OPT_COLUMN_ADDER if columns else 0))
 
 
 def _plan(rc, gates, levels):
@@ -151,13 +153,13 @@ def _plan(rc, gates, levels):
 
 
 def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                   cells3: bool = False):
+                   cells3: bool = False, columns: bool = False):
     """(gates, levels) of she_shift_acc for these weights; runs on the host, no GPU needed."""
     w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
     g, lv = C.c_uint64(0), C.c_uint32(0)
     return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
-                                                   acc_bits, _options(fold, False, cells3), C.byref(g), C.byref(lv),
-                                                   None), g, lv)
+                                                   acc_bits, _options(fold, False, cells3, columns), C.byref(g),
+                                                   C.byref(lv), None), g, lv)
 
 
 def plan_relu(count: int, bits: int, fold: bool = False):

@@ -542,7 +542,18 @@ static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids,
 {
     std::vector<uint32_t> wires;
     wires.reserve((size_t)units * acc_bits);
-    for (uint32_t u = 0; u < units; u++) {
+    for (uint32_t u = 0; nl.columns && u < units; u++) {
+        std::vector<SignedTerm> signed_terms(terms);
+        for (uint32_t t = 0; t < terms; t++) {
+            const size_t k = (size_t)u * terms + t;
+            const uint32_t drop = (uint32_t)(-(int)w_exp[k]);            // x >> drop: the low wires fall away
+            signed_terms[t].bits.assign(x_ids + k * in_bits + std::min(drop, in_bits), x_ids + (k + 1) * in_bits);
+            signed_terms[t].sign = w_sign[k] > 0 ? 1 : -1;
+        }
+        const std::vector<uint32_t> total = nl_columns(nl, signed_terms, acc_bits);
+        wires.insert(wires.end(), total.begin(), total.end());
+    }
+    for (uint32_t u = 0; !nl.columns && u < units; u++) {
         std::vector<std::vector<uint32_t>> pos, neg;
         for (uint32_t t = 0; t < terms; t++) {
             const size_t k = (size_t)u * terms + t;
@@ -630,8 +641,10 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     const char *why = "";
     if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return fail(c, SHE_EINVAL, why);
+    if (c->columns && !(c->fold && c->cells3))
+        return fail(c, SHE_EINVAL, "SHE_OPT_COLUMN_ADDER needs SHE_OPT_FOLD_CONSTANTS and SHE_OPT_GATE3_CELLS");
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
         const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -653,7 +666,7 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
         const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -676,7 +689,7 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
         const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -699,7 +712,7 @@ int she_relu_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, 
     if ((rc = check_ids(c, out_ids, n_out, "she_relu_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
         const std::vector<uint32_t> wires = wires_relu_maxpool(nl, x_ids, H, W, C, bits);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
@@ -713,6 +726,7 @@ int she_set_option(she_ctx *c, int option, int value)
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
     if (option == SHE_OPT_GATE3_CELLS) { c->cells3 = value != 0; return SHE_OK; }
+    if (option == SHE_OPT_COLUMN_ADDER) { c->columns = value != 0; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) {
         if (value < 0) return fail(c, SHE_EINVAL, "SHE_OPT_SPLIT_BELOW takes a gate count >= 0");
         c->split_below = (size_t)value;
@@ -728,6 +742,7 @@ int she_get_option(she_ctx *c, int option, int *value)
     if (option == SHE_OPT_FOLD_CONSTANTS) { *value = c->fold; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { *value = c->native_mux; return SHE_OK; }
     if (option == SHE_OPT_GATE3_CELLS) { *value = c->cells3; return SHE_OK; }
+    if (option == SHE_OPT_COLUMN_ADDER) { *value = c->columns; return SHE_OK; }
     if (option == SHE_OPT_SPLIT_BELOW) { *value = (int)std::min<size_t>(c->split_below, 0x7FFFFFFF); return SHE_OK; }
     return fail(c, SHE_EINVAL, "unknown option");
 }
@@ -797,7 +812,7 @@ int she_eval_circuit(she_ctx *c, const uint8_t *type, const uint32_t *in0, const
     int rc;
     if ((rc = check_ids(c, out_ids, nout, "she_eval_circuit out_ids"))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3);
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
         std::vector<uint32_t> wires;
         bool range_error = false;
         const std::string why = circuit_to_netlist(nl, type, in0, in1, in2, ngates, wires, &range_error);
@@ -844,7 +859,7 @@ int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0
     if (capacity == 0 || capacity > 0x3FFFFFF0u || ngates >= SHE_WIRE_GATE - 2) return SHE_EINVAL;
     try {
         Netlist nl(capacity, (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_GATE3_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
         std::vector<uint32_t> wires;
         bool range_error = false;
         const std::string why = circuit_to_netlist(nl, type, in0, in1, in2, ngates, wires, &range_error);
@@ -873,11 +888,12 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
     if (n_in > 0x40000000u || (terms && units && (!w_sign || !w_exp))) return SHE_EINVAL;
     const char *why = "";
     if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return SHE_EINVAL;
+    if ((options & SHE_OPT_COLUMN_ADDER) && !((options & SHE_OPT_FOLD_CONSTANTS) && (options & SHE_OPT_GATE3_CELLS))) return SHE_EINVAL;
     try {
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_GATE3_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
         wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -892,7 +908,7 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
         std::vector<uint32_t> ids((size_t)count * bits);
         for (size_t k = 0; k < ids.size(); k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(ids.size(), 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_GATE3_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
         wires_relu(nl, ids.data(), count, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -909,7 +925,7 @@ int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_GATE3_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
         wires_relu_maxpool(nl, ids.data(), H, W, C, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
@@ -926,7 +942,7 @@ int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int opti
         std::vector<uint32_t> ids(n_in);
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
-                   (options & SHE_OPT_GATE3_CELLS) != 0);
+                   (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
         wires_maxpool(nl, ids.data(), H, W, C, bits);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {

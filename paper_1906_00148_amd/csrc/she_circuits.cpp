@@ -293,6 +293,67 @@ std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const 
 
 // Mixed-bitwidth accumulator: tree level j adds neighbours with min(in_bits+j, acc_bits)-bit adders,
 // an unpaired last vector moves up zero-extended; the result is zero-extended to acc_bits.
+// Section 3.3 wants an accumulator whose adders are only as wide as the bits that reach them.  Here every bit sits in
+// the column of its weight.  A negative term contributes the complements of its w wires and the constant 1 - 2^w
+// (-t = not(t) - 2^w + 1 on w bits); the constants are summed in plain arithmetic and enter as trivial-one wires.
+// A stage turns each run of three wires of a column, from the front, into a parity wire in that column and a
+// majority wire in the next one (none beyond the top column); what is left of the column follows unchanged.  In the
+// new column the carries from below come first, then the parities, then the leftovers; a wire that folding proves
+// zero is dropped.  Once no column holds more than two wires a ripple adder of cells finishes the sum.
+std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits)
+{
+    std::vector<std::vector<uint32_t>> cols(acc_bits);
+    uint64_t constant = 0;                                   // mod 2^acc_bits at the end (acc_bits <= 32)
+    for (const SignedTerm &term : terms) {
+        for (size_t b = 0; b < term.bits.size() && b < acc_bits; b++)
+            cols[b].push_back(term.sign > 0 ? term.bits[b] : term.bits[b] ^ WIRE_NEG);
+        if (term.sign < 0) constant += 1 - ((uint64_t)1 << term.bits.size());      // wraps mod 2^64: fine
+    }
+    for (uint32_t j = 0; j < acc_bits; j++)
+        if ((constant >> j) & 1u) cols[j].push_back(nl.one());
+    auto widest = [&]() { size_t w = 0; for (const auto &c : cols) w = std::max(w, c.size()); return w; };
+    while (widest() > 2) {
+        std::vector<std::vector<uint32_t>> next(acc_bits);
+        for (uint32_t j = 0; j < acc_bits; j++) {
+            const std::vector<uint32_t> &bits = cols[j];
+            size_t k = 0;
+            for (; bits.size() - k >= 3; k += 3) {
+                const uint32_t s = nl.gate3(SHE_XOR3, bits[k], bits[k + 1], bits[k + 2]);
+                if (s != nl.zero()) next[j].push_back(s);
+                if (j + 1 < acc_bits) {
+                    const uint32_t m = nl.gate3(SHE_MAJ3, bits[k], bits[k + 1], bits[k + 2]);
+                    if (m != nl.zero()) next[j + 1].push_back(m);
+                }
+            }
+            next[j].insert(next[j].end(), bits.begin() + k, bits.end());
+        }
+        cols.swap(next);
+    }
+    std::vector<uint32_t> out;
+    out.reserve(acc_bits);
+    bool have_carry = false;
+    uint32_t carry = 0;
+    for (uint32_t j = 0; j < acc_bits; j++) {
+        std::vector<uint32_t> ops = cols[j];
+        if (have_carry) ops.push_back(carry);
+        const bool last = j + 1 == acc_bits;
+        have_carry = false;
+        if (ops.empty()) {
+            out.push_back(nl.zero());
+        } else if (ops.size() == 1) {
+            out.push_back(ops[0]);
+        } else if (ops.size() == 2) {
+            out.push_back(nl.gate(SHE_XOR, ops[0], ops[1]));
+            if (!last) { carry = nl.gate(SHE_AND, ops[0], ops[1]); have_carry = true; }
+        } else {
+            out.push_back(nl.gate3(SHE_XOR3, ops[0], ops[1], ops[2]));
+            if (!last) { carry = nl.gate3(SHE_MAJ3, ops[0], ops[1], ops[2]); have_carry = true; }
+        }
+        if (have_carry && carry == nl.zero()) have_carry = false;
+    }
+    return out;
+}
+
 std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> terms, uint32_t in_bits, uint32_t acc_bits)
 {
     uint32_t width = in_bits;

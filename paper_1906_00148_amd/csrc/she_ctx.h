@@ -52,6 +52,7 @@ struct she_ctx {
     bool fold = false;                   // SHE_OPT_FOLD_CONSTANTS
     bool native_mux = false;             // SHE_OPT_NATIVE_MUX
     bool cells3 = false;                 // SHE_OPT_GATE3_CELLS
+    bool columns = false;                // SHE_OPT_COLUMN_ADDER
     size_t split_below = 0;              // SHE_OPT_SPLIT_BELOW (set at creation: 6 x compute units)
     uint8_t *d_mtype = nullptr;          // device staging of MUX rotations: 2 jobs per MUX entry
     uint32_t *d_min0 = nullptr, *d_min1 = nullptr, *d_mout = nullptr;

@@ -117,13 +117,16 @@ struct Netlist {
     bool fold = false;
     bool native_mux = false;                    // mux() emits one three-input entry instead of three gates
     bool cells3 = false;                        // adders use cells of two three-input gates (parity, majority)
+    bool columns = false;                       // shift-accumulate sums by column compression (nl_columns)
     bool overflow = false;                      // more wires than 31-bit ids can name
     std::vector<uint8_t> type;
     std::vector<uint32_t> in0, in1, in2, out;   // in2: third operand of MUX entries and three-input gates (0 otherwise)
     std::vector<uint32_t> copy_src, copy_dst;   // executed after all gates; copy_src may carry WIRE_NEG
 
-    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false, bool cells3 = false)
-        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native), cells3(cells3) {}
+    explicit Netlist(uint32_t capacity, bool fold_constants = false, bool mux_native = false, bool cells3 = false,
+                     bool columns = false)
+        : cap(capacity), next_temp(capacity + 2), fold(fold_constants), native_mux(mux_native), cells3(cells3),
+          columns(columns) {}
     uint64_t rotations() const;                 // blind rotations: one per gate, two per MUX entry
     uint32_t zero() const { return cap; }
     uint32_t one() const { return cap + 1; }
@@ -142,5 +145,9 @@ std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const 
 std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const std::vector<uint32_t> &q);
 std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> terms, uint32_t in_bits, uint32_t acc_bits);
 std::vector<uint32_t> nl_max(Netlist &nl, const std::vector<uint32_t> &x, const std::vector<uint32_t> &y);
+// signed sum of unsigned terms (wires LSB first, no padding; sign +1 / -1) mod 2^acc_bits by column compression;
+// the netlist must fold constants and use three-input cells
+struct SignedTerm { std::vector<uint32_t> bits; int sign; };
+std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits);
 
 }  // namespace she

@@ -60,6 +60,26 @@ def test_cfg3_neuron_with_three_input_cells(ctx):
     assert np.array_equal(OC.from_bits(ctx.decrypt(out), True), OC.plain_shift_acc(x, sign, exp, 16))
 
 
+def test_cfg3_neuron_by_column_compression(ctx):
+    """The 576-term neuron with SHE_OPT_COLUMN_ADDER: 5,398 gates instead of 8,847, the same sum."""
+    import paper_1906_00148_amd as pkg
+    x, sign, exp = S.cfg3_neuron()
+    ids = encrypt_values(ctx, x, 8, S.data_seed(3))
+    out = np.arange(200000, 200016, dtype=np.uint32).reshape(1, 16)
+    for opt in (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER):
+        ctx.set_option(opt, 1)
+    try:
+        gates = ctx.shift_acc(ids, sign, exp, 16, out)
+        t = ctx.last_timing()
+        print(f"\ncfg3, column compression: {gates} gates in {t['levels']} levels, blind rotate {t['blind_rotate_ms']:.1f} ms")
+        nl, _ = OC.build_shift_acc(1, 576, 8, sign, exp, 16, fold=True, cells3=True, columns=True)
+        assert gates == len(nl.gtype) == 5398 and t["levels"] == int(nl.levels().max()) == 23
+        assert np.array_equal(OC.from_bits(ctx.decrypt(out), True), OC.plain_shift_acc(x, sign, exp, 16))
+    finally:
+        for opt in (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER):
+            ctx.set_option(opt, 0)
+
+
 def test_cfg4_relu_maxpool_reduced_and_corner_values(ctx):
     fm = S.cfg4_feature_map(8, 8, 4)
     fm[0, 0, 0], fm[0, 1, 0], fm[1, 0, 0], fm[1, 1, 0] = -32768, 32767, 0, -1

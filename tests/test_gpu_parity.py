@@ -502,6 +502,36 @@ def test_shift_acc_with_cells3_matches_oracle_netlist_toy(toy_ctx, toy_keys, fol
         toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
 
 
+def test_shift_acc_by_column_compression_matches_oracle_netlist_toy(toy_ctx, toy_keys):
+    """SHE_OPT_COLUMN_ADDER: every output word against the oracle's netlist of the same accumulator (outputs may be
+    complemented wires or constants: the all-negative and the empty unit), decrypted sums against plain arithmetic,
+    and the option refused without folding and cells."""
+    pkg = she()
+    x = np.array([[5, 7, 2, 6, 1, 4, 7], [3, 3, 0, 7, 4, 1, 6], [7, 7, 7, 7, 7, 7, 7]])
+    sign = np.array([[1, -1, 1, 1, -1, 1, 1], [1, 1, 1, 1, 1, 1, 1], [-1, -1, -1, -1, -1, -1, -1]], np.int8)
+    exp = np.array([[0, -1, 0, -2, 0, 0, -1], [0, 0, -1, -2, -2, 0, 0], [0, 0, 0, -1, -2, 0, 0]], np.int8)
+    in_bits, acc_bits = 3, 6
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 72, 0)
+    out_ids = np.arange(1000, 1000 + 3 * acc_bits, dtype=np.uint32).reshape(3, acc_bits)
+    toy_ctx.set_option(pkg.OPT_COLUMN_ADDER, 1)
+    try:
+        with pytest.raises(pkg.SheError):
+            toy_ctx.shift_acc(ids.reshape(3, 7, in_bits), sign, exp, acc_bits, out_ids)
+        toy_ctx.set_option(pkg.OPT_GATE3_CELLS, 1)
+        toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 1)
+        gates = toy_ctx.shift_acc(ids.reshape(3, 7, in_bits), sign, exp, acc_bits, out_ids)
+        nl, outs = OC.build_shift_acc(3, 7, in_bits, sign, exp, acc_bits, fold=True, cells3=True, columns=True)
+        trees, _ = OC.build_shift_acc(3, 7, in_bits, sign, exp, acc_bits, fold=True, cells3=True)
+        assert gates == len(nl.gtype) < len(trees.gtype)
+        assert toy_ctx.last_timing()["levels"] == int(nl.levels().max())
+        pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+        assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(out_ids), True), OC.plain_shift_acc(x, sign, exp, acc_bits))
+    finally:
+        for opt in (pkg.OPT_COLUMN_ADDER, pkg.OPT_GATE3_CELLS, pkg.OPT_FOLD_CONSTANTS):
+            toy_ctx.set_option(opt, 0)
+
+
 @pytest.mark.parametrize("fold,native", [(False, False), (True, True)])
 def test_maxpool_with_majority_comparator_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold, native):
     pkg = she()

@@ -332,3 +332,46 @@ def test_random_circuits_plan_like_the_oracle_netlist_and_evaluate_to_the_plain_
         pkg.plan_circuit(8, [1], [8], [0], [0])
     with pytest.raises(pkg.SheError):                          # unknown code
         pkg.plan_circuit(8, [99], [0], [1], [0])
+
+
+# ------------------------------------------------------------------ accumulator by column compression
+def test_column_accumulator_sums_like_plain_arithmetic_and_plans_like_the_library():
+    """Oracle netlist of the column-compression accumulator evaluated on plaintext bits against the definition
+    sum_i sign_i (x_i >> |e_i|) mod 2^acc (random shapes, weights and inputs; all inputs of a small shape
+    exhaustively), and its entry / level counts against the library's own builder (host-only planning call)."""
+    import paper_1906_00148_amd as pkg
+    rng = np.random.default_rng(33)
+
+    def check(units, terms, in_bits, acc, sign, exp, inputs):
+        nl, outs = C.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=True, cells3=True, columns=True)
+        for x in inputs:
+            val = nl.run_plain(C.to_bits(np.asarray(x).ravel(), in_bits).ravel())
+            got = [int(C.from_bits(C.Netlist.read_plain(val, outs[u])[None, :], False)[0]) for u in range(units)]
+            want = [sum(int(s) * (int(v) >> int(-e)) for s, v, e in zip(sign[u], x[u], exp[u])) % (1 << acc)
+                    for u in range(units)]
+            assert got == want, (units, terms, in_bits, acc)
+        entries, levels = pkg.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold=True, cells3=True, columns=True)
+        lev = nl.levels()
+        assert entries == len(nl.gtype) and levels == (int(lev.max()) if lev.size else 0)
+
+    for _ in range(120):
+        units, terms, in_bits = int(rng.integers(1, 3)), int(rng.integers(1, 14)), int(rng.integers(1, 7))
+        acc = int(rng.integers(in_bits, in_bits + 7))
+        sign = rng.choice([-1, 1], (units, terms))
+        exp = -rng.integers(0, in_bits, (units, terms))
+        check(units, terms, in_bits, acc, sign, exp, [rng.integers(0, 1 << in_bits, (units, terms)) for _ in range(3)])
+    # one shape exhaustively: three 2-bit inputs, every sign pattern, two shift patterns
+    for signs in itertools.product([-1, 1], repeat=3):
+        for exps in ((0, 0, 0), (0, -1, 0)):
+            xs = [np.array([v]) for v in itertools.product(range(4), repeat=3)]
+            check(1, 3, 2, 4, np.array([signs]), np.array([exps]), xs)
+    # all-negative weights, maximal inputs, and the closed-form constant: -(255 + 255) mod 2^16
+    nl, outs = C.build_shift_acc(1, 2, 8, [[-1, -1]], [[0, 0]], 16, fold=True, cells3=True, columns=True)
+    val = nl.run_plain(C.to_bits(np.array([255, 255]), 8).ravel())
+    assert int(C.from_bits(C.Netlist.read_plain(val, outs[0])[None, :], False)[0]) == (65536 - 510)
+    # the option without folding and cells is refused
+    with pytest.raises(pkg.SheError):
+        pkg.plan_shift_acc(1, 2, 8, [[1, 1]], [[0, 0]], 16, fold=False, cells3=True, columns=True)
+    # closed forms of the gate counts for the benchmark shapes
+    x, sign, exp = S.cfg3_neuron()
+    assert pkg.plan_shift_acc(1, 576, 8, sign, exp, 16, fold=True, cells3=True, columns=True) == (5398, 23)
