@@ -133,7 +133,7 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
 
 def network(ctx_factory):
     """A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
-    network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX and three-input cells on."""
+    network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX, three-input cells and the column adder on."""
     import numpy as np
 
     import synth_inputs as S
@@ -164,6 +164,7 @@ def network(ctx_factory):
     ctx.set_option(1, 1)
     ctx.set_option(2, 1)
     ctx.set_option(4, 1)
+    ctx.set_option(8, 1)
     bits = ((img[..., None, None] >> np.arange(8)) & 1).astype(np.uint8)
     x_ids = np.arange(bits.size, dtype=np.uint32).reshape(bits.shape)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
@@ -179,7 +180,7 @@ def network(ctx_factory):
     assert np.array_equal(got, want), "network decrypts wrongly"
     ctx.close()
     return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
-                        "constant folding, native MUX and three-input cells on", "latency_s": dt, "entries": int(net.gates),
+                        "constant folding, native MUX, three-input cells and column-compression accumulators on", "latency_s": dt, "entries": int(net.gates),
             "entries_per_s": net.gates / dt}
 
 
