@@ -139,11 +139,12 @@ def test_cfg4_full_feature_map_relu_then_pool():
         assert np.array_equal(got, OC.plain_relu(fm).reshape(-1)[sub])
 
 
-@pytest.mark.parametrize("fold,cells", [(False, False), (True, False), (True, True)])
-def test_cfg5_conv_layer_full(fold, cells):
+@pytest.mark.parametrize("fold,cells,columns", [(False, False, False), (True, False, False), (True, True, False),
+                                                (True, True, True)])
+def test_cfg5_conv_layer_full(fold, cells, columns):
     """28x28x1 -> 3x3 conv, 8 channels (shift-accumulate) -> ReLU -> 2x2 max pool, all 1352 outputs checked;
     once with every gate of the stated netlists, once with constant folding, once with folding, full-adder cells
-    of three-input gates and native MUX gates."""
+    of three-input gates and native MUX gates, once with the sums by column compression on top."""
     import paper_1906_00148_amd as pkg
     img, sign, exp = S.cfg5_conv_layer()
     H, W = img.shape
@@ -156,6 +157,7 @@ def test_cfg5_conv_layer_full(fold, cells):
         c.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
         c.set_option(pkg.OPT_GATE3_CELLS, int(cells))
         c.set_option(pkg.OPT_NATIVE_MUX, int(cells))
+        c.set_option(pkg.OPT_COLUMN_ADDER, int(columns))
         in_ids = encrypt_values(c, img, 8, S.data_seed(5))                       # [H][W][8]
         x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)
         for dy in range(k):
@@ -171,9 +173,10 @@ def test_cfg5_conv_layer_full(fold, cells):
         g2 = c.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
         g3 = c.maxpool(relu_ids, pool_ids)
         t3 = c.last_timing()
-        print(f"\ncfg5 fold={fold} cells={cells}: conv {g1} gates / {t1['levels']} levels, relu {g2}, pool {g3} gates / "
+        print(f"\ncfg5 fold={fold} cells={cells} columns={columns}: conv {g1} gates / {t1['levels']} levels, relu {g2}, pool {g3} gates / "
               f"{t3['levels']} levels; total {g1 + g2 + g3}")
-        assert g1 == 676 * pkg.plan_shift_acc(oc, k * k, 8, sign.reshape(oc, -1), exp.reshape(oc, -1), 16, fold, cells)[0]
+        assert g1 == 676 * pkg.plan_shift_acc(oc, k * k, 8, sign.reshape(oc, -1), exp.reshape(oc, -1), 16, fold, cells,
+                                              columns)[0]
         # plain integer reference: windows, shifts, signed sum mod 2^16, ReLU, pool
         patches = np.zeros((oh, ow, k * k), np.int64)
         for dy in range(k):
