@@ -173,8 +173,8 @@ int she_relu_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W
 #define SHE_CIRCUIT_MUX 255
 int she_eval_circuit(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                      size_t ngates, const uint32_t *out_refs, const uint32_t *out_ids, size_t nout, uint64_t *entries_out);
-/* The same circuit without a GPU: entries left after folding under `options` (bitwise OR of SHE_OPT_* values), depth
- * levels and blind rotations; pool ids in the references must be below `capacity`. */
+/* The same circuit without a GPU: entries left after folding under `options` (bitwise OR of the netlist options SHE_OPT_FOLD_CONSTANTS,
+ * SHE_OPT_NATIVE_MUX, SHE_OPT_GATE3_CELLS, SHE_OPT_COLUMN_ADDER: 1, 2, 4, 8), depth levels and blind rotations; pool ids in the references must be below `capacity`. */
 int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                      size_t ngates, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
 
@@ -216,7 +216,8 @@ int she_eval_mux(she_ctx *ctx, const uint32_t *sel, const uint32_t *in1, const u
                  size_t nmux);
 
 /* Host-only planning (no GPU, no context): what she_shift_acc / she_relu / she_maxpool would evaluate
- * for these shapes and weights under `options` (bitwise OR of SHE_OPT_* values): number of netlist
+ * for these shapes and weights under `options` (bitwise OR of the netlist options SHE_OPT_FOLD_CONSTANTS, SHE_OPT_NATIVE_MUX,
+ * SHE_OPT_GATE3_CELLS, SHE_OPT_COLUMN_ADDER, which are 1, 2, 4, 8; SHE_OPT_SPLIT_BELOW is not one): number of netlist
  * entries (gates + MUX entries), of circuit levels, and of blind rotations (one per gate, two per
  * MUX entry).  Any output pointer may be NULL.  Same argument checks as the operators. */
 int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
