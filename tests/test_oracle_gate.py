@@ -265,6 +265,65 @@ def test_key_switch_of_zero_mask_is_trivial(toy_keys):
     assert not out[:P.n].any() and out[P.n] == 12345
 
 
+def _noiseless_ks(P, lwe_key, ring_key, rng, trivial_masks):
+    """A key-switching key without noise, built here in Python integers: row (i, j, v) is a TLWE sample of
+    v * s''_i * 2^(32 - (j+1)*basebit) under lwe_key with mask zero (trivial_masks) or uniform."""
+    base = 1 << P.ks_basebit
+    ks = np.zeros((P.N, P.ks_t, base - 1, P.n + 1), np.uint32)
+    for i in range(P.N):
+        for j in range(P.ks_t):
+            for v in range(1, base):
+                a = np.zeros(P.n, np.uint64) if trivial_masks else rng.integers(0, 1 << 32, P.n, dtype=np.uint64)
+                msg = v * int(ring_key[i]) << (32 - (j + 1) * P.ks_basebit)
+                body = (sum(int(x) * int(s) for x, s in zip(a, lwe_key)) + msg) % (1 << 32)
+                ks[i, j, v - 1, :P.n] = a.astype(np.uint32)
+                ks[i, j, v - 1, P.n] = body
+    return ks
+
+
+def test_key_switch_rounds_each_mask_word_to_nearest_exact_phase():
+    """With a noiseless key the key switch is exact arithmetic: phase_out = b'' - sum_i s''_i * R(a''_i), where R
+    rounds to the nearest multiple of 2^(32 - t*basebit) with ties upwards (reading 8: the digits are taken from
+    a''_i + 2^15 at t*basebit = 16).  The mask holds words exactly on the tie (2^15, which must round UP to 2^16 and
+    select the lowest digit's row), one unit below it (rounds to zero, selects nothing), a carry that ripples through
+    every digit, and a wrap past 2^32.  Flooring instead of rounding, a tie that rounds down, a digit order or a
+    row index off by one all change the expected integer."""
+    P = tfhe.Params(n=5, N=8, ks_t=8, ks_basebit=2)
+    rng = np.random.default_rng(2718)
+    lwe_key = np.array([1, 0, 1, 1, 0], np.uint8)
+    ring_key = np.array([1, 1, 0, 1, 1, 1, 0, 1], np.uint8)
+    words = [1 << 15, (1 << 15) - 1, 0x12348000, 0x3FFF7FFF, 0xFFFF8000, 0xFFFF7FFF, 0x00018000, 0x80000000]
+    keep = 32 - P.ks_t * P.ks_basebit                       # 16 dropped bits
+
+    def rounded(x):                                         # nearest multiple of 2^keep, ties up, modulo 2^32
+        return (((x + (1 << (keep - 1))) >> keep) << keep) % (1 << 32)
+
+    assert rounded(1 << 15) == 1 << 16 and rounded((1 << 15) - 1) == 0 and rounded(0xFFFF8000) == 0
+    for trivial in (True, False):
+        ks = _noiseless_ks(P, lwe_key, ring_key, rng, trivial)
+        for shift in range(P.N):                            # every word meets a set and a clear key bit
+            ext = np.array(words[shift:] + words[:shift] + [0xCAFE1234], np.uint32)
+            out = tfhe.key_switch(P, ks, ext)
+            want = (int(ext[P.N]) - sum(int(ring_key[i]) * rounded(int(ext[i])) for i in range(P.N))) % (1 << 32)
+            assert tfhe.lwe_phase(lwe_key, out) == want, (trivial, shift)
+            if trivial:
+                assert not out[:P.n].any()
+    # the same with the paper-sized digit count but base 16 (t = 4): the rounding constant follows t*basebit
+    P4 = tfhe.Params(n=5, N=8, ks_t=4, ks_basebit=4)
+    ks = _noiseless_ks(P4, lwe_key, ring_key, rng, False)
+    ext = np.array(words + [7], np.uint32)
+    out = tfhe.key_switch(P4, ks, ext)
+    want = (7 - sum(int(ring_key[i]) * rounded(int(ext[i])) for i in range(P4.N))) % (1 << 32)
+    assert tfhe.lwe_phase(lwe_key, out) == want
+    # and with 12 kept bits (t = 6, base 4): ties at 2^19
+    P6 = tfhe.Params(n=5, N=8, ks_t=6, ks_basebit=2)
+    ks = _noiseless_ks(P6, lwe_key, ring_key, rng, False)
+    ext = np.array([1 << 19, (1 << 19) - 1, 0xFFF80000, 0x12380000, 3 << 19, 0, 1 << 20, 0x7FF7FFFF, 99], np.uint32)
+    out = tfhe.key_switch(P6, ks, ext)
+    want = (99 - sum(int(ring_key[i]) * ((((int(ext[i]) + (1 << 19)) >> 20) << 20) % (1 << 32)) for i in range(P6.N))) % (1 << 32)
+    assert tfhe.lwe_phase(lwe_key, out) == want
+
+
 # ----------------------------------------------------------------- whole gates
 def _truth_table_run(K, reps, threads=8):
     P = K.params
