@@ -295,6 +295,20 @@ size_t she_pool_bytes(const she_ctx *ctx);
 int she_eval_gates_device(she_ctx *ctx, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
                           const uint32_t *d_out, size_t ngates);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): she_eval_gates_device with the level's scratch (rounded samples,
+ * extracted bodies, key-switch digits) in a static 16 MiB device buffer of the library instead of
+ * allocated buffers.  It calls no hipMalloc / hipFree and creates no events (it is never timed:
+ * she_last_timing does not see it); inputs, outputs, the pool and the keys are the caller's and the
+ * context's as before.  Same arguments, same results word for word, same lack of validation and of
+ * synchronisation as she_eval_gates_device.  Limit: bar + bodies + digits of one call must fit the
+ * buffer, i.e. ngates * (2*(n+1 rounded up to 2) + 4 + 2*N) bytes (+ alignment) <= 16 MiB: 5056 gates at
+ * n=630, N=1024; more gives SHE_ERANGE and she_last_error names the limit.  Every context on one GPU
+ * shares that GPU's buffer, which keeps the previous call's contents (nothing in it has to start at
+ * zero): calls that overlap on one GPU (two streams, two contexts) race; calls on one stream are safe. */
+int she_eval_gates_device_noalloc(she_ctx *ctx, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                                  const uint32_t *d_out, size_t ngates);
+
 /* Largest distance from an integer seen by the blind rotation's rounding of inverse
  * transform outputs since the last reset (0 <= value <= 0.5); only recorded while
  * tracking is on (slower kernel).  Exact integer results need this to stay well below 0.5. */

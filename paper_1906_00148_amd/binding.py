@@ -103,6 +103,7 @@ def load_library() -> C.CDLL:
         "she_bind_pool": (C.c_int, [ctx, C.c_void_p, C.c_size_t]),
         "she_pool_bytes": (C.c_size_t, [ctx]),
         "she_eval_gates_device": (C.c_int, [ctx, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+        "she_eval_gates_device_noalloc": (C.c_int, [ctx, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
         "she_set_round_tracking": (C.c_int, [ctx, C.c_int]),
         "she_get_round_error": (C.c_int, [ctx, C.POINTER(C.c_double), C.c_int]),
         "she_probe_fp64_rate": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
@@ -404,6 +405,11 @@ class Context:
         """Device pointers (ints); enqueues without validation or synchronisation."""
         self._check(self._L.she_eval_gates_device(self._h, C.c_void_p(d_type), C.c_void_p(d_in0), C.c_void_p(d_in1),
                                                   C.c_void_p(d_out), ngates))
+
+    def eval_gates_device_noalloc(self, d_type, d_in0, d_in1, d_out, ngates: int):
+        """eval_gates_device with the level's scratch in the library's static device buffer: allocates nothing."""
+        self._check(self._L.she_eval_gates_device_noalloc(self._h, C.c_void_p(d_type), C.c_void_p(d_in0),
+                                                          C.c_void_p(d_in1), C.c_void_p(d_out), ngates))
 
     def set_round_tracking(self, on: bool):
         self._check(self._L.she_set_round_tracking(self._h, int(on)))

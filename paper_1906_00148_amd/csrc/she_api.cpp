@@ -110,25 +110,33 @@ int ensure_mux_arrays(she_ctx *c, size_t muxes)
 
 
 // Enqueues one level (device arrays), cut into chunks of at most MAX_LEVEL_CHUNK gates.
-int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
-                  const uint32_t *d_out, size_t gates, const uint32_t *d_in2 = nullptr)
+// `W` is the level's scratch (the context's own buffers, or the caller-free static buffer); `timed` records HIP events
+// around the kernels (creating an event allocates, so the entry point that must not allocate passes false).
+int enqueue_level_on(she_ctx *c, const LevelWork &W, bool timed, const uint8_t *d_type, const uint32_t *d_in0,
+                     const uint32_t *d_in1, const uint32_t *d_out, size_t gates, const uint32_t *d_in2 = nullptr)
 {
     const CtSpace cs = space(c);
-    LevelTimer *timer = c->timing ? &c->timer : nullptr;
-    c->timer_levels++;
+    LevelTimer *timer = timed ? &c->timer : nullptr;
+    if (timed) c->timer_levels++;
     for (size_t off = 0; off < gates; off += MAX_LEVEL_CHUNK) {
         const size_t cnt = std::min<size_t>(MAX_LEVEL_CHUNK, gates - off);
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, d_in2 ? d_in2 + off : nullptr, cnt, c->work,
+        HIP_TRY(c, launch_lincomb(c->P, cs, d_type + off, d_in0 + off, d_in1 + off, d_in2 ? d_in2 + off : nullptr, cnt, W,
                                   c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, c->work, c->track_round ? c->d_round_err : nullptr, c->stream,
+        HIP_TRY(c, launch_blind_rotate(c->P, c->dk, cs, d_out + off, cnt, W, c->track_round ? c->d_round_err : nullptr, c->stream,
                                        false, cnt <= c->split_below));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
-        HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, c->work, c->stream));
+        HIP_TRY(c, launch_key_switch(c->P, c->dk, cs, d_out + off, cnt, W, c->stream));
         if (timer) HIP_TRY(c, timer->mark(c->stream));
     }
     return SHE_OK;
+}
+
+int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                  const uint32_t *d_out, size_t gates, const uint32_t *d_in2 = nullptr)
+{
+    return enqueue_level_on(c, c->work, c->timing, d_type, d_in0, d_in1, d_out, gates, d_in2);
 }
 
 // Enqueues one level of native MUX entries: jobs 2m and 2m+1 are the two rotations of entry m
@@ -360,6 +368,8 @@ int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, 
         HIP_TRY(cc, hipMemset(cc->d_round_err, 0, sizeof(unsigned)));
         int rc = ensure_temp(cc, 2);
         if (rc) return rc;
+        // address of this device's copy of the static scratch buffer (the entry point that allocates nothing)
+        HIP_TRY(cc, noalloc_scratch(cc->device, &cc->na_scratch, &cc->na_bytes));
         return SHE_OK;
     };
     int rc = body();
@@ -496,6 +506,38 @@ int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_i
     int rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK));
     if (rc) return rc;
     return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates);
+}
+
+int she_eval_gates_device_noalloc(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
+                                  const uint32_t *d_out, size_t ngates)
+{
+    if (!c) return SHE_EINVAL;
+    if (ngates == 0) return SHE_OK;
+    if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
+    if (!c->na_scratch) return fail(c, SHE_EDEVICE, "the static scratch buffer has no address on this device");
+    // carve the level's three arrays out of the static buffer, each on a 256-byte boundary
+    auto up256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    const uint32_t bar_stride = round_up(c->P.n + 1, 2);
+    const size_t groups = (ngates + KS_GROUP - 1) / KS_GROUP;
+    const size_t bar_bytes = up256(ngates * bar_stride * sizeof(uint16_t)), ext_bytes = up256(ngates * sizeof(uint32_t));
+    const size_t ksd_bytes = up256(groups * c->P.N * KS_GROUP * sizeof(uint16_t));
+    if (ngates > MAX_LEVEL_CHUNK || bar_bytes + ext_bytes + ksd_bytes > c->na_bytes) {
+        const size_t per_group = KS_GROUP * (bar_stride * sizeof(uint16_t) + sizeof(uint32_t)) + c->P.N * KS_GROUP * sizeof(uint16_t);
+        const size_t most = std::min<size_t>(MAX_LEVEL_CHUNK, (c->na_bytes - 3 * 256) / per_group * KS_GROUP);
+        return fail(c, SHE_ERANGE, "she_eval_gates_device_noalloc: " + std::to_string(ngates) + " gates need more than the " +
+                                       std::to_string(c->na_bytes) + " bytes of static scratch; at most " +
+                                       std::to_string(most) + " gates per call at these parameters");
+    }
+    LevelWork W;
+    unsigned char *base = static_cast<unsigned char *>(c->na_scratch);
+    W.bar = reinterpret_cast<uint16_t *>(base);
+    W.ext_b = reinterpret_cast<uint32_t *>(base + bar_bytes);
+    W.ksd = reinterpret_cast<uint16_t *>(base + bar_bytes + ext_bytes);
+    W.bar_stride = bar_stride;
+    W.gates = ngates;
+    // nothing in the scratch has to start at zero: every word a live gate reads is written earlier in the same call,
+    // and what the key switch computes from stale digits of gates past the end is discarded
+    return enqueue_level_on(c, W, false, d_type, d_in0, d_in1, d_out, ngates);
 }
 
 int she_eval_mux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,

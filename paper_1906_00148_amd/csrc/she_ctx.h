@@ -62,6 +62,8 @@ struct she_ctx {
     size_t timer_levels = 0;
     double last_ms[4] = {0, 0, 0, 0};
     she::LeveledPools lev;
+    void *na_scratch = nullptr;          // this device's copy of the static scratch buffer (never freed)
+    size_t na_bytes = 0;
     std::string err;
 };
 

@@ -78,6 +78,10 @@ hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters
 hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const uint32_t *d_dst_ids, size_t count,
                           uint32_t n, hipStream_t st);
 
+// Device address and size of the static scratch buffer on `device` (which must be the current device); looked up
+// once per device and kept.  The buffer belongs to the loaded code object: it is never freed.
+hipError_t noalloc_scratch(int device, void **ptr, size_t *bytes);
+
 // ---- host-side key material and samples (she_host.cpp) ----
 struct HostKeys {
     std::vector<uint8_t> lwe_key, ring_key;

@@ -10,6 +10,7 @@
 // construction itself is the cited TFHE gate bootstrapping.)
 #include "negacyclic_fft.h"
 #include "she_internal.h"
+#include <mutex>
 #pragma clang fp contract(fast)
 
 namespace she {
@@ -1025,6 +1026,39 @@ hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const ui
     if (!count) return hipSuccess;
     hipLaunchKernelGGL(k_copy_ct, dim3((unsigned)count), dim3(128), 0, st, cs, d_src_ids, d_dst_ids, n);
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Scratch of the entry point that allocates nothing (she_eval_gates_device_noalloc): the level's rounded
+// samples, extracted bodies and key-switch digits live in this file-scope array instead of allocated
+// buffers.  Every GPU that loads the library holds its own 16 MiB copy until the process ends.  In host code
+// the array's name is only a stand-in: the device address comes from hipGetSymbolAddress, once per device
+// with that device current, and only that pointer is handed to kernels.
+// ------------------------------------------------------------------------------------------
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+
+hipError_t noalloc_scratch(int device, void **ptr, size_t *bytes)
+{
+    constexpr int MAX_DEVICES = 64;
+    static void *address[MAX_DEVICES] = {};
+    static std::mutex guard;
+    if (device < 0 || device >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[device]) {
+        int current = -1;
+        hipError_t rc = hipGetDevice(&current);
+        if (rc != hipSuccess) return rc;
+        if (current != device) return hipErrorInvalidDevice;
+        void *p = nullptr;
+        rc = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (rc != hipSuccess) return rc;
+        if (!p) return hipErrorInvalidSymbol;
+        address[device] = p;
+    }
+    *ptr = address[device];
+    *bytes = NOALLOC_SCRATCH_BYTES;
+    return hipSuccess;
 }
 
 // ------------------------------------------------------------------------------------------
