@@ -32,15 +32,20 @@ FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop/FMA 
 # ISA: 6 forward rows x 323 + 518 (inverse transforms, rounding); beside them 443 LDS, 97 global-load and about 535
 # integer vector instructions
 FP64_INSTR_PER_CMUX = 2456
-# HBM-side bytes per blind-rotation launch from two rocprofv3 --pmc runs (FETCH_SIZE 948,610 KiB scaled by 2.00,
-# WRITE_SIZE 110,478 KiB scaled by 1.00; scales from a 256 MiB device copy in the same runs), see
-# profiles/k_blind_rotate_level4096_n630_N1024_counters.txt.  Algorithmic bytes are ~75 MB: the excess is the
-# key spectra streamed once per XCD L2 and per resident batch (8 x 2 x 61.9 MB), served by the Infinity Cache.
+# HBM-side bytes per blind-rotation launch.  NOT measured by this program: the figure comes from two separate
+# rocprofv3 --pmc runs of this same command (FETCH_SIZE 948,610 KiB scaled by 2.00, WRITE_SIZE 110,478 KiB scaled by
+# 1.00; scales from a 256 MiB device copy in the same runs) whose summary is the file named below.  Algorithmic bytes
+# are ~85 MB: the excess is the key spectra streamed once per XCD L2 and per resident batch (8 x 2 x 61.9 MB), served
+# by the Infinity Cache.
 MEASURED_TRAFFIC_BYTES = 2.06e9
+TRAFFIC_SOURCE = ("profiles/k_blind_rotate_level4096_n630_N1024_counters.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE "
+                  "passes over `bench.py --calibrate-copy`, scaled by a 256 MiB device copy; carried over, not measured "
+                  "in this run")
 
 
-def cpu_baseline(sample_gates: int):
-    """The oracle, as it stands, on this machine's host cores, on the first gates of the same workload."""
+def cpu_baseline(sample_gates: int, single_thread_gates: int = 8):
+    """The oracle, as it stands, on this machine's host cores, on the first gates of the same workload: once spread
+    over the host threads, once on a single thread (a smaller sample, so that both legs stay within ~30 s)."""
     import numpy as np
 
     import synth_inputs as S
@@ -49,17 +54,20 @@ def cpu_baseline(sample_gates: int):
     threads = max(1, min(os.cpu_count() or 1, 16))
     bits, codes = S.cfg2_real_level(GATES_PER_LEVEL)
     K = O.keygen(O.REAL, S.KEY_SEED)
-    g = sample_gates
-    fresh = O.encrypt_bits(K, bits[: 2 * g], S.data_seed(2))
-    pool = np.zeros((3 * g, K.params.n + 1), np.uint32)
-    pool[: 2 * g] = fresh
-    ids = np.arange(2 * g, dtype=np.uint32)
-    t0 = time.perf_counter()
-    O.eval_gates(K, pool, codes[:g], ids[0::2], ids[1::2], np.arange(2 * g, 3 * g, dtype=np.uint32), threads=threads)
-    dt = time.perf_counter() - t0
-    return {"value": g / dt, "unit": "gates/s", "cores": min(threads, g), "kind": "oracle",
-            "sample": f"first {g} gates of the 4096-gate level, schoolbook negacyclic products, "
-                      f"{min(threads, g)} OpenMP threads, {dt:.1f} s wall"}
+
+    def leg(g, thr):
+        fresh = O.encrypt_bits(K, bits[: 2 * g], S.data_seed(2))
+        pool = np.zeros((3 * g, K.params.n + 1), np.uint32)
+        pool[: 2 * g] = fresh
+        ids = np.arange(2 * g, dtype=np.uint32)
+        t0 = time.perf_counter()
+        O.eval_gates(K, pool, codes[:g], ids[0::2], ids[1::2], np.arange(2 * g, 3 * g, dtype=np.uint32), threads=thr)
+        dt = time.perf_counter() - t0
+        return {"value": g / dt, "unit": "gates/s", "cores": min(thr, g), "kind": "oracle",
+                "sample": f"first {g} gates of the 4096-gate level, schoolbook negacyclic products, "
+                          f"{min(thr, g)} OpenMP thread(s), {dt:.1f} s wall"}
+
+    return leg(sample_gates, threads), leg(single_thread_gates, 1)
 
 
 def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool = False, fused_pool: bool = False,
@@ -295,24 +303,38 @@ def main():
                                 "key_switch": tim["key_switch_ms"] / args.steps},
         "roofline": {"bound": "alu", "kernel": "k_blind_rotate", "achieved": achieved,
                      "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / FP64_VECTOR_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES},
+                     "traffic": MEASURED_TRAFFIC_BYTES, "traffic_source": TRAFFIC_SOURCE},
         "paper_context": {"value": 77, "unit": "gates/s", "note": "implied by the paper's projected fully-homomorphic "
                           "latency / gate count (about 13 ms per gate), Xeon E7-4850, different parameter set"},
     }
-    # what the FP64 pipes of this box issue at (2 wavefronts per SIMD, sustained): the published peak assumes one FMA per
-    # lane and cycle at 2.4 GHz (1.67 ns per wave64 instruction and SIMD)
+    # exactness of what was timed: the same level once more with the kernel recording the largest distance from an
+    # integer of everything it rounds (outside the timed region; the tracking kernel is slower)
+    ctx.set_round_tracking(True)
+    ctx.get_round_error(reset=True)
+    step()
+    torch.cuda.synchronize()
+    worst = ctx.get_round_error()
+    ctx.set_round_tracking(False)
+    ctx.last_timing()
+    assert 0.0 < worst < 0.2, f"FP64 products are not safely exact: largest distance from an integer {worst}"
+    out["max_distance_from_integer_before_rounding"] = worst
+    # DIAGNOSTICS, not rooflines: what the FP64 pipes of this box issue at (2 wavefronts per SIMD, sustained; the
+    # published peak assumes one FMA per lane and cycle at 2.4 GHz = 1.67 ns per wave64 instruction and SIMD), and a
+    # probe that issues plain additions with the kernel's own LDS and key-load pattern beside them.  The second ratio
+    # compares the kernel with something shaped like itself: it says where the time goes, not how far a roofline is.
     probe = {name: ctx.probe_fp64_rate(form) for form, name in ((0, "fma_scalar_operands"), (1, "fma_three_registers"),
                                                                (2, "add_two_registers"),
                                                                (3, "add_with_the_kernels_lds_and_key_loads"))}
-    out["roofline"]["measured_fp64_issue"] = probe
-    out["roofline"]["frac_of_measured_fma_rate"] = achieved / probe["fma_scalar_operands"]["tflops_as_fma"]
-    # the blind rotation's own FP64 instruction rate (2456 per CMux and wavefront, counted in its ISA) against the rate
-    # at which plain additions issue with the kernel's LDS and key-load instructions beside them
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     br_ns = br_ms * 1e6 / (G * 630 * FP64_INSTR_PER_CMUX / (4.0 * cus))
-    out["roofline"]["blind_rotate_ns_per_fp64_instruction_per_simd"] = br_ns
-    out["roofline"]["frac_of_measured_mixed_issue_rate"] = probe["add_with_the_kernels_lds_and_key_loads"][
-        "ns_per_instruction_per_simd"] / br_ns
+    out["diagnostics"] = {
+        "note": "issue-rate probes; not part of the roofline, whose fraction is against the published 78.6 TFLOP/s",
+        "measured_fp64_issue": probe,
+        "blind_rotate_over_measured_fma_rate": achieved / probe["fma_scalar_operands"]["tflops_as_fma"],
+        "blind_rotate_ns_per_fp64_instruction_per_simd": br_ns,
+        "probe_with_kernel_memory_pattern_over_blind_rotate": probe["add_with_the_kernels_lds_and_key_loads"][
+            "ns_per_instruction_per_simd"] / br_ns,
+    }
     ctx.close()
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.int32, device="cuda")
@@ -333,7 +355,7 @@ def main():
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_sample_gates)
+        out["cpu_baseline"], out["cpu_baseline_single_thread"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))
 
 

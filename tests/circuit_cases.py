@@ -72,3 +72,28 @@ def plain_circuit(kinds, ops, neg, outs, n_inputs, bits):
         else:
             val.append((a + b + c) & 1)
     return np.asarray([get(int(v), False) for v in outs], np.uint8)
+
+
+def netlist_to_she_arrays(pkg, nl, in_ids):
+    """An oracle netlist built WITHOUT folding, as the reference arrays of she_eval_circuit: entry g keeps its place,
+    input wire k becomes pool slot in_ids[k], wire n_inputs + 2 + h the result of entry h.  Two-input and three-input
+    codes are the same numbers on both sides; a native MUX entry (AND / ANDNY rotations) becomes SHE_CIRCUIT_MUX."""
+    from oracle import tfhe as O
+    assert not nl.fold
+    in_ids = np.asarray(in_ids, np.int64).ravel()
+    first_gate_wire = nl.n_inputs + 2
+
+    def refs(wires):
+        w = np.asarray(wires, np.int64)
+        out = np.where(w >= first_gate_wire, pkg.WIRE_GATE | (w - first_gate_wire), 0)
+        out = np.where(w == nl.ZERO, pkg.WIRE_ZERO, out)
+        out = np.where(w == nl.ONE, pkg.WIRE_ONE, out)
+        is_in = w < nl.n_inputs
+        out[is_in] = in_ids[w[is_in]]
+        return out.astype(np.uint32)
+
+    t = np.asarray(nl.gtype, np.int64)
+    plain_mux = O.MUX_BASE + 16 * O.GATES["AND"] + O.GATES["ANDNY"]
+    assert not (((t >= O.MUX_BASE) & (t < O.GATE3_BASE)) & (t != plain_mux)).any()
+    types = np.where(t == plain_mux, pkg.CIRCUIT_MUX, t).astype(np.uint8)
+    return types, refs(nl.in0), refs(nl.in1), refs(nl.in2), refs

@@ -1,0 +1,240 @@
+"""Ciphertext-level parity at the benchmark's real parameters (n=630, N=1024) on gates whose inputs are themselves
+bootstrapped outputs: the neuron, ReLU + pooling and conv-layer circuits run through she_eval_circuit, which keeps
+sampled entries and their operands in pool slots; the oracle then recomputes every sampled entry from the operand
+ciphertexts the GPU produced and each output word must match.  Operands of an entry are results of earlier entries,
+so an entry verified this way extends, step by step, the agreement from the fresh inputs (identical on both sides) to
+the circuit's outputs.  The operator calls (she_shift_acc, she_relu, she_maxpool) must then give the same words as
+the circuit call on the same netlist.  Integer work: bit-exact."""
+import numpy as np
+import pytest
+
+import synth_inputs as S
+from circuit_cases import netlist_to_she_arrays
+from oracle import circuits as OC
+from oracle import tfhe as O
+
+pytestmark = pytest.mark.gpu
+
+CAP = 40000
+OUT0 = 30000          # slots from here on receive sampled wires and outputs
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_1906_00148_amd as pkg
+    c = pkg.Context(pkg.REAL, S.KEY_SEED, CAP)
+    yield c
+    c.close()
+
+
+def sample_entries(nl, count, seed):
+    """`count` entries spread over the early, middle and last third of the depth levels (a seeded draw in each third),
+    always with the deepest entry, and with every kind of entry the netlist has (2-input, majority, parity, MUX)."""
+    lev = nl.levels()
+    rng = np.random.default_rng(seed)
+    depth = int(lev.max())
+    picks = {int(np.argmax(lev))}
+    t = np.asarray(nl.gtype)
+    for kind in (t < O.MUX_BASE, (t >= O.MUX_BASE) & (t < O.GATE3_BASE), (t >= O.MAJ3) & (t < O.XOR3), t >= O.XOR3):
+        idx = np.flatnonzero(kind & (lev > 1))
+        if idx.size:
+            picks.add(int(rng.choice(idx)))
+    thirds = [(0, depth // 3), (depth // 3, 2 * depth // 3), (2 * depth // 3, depth)]
+    for lo, hi in thirds:
+        idx = np.flatnonzero((lev > lo) & (lev <= hi))
+        for g in rng.choice(idx, size=min(idx.size, -(-count // 3)), replace=False):
+            picks.add(int(g))
+    return np.array(sorted(picks))[: max(count, len(picks))]
+
+
+def run_and_check(ctx, keys, nl, in_ids, out_wires, sampled, threads=16):
+    """Runs the netlist through she_eval_circuit keeping the sampled entries, their operands and out_wires; checks
+    every sampled entry against the oracle on the GPU's operand ciphertexts; returns the ciphertexts of out_wires."""
+    import paper_1906_00148_amd as pkg
+    types, r0, r1, r2, refs = netlist_to_she_arrays(pkg, nl, in_ids)
+    t = np.asarray(nl.gtype)
+    a, b, c, o = (np.asarray(v, np.int64) for v in (nl.in0, nl.in1, nl.in2, nl.out))
+    # wires to keep: results of sampled entries and their operands that are results of earlier entries
+    keep = set(int(w) for w in np.asarray(out_wires, np.int64).ravel() if w >= nl.n_inputs + 2)
+    for g in sampled:
+        keep.add(int(o[g]))
+        for w in (a[g], b[g]) + ((c[g],) if t[g] >= O.MUX_BASE else ()):
+            if w >= nl.n_inputs + 2:
+                keep.add(int(w))
+    keep = np.array(sorted(keep))
+    slot_of = {int(w): OUT0 + k for k, w in enumerate(keep)}
+    assert OUT0 + keep.size <= CAP and np.asarray(in_ids).max() < OUT0
+    n_entries = ctx.eval_circuit(types, r0, r1, r2, refs(keep), np.array([slot_of[int(w)] for w in keep], np.uint32))
+    assert n_entries == len(nl.gtype)
+    n = keys.params.n
+
+    def ct_of(w):
+        w = int(w)
+        if w == nl.ZERO or w == nl.ONE:
+            ct = np.zeros(n + 1, np.uint32)
+            ct[n] = (1 << 29) if w == nl.ONE else (-(1 << 29)) & 0xFFFFFFFF
+            return ct
+        return ctx.read_ct(int(np.asarray(in_ids).ravel()[w]) if w < nl.n_inputs else slot_of[w])
+
+    # one oracle pool: three operand slots and one result slot per sampled entry, all entries independent
+    pool = np.zeros((4 * len(sampled), n + 1), np.uint32)
+    gt, i0, i1, i2, io = [], [], [], [], []
+    fed_by_gates = 0
+    for k, g in enumerate(sampled):
+        pool[4 * k] = ct_of(a[g]); pool[4 * k + 1] = ct_of(b[g])
+        if t[g] >= O.MUX_BASE:
+            pool[4 * k + 2] = ct_of(c[g])
+        fed_by_gates += int(a[g] >= nl.n_inputs + 2 or b[g] >= nl.n_inputs + 2)
+        gt.append(int(t[g])); i0.append(4 * k); i1.append(4 * k + 1); i2.append(4 * k + 2); io.append(4 * k + 3)
+    O.eval_netlist(keys, pool, gt, i0, i1, i2, io, threads)
+    for k, g in enumerate(sampled):
+        got = ctx.read_ct(slot_of[int(o[g])])
+        assert np.array_equal(got, pool[4 * k + 3]), f"entry {g} (type {t[g]}, level {nl.levels()[g]}) differs from the oracle"
+    print(f"  {len(sampled)} sampled entries bit-exact ({fed_by_gates} fed by earlier bootstraps; types {sorted(set(gt))}; "
+          f"levels {sorted(set(int(v) for v in nl.levels()[sampled]))[:4]}..{int(nl.levels()[sampled].max())})", flush=True)
+    assert fed_by_gates >= len(sampled) // 2
+    return np.stack([ct_of(w) for w in np.asarray(out_wires, np.int64).ravel()])
+
+
+def encrypt_values(ctx, values, bits, seed, first_id=0):
+    b = OC.to_bits(np.asarray(values), bits)
+    ids = np.arange(first_id, first_id + b.size, dtype=np.uint32).reshape(b.shape)
+    ctx.encrypt_bits(b.ravel(), seed, ids.ravel())
+    return ids
+
+
+def set_modes(ctx, cells):
+    import paper_1906_00148_amd as pkg
+    ctx.set_option(pkg.OPT_GATE3_CELLS, int(cells))
+    ctx.set_option(pkg.OPT_NATIVE_MUX, int(cells))
+
+
+@pytest.mark.parametrize("cells", [False, True])
+def test_cfg3_neuron_sampled_entries_word_for_word(ctx, real_keys, cells):
+    # the full 576-term neuron: 24,144 gates in 48 levels (10,372 in 25 with three-input cells)
+    x, sign, exp = S.cfg3_neuron()
+    ids = encrypt_values(ctx, x, 8, S.data_seed(3))
+    nl, outs = OC.build_shift_acc(1, 576, 8, sign, exp, 16, cells3=cells)
+    set_modes(ctx, cells)
+    try:
+        print(f"\ncfg3 cells={cells}: {len(nl.gtype)} entries, {int(nl.levels().max())} levels", flush=True)
+        sampled = sample_entries(nl, 36, 33)
+        got = run_and_check(ctx, real_keys, nl, ids.ravel(), outs[0], sampled)
+        want = OC.plain_shift_acc(x, sign, exp, 16)
+        assert np.array_equal(OC.from_bits(O.decrypt_bits(real_keys, got), True).reshape(1), want)
+        # the operator call builds its own netlist: the same gates on the same inputs give the same words
+        out = np.arange(CAP - 16, CAP, dtype=np.uint32).reshape(1, 16)
+        assert ctx.shift_acc(ids, sign, exp, 16, out) == len(nl.gtype)
+        assert np.array_equal(ctx.read_cts(out.ravel()), got)
+    finally:
+        set_modes(ctx, False)
+
+
+@pytest.mark.parametrize("cells", [False, True])
+def test_cfg4_relu_then_pool_sampled_entries_word_for_word(ctx, real_keys, cells):
+    # the shape of config 4 on a reduced 8x8x4 map of 16-bit values; the pooling reads bootstrapped ReLU outputs
+    fm = S.cfg4_feature_map(8, 8, 4)
+    fm[0, 0, 0], fm[0, 1, 0], fm[1, 0, 0], fm[1, 1, 0] = -32768, 32767, 0, -1
+    ids = encrypt_values(ctx, fm, 16, S.data_seed(4))
+    relu_ids = ids + 8192
+    set_modes(ctx, cells)
+    try:
+        assert ctx.relu(ids.reshape(-1, 16), relu_ids.reshape(-1, 16)) == 8 * 8 * 4 * 15
+        nl_r, outs_r = OC.build_relu(8 * 8 * 4, 16)
+        sampled = S.subset(len(nl_r.gtype), 12, 44)
+        # ReLU is one level on fresh inputs: every sampled gate from the fresh ciphertexts
+        fresh = O.encrypt_bits(real_keys, OC.to_bits(fm, 16).ravel(), S.data_seed(4))
+        t, a, b, o = (np.asarray(v) for v in (nl_r.gtype, nl_r.in0, nl_r.in1, nl_r.out))
+        pool = np.zeros((nl_r.n_wires, real_keys.params.n + 1), np.uint32)
+        pool[: fresh.shape[0]] = fresh
+        O.eval_netlist(real_keys, pool, t[sampled], a[sampled], b[sampled], 0 * a[sampled], o[sampled], 12)
+        flat_out = np.asarray(outs_r, np.int64).ravel()
+        for g in sampled:
+            pos = int(np.flatnonzero(flat_out == o[g])[0])
+            assert np.array_equal(ctx.read_ct(int(relu_ids.ravel()[pos])), pool[o[g]])
+        nl, outs = OC.build_maxpool(8, 8, 4, 16, native_mux=cells, cells3=cells)
+        print(f"\ncfg4 shape cells={cells}: pooling {len(nl.gtype)} entries, {int(nl.levels().max())} levels", flush=True)
+        got = run_and_check(ctx, real_keys, nl, relu_ids.ravel(), np.asarray(outs).ravel(), sample_entries(nl, 36, 45))
+        want = OC.plain_maxpool2x2(OC.plain_relu(fm))
+        assert np.array_equal(OC.from_bits(O.decrypt_bits(real_keys, got).reshape(4, 4, 4, 16), True), want)
+        pool_ids = (CAP - 4 * 4 * 4 * 16 + np.arange(4 * 4 * 4 * 16, dtype=np.uint32)).reshape(4, 4, 4, 16)
+        assert ctx.maxpool(relu_ids, pool_ids) == len(nl.gtype)
+        assert np.array_equal(ctx.read_cts(pool_ids.ravel()), got)
+    finally:
+        set_modes(ctx, False)
+
+
+@pytest.mark.parametrize("cells", [False, True])
+def test_cfg5_conv_layer_sampled_entries_word_for_word(ctx, real_keys, cells):
+    # the shape of config 5 on a reduced 8x8 image: 3x3 conv with 8 channels (288 neurons), ReLU, 2x2 pooling
+    img, sign, exp = S.cfg5_conv_layer(8, 8)
+    oc, k = sign.shape[0], sign.shape[1]
+    oh = ow = 8 - k + 1
+    in_ids = encrypt_values(ctx, img, 8, S.data_seed(5))                        # [8][8][8 bits]
+    x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)
+    for dy in range(k):
+        for dx in range(k):
+            x_ids[:, :, :, dy * k + dx, :] = in_ids[dy:dy + oh, dx:dx + ow, None, :]
+    units = oh * ow * oc
+    w_sign = np.broadcast_to(sign.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(units, k * k)
+    w_exp = np.broadcast_to(exp.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(units, k * k)
+    conv_ids = (1024 + np.arange(units * 16, dtype=np.uint32)).reshape(oh, ow, oc, 16)
+    relu_ids = conv_ids + units * 16
+    set_modes(ctx, cells)
+    try:
+        nl, outs = OC.build_shift_acc(units, k * k, 8, w_sign, w_exp, 16, cells3=cells)
+        print(f"\ncfg5 shape cells={cells}: conv {len(nl.gtype)} entries, {int(nl.levels().max())} levels", flush=True)
+        # the netlist's input wire (u, t, bit) is pool slot x_ids[u][t][bit]: pixels are shared between neurons
+        got = run_and_check(ctx, real_keys, nl, x_ids.reshape(-1), np.asarray(outs).ravel(), sample_entries(nl, 36, 55))
+        patches = np.zeros((oh, ow, k * k), np.int64)
+        for dy in range(k):
+            for dx in range(k):
+                patches[:, :, dy * k + dx] = img[dy:dy + oh, dx:dx + ow]
+        conv = np.stack([OC.plain_shift_acc(patches.reshape(-1, k * k), np.tile(sign[ch].reshape(1, -1), (oh * ow, 1)),
+                                            np.tile(exp[ch].reshape(1, -1), (oh * ow, 1)), 16).reshape(oh, ow)
+                         for ch in range(oc)], axis=-1)
+        assert np.array_equal(OC.from_bits(O.decrypt_bits(real_keys, got).reshape(oh, ow, oc, 16), True), conv)
+        assert ctx.shift_acc(x_ids.reshape(units, k * k, 8), w_sign, w_exp, 16, conv_ids.reshape(units, 16)) == len(nl.gtype)
+        assert np.array_equal(ctx.read_cts(conv_ids.ravel()[:: 7]), got[:: 7])
+        # ReLU and pooling on the convolution's bootstrapped outputs, as one pooled circuit each
+        ctx.relu(conv_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+        nl_p, outs_p = OC.build_maxpool(oh, ow, oc, 16, native_mux=cells, cells3=cells)
+        got_p = run_and_check(ctx, real_keys, nl_p, relu_ids.ravel(), np.asarray(outs_p).ravel(), sample_entries(nl_p, 33, 56))
+        want = OC.plain_maxpool2x2(OC.plain_relu(conv))
+        assert np.array_equal(OC.from_bits(O.decrypt_bits(real_keys, got_p).reshape(oh // 2, ow // 2, oc, 16), True), want)
+    finally:
+        set_modes(ctx, False)
+
+
+def test_xor_chain_of_depth_40_word_for_word(ctx, real_keys):
+    # x_{k+1} = XOR(x_k, y_k): the worst case for the noise (the combination doubles both operands); every step's
+    # output is recomputed by the oracle from the GPU's own x_k, so the chain agrees link by link
+    depth = 40
+    rng = np.random.default_rng(S.data_seed(8))
+    bits = rng.integers(0, 2, depth + 1).astype(np.uint8)
+    ids = np.arange(depth + 1, dtype=np.uint32)
+    ctx.encrypt_bits(bits, S.data_seed(8), ids)
+    xor = np.array([O.GATES["XOR"]], np.uint8)
+    chain = OUT0 + np.arange(depth + 1, dtype=np.uint32)
+    ctx.eval_gates(np.array([O.GATES["OR"]], np.uint8), ids[:1], ids[:1], chain[:1])       # x_0 = y_0 or y_0, bootstrapped
+    for k in range(depth):
+        ctx.eval_gates(xor, chain[k:k + 1], ids[k + 1:k + 2], chain[k + 1:k + 2])
+    gpu = ctx.read_cts(chain)
+    fresh = O.encrypt_bits(real_keys, bits, S.data_seed(8))
+    n = real_keys.params.n
+    pool = np.zeros((3 * (depth + 1), n + 1), np.uint32)
+    pool[0] = pool[1] = fresh[0]
+    gt, i0, i1, io = [O.GATES["OR"]], [0], [1], [2]
+    for k in range(depth):
+        pool[3 * (k + 1)] = gpu[k]; pool[3 * (k + 1) + 1] = fresh[k + 1]
+        gt.append(O.GATES["XOR"]); i0.append(3 * (k + 1)); i1.append(3 * (k + 1) + 1); io.append(3 * (k + 1) + 2)
+    O.eval_gates(real_keys, pool, gt, i0, i1, io, threads=16)
+    for k in range(depth + 1):
+        assert np.array_equal(gpu[k], pool[3 * k + 2]), f"link {k} of the chain differs from the oracle"
+    want = np.bitwise_xor.accumulate(bits)
+    assert np.array_equal(ctx.decrypt(chain), want)
+    # noise stays at the single-gate level along the chain (bootstrapping resets it): phases within 1/16 of +-1/8
+    for k in range(depth + 1):
+        ph = O.lwe_phase(real_keys.lwe_key, gpu[k])
+        err = ((ph - ((1 << 29) if want[k] else -(1 << 29)) + (1 << 31)) % (1 << 32)) - (1 << 31)
+        assert abs(err) < (1 << 28)
