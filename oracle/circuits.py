@@ -53,11 +53,17 @@ def is_mux(t: int) -> bool:
 
 
 # ------------------------------------------------------------------ plain meaning
-def plain_shift_acc(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int) -> np.ndarray:
-    """x[units][terms] unsigned; result sum_i sign_i * (x_i >> |e_i|), wrapped to acc_bits, as signed ints."""
+def plain_shift_acc(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int, bias=None) -> np.ndarray:
+    """x[units][terms] unsigned; result bias + sum_i sign_i * (x_i >> |e_i|), wrapped to acc_bits, as signed ints.
+    bias[units]: the plaintext constant of each unit (Section 5, Table 3: the layer sequences C-B-A-P put a batch
+    normalisation between the linear layer and the activation; with plaintext weights its scale folds into the
+    weights and its shift is a per-unit constant added to the sum), None = 0."""
     x = np.asarray(x, np.int64)
     s = (x >> np.abs(np.asarray(w_exp, np.int64))) * np.asarray(w_sign, np.int64)
-    tot = s.sum(axis=-1) & ((1 << acc_bits) - 1)
+    tot = s.sum(axis=-1)
+    if bias is not None:
+        tot = tot + np.asarray(bias, np.int64).reshape(tot.shape)
+    tot = tot & ((1 << acc_bits) - 1)
     return np.where(tot >= (1 << (acc_bits - 1)), tot - (1 << acc_bits), tot)
 
 
@@ -73,9 +79,9 @@ def plain_maxpool2x2(x: np.ndarray) -> np.ndarray:
     return np.maximum(np.maximum(x[0::2, 0::2], x[0::2, 1::2]), np.maximum(x[1::2, 0::2], x[1::2, 1::2]))
 
 
-def plain_conv(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int) -> np.ndarray:
+def plain_conv(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: int, bias=None) -> np.ndarray:
     """Valid stride-1 convolution of x[H][W][C] (unsigned) with shift weights [OC][k][k][C]:
-    out[y][x][o] = sum sign * (pixel >> |exp|), wrapped to acc_bits (signed)."""
+    out[y][x][o] = bias[o] + sum sign * (pixel >> |exp|), wrapped to acc_bits (signed)."""
     x = np.asarray(x, np.int64)
     OC, k = w_sign.shape[0], w_sign.shape[1]
     oh, ow = x.shape[0] - k + 1, x.shape[1] - k + 1
@@ -84,15 +90,17 @@ def plain_conv(x: np.ndarray, w_sign: np.ndarray, w_exp: np.ndarray, acc_bits: i
         for xx in range(ow):
             patch = x[yy:yy + k, xx:xx + k, :]
             for o in range(OC):
-                out[yy, xx, o] = plain_shift_acc(patch.reshape(1, -1), w_sign[o].reshape(1, -1), w_exp[o].reshape(1, -1), acc_bits)[0]
+                out[yy, xx, o] = plain_shift_acc(patch.reshape(1, -1), w_sign[o].reshape(1, -1), w_exp[o].reshape(1, -1), acc_bits,
+                                                 None if bias is None else [bias[o]])[0]
     return out
 
 
-def plain_network(img, w1, w2, w3, acc_bits: int = 16) -> np.ndarray:
-    """conv - ReLU - pool - conv - ReLU - pool - dense with shift weights; the class scores (signed)."""
-    a = plain_maxpool2x2(plain_relu(plain_conv(np.asarray(img)[..., None], w1[0], w1[1], acc_bits)))
-    b = plain_maxpool2x2(plain_relu(plain_conv(a, w2[0], w2[1], acc_bits)))
-    return plain_shift_acc(np.broadcast_to(b.reshape(1, -1), (w3[0].shape[0], b.size)), w3[0], w3[1], acc_bits)
+def plain_network(img, w1, w2, w3, acc_bits: int = 16, biases=(None, None, None)) -> np.ndarray:
+    """conv - ReLU - pool - conv - ReLU - pool - dense with shift weights (and per-channel constants `biases`, one
+    array per linear layer or None); the class scores (signed)."""
+    a = plain_maxpool2x2(plain_relu(plain_conv(np.asarray(img)[..., None], w1[0], w1[1], acc_bits, biases[0])))
+    b = plain_maxpool2x2(plain_relu(plain_conv(a, w2[0], w2[1], acc_bits, biases[1])))
+    return plain_shift_acc(np.broadcast_to(b.reshape(1, -1), (w3[0].shape[0], b.size)), w3[0], w3[1], acc_bits, biases[2])
 
 
 def to_bits(v: np.ndarray, bits: int) -> np.ndarray:
@@ -400,7 +408,7 @@ def shifted_term(nl: Netlist, x_bits: list, exp: int) -> list:
     return list(x_bits[s:]) + [nl.ZERO] * min(s, w)
 
 
-def column_accumulate(nl: Netlist, terms: list, acc_bits: int) -> list:
+def column_accumulate(nl: Netlist, terms: list, acc_bits: int, constant: int = 0) -> list:
     """Sum of signed terms mod 2^acc_bits by column compression (Section 3.3 asks for an accumulator whose adders are
     only as wide as the bits they receive; here every bit is placed in the column of its weight and columns are
     compressed with full-adder cells).  terms: (wires of an unsigned value, LSB first, no padding; sign).  A negative
@@ -409,10 +417,11 @@ def column_accumulate(nl: Netlist, terms: list, acc_bits: int) -> list:
     column, left to right, each run of three wires becomes a parity wire in the same column and a majority wire in the
     next (dropped beyond the top column), leftovers stay; a stage's column holds the carries from the column below
     first, then its own parities, then its leftovers; wires that folding proves ZERO are dropped.  When no column holds
-    more than two wires, one ripple adder of cells finishes.  Needs fold (complements, constants) and cells3."""
+    more than two wires, one ripple adder of cells finishes.  Needs fold (complements, constants) and cells3.
+    `constant` (the unit's plaintext bias) joins the negative terms' constants before they enter as ONE wires."""
     assert nl.fold and nl.cells3
     cols = [[] for _ in range(acc_bits)]
-    const = 0
+    const = int(constant)
     for bits, sign in terms:
         for b, wire in enumerate(bits[:acc_bits]):
             cols[b].append(wire if sign > 0 else wire ^ NEG)
@@ -459,12 +468,22 @@ def column_accumulate(nl: Netlist, terms: list, acc_bits: int) -> list:
     return out
 
 
+def constant_wires(nl: Netlist, value: int, bits: int) -> list:
+    """two's complement of a plaintext integer as trivial wires (ZERO / ONE), LSB first: no gate"""
+    v = int(value) % (1 << bits)
+    return [nl.ONE if (v >> i) & 1 else nl.ZERO for i in range(bits)]
+
+
 def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                    cells3: bool = False, columns: bool = False):
+                    cells3: bool = False, columns: bool = False, bias=None):
     """Inputs are wires [units][terms][in_bits].  Returns (netlist, out_wires[units][acc_bits]).  columns: the sum
-    by column compression (column_accumulate) instead of the adder trees and the subtraction."""
+    by column compression (column_accumulate) instead of the adder trees and the subtraction.  bias[units]: plaintext
+    constants.  With the adder trees a non-zero bias is one more acc_bits-wide addition of trivial wires to the
+    positive tree's sum, before the subtraction (a zero bias leaves the netlist as it was); with column compression
+    it joins the constants of the negative terms in plain arithmetic and costs no adder."""
     w_sign = np.asarray(w_sign).reshape(units, terms)
     w_exp = np.asarray(w_exp).reshape(units, terms)
+    bias = np.zeros(units, np.int64) if bias is None else np.asarray(bias, np.int64).reshape(units)
     nl = Netlist(units * terms * in_bits, fold, cells3=cells3)
     outs = []
     if columns:
@@ -474,7 +493,7 @@ def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bit
                 base = (u * terms + t) * in_bits
                 drop = abs(int(w_exp[u, t]))
                 vecs.append((list(range(base + drop, base + in_bits)), int(w_sign[u, t])))
-            outs.append(column_accumulate(nl, vecs, acc_bits))
+            outs.append(column_accumulate(nl, vecs, acc_bits, int(bias[u])))
         return nl, outs
     for u in range(units):
         pos, neg = [], []
@@ -483,6 +502,8 @@ def build_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bit
             term = shifted_term(nl, list(range(base, base + in_bits)), w_exp[u, t])
             (pos if w_sign[u, t] > 0 else neg).append(term)
         P = adder_tree(nl, pos, in_bits, acc_bits)
+        if int(bias[u]) % (1 << acc_bits):
+            P = add_unsigned(nl, P, constant_wires(nl, int(bias[u]), acc_bits), acc_bits)
         if neg:
             Q = adder_tree(nl, neg, in_bits, acc_bits)
             outs.append(sub_wrapped(nl, P, Q))

@@ -375,3 +375,72 @@ def test_column_accumulator_sums_like_plain_arithmetic_and_plans_like_the_librar
     # closed forms of the gate counts for the benchmark shapes
     x, sign, exp = S.cfg3_neuron()
     assert pkg.plan_shift_acc(1, 576, 8, sign, exp, 16, fold=True, cells3=True, columns=True) == (5398, 23)
+
+
+# ------------------------------------------------------------------ per-unit constant (folded batch-norm shift / bias)
+def _bias_cases():
+    """(fold, cells3, columns) modes in which the accumulator netlists exist"""
+    return [(False, False, False), (True, False, False), (False, True, False), (True, True, False), (True, True, True)]
+
+
+def test_plain_shift_acc_with_bias_by_hand():
+    # 200>>1 - 7 + 255>>7 = 94; bias 10 -> 104; bias -100 -> -6; wrap: 94 + 32700 = 32794 -> -32742 at 16 bits
+    x, s, e = [[200, 7, 255]], [[1, -1, 1]], [[-1, 0, -7]]
+    assert C.plain_shift_acc(x, s, e, 16, [10]).tolist() == [104]
+    assert C.plain_shift_acc(x, s, e, 16, [-100]).tolist() == [-6]
+    assert C.plain_shift_acc(x, s, e, 16, [32700]).tolist() == [32794 - 65536]
+    assert C.plain_shift_acc(x, s, e, 16, None).tolist() == C.plain_shift_acc(x, s, e, 16, [0]).tolist() == [94]
+    # a bias per unit
+    assert C.plain_shift_acc([[1, 2], [3, 4]], [[1, 1], [1, -1]], [[0, 0], [0, 0]], 8, [5, -5]).tolist() == [8, -6]
+
+
+@pytest.mark.parametrize("fold,cells3,columns", _bias_cases())
+def test_shift_acc_netlists_with_bias_equal_the_definition(fold, cells3, columns):
+    """The accumulator netlists with a plaintext constant per unit, evaluated on plaintext bits, against
+    bias + sum_i sign_i (x_i >> |e_i|) mod 2^acc written out in Python integers: one small shape over every input,
+    every sign pattern and every bias residue; random shapes with positive, negative and out-of-range biases."""
+    rng = np.random.default_rng(77)
+
+    def check(units, terms, in_bits, acc, sign, exp, bias, inputs):
+        nl, outs = C.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold, cells3=cells3, columns=columns, bias=bias)
+        for x in inputs:
+            val = nl.run_plain(C.to_bits(np.asarray(x).ravel(), in_bits).ravel())
+            got = [int(C.from_bits(C.Netlist.read_plain(val, outs[u])[None, :], False)[0]) for u in range(units)]
+            want = [(int(bias[u]) + sum(int(s) * (int(v) >> int(-e)) for s, v, e in zip(sign[u], x[u], exp[u]))) % (1 << acc)
+                    for u in range(units)]
+            assert got == want, (units, terms, in_bits, acc, list(bias))
+        return nl
+
+    for signs in itertools.product([-1, 1], repeat=2):
+        xs = [np.array([v]) for v in itertools.product(range(4), repeat=2)]
+        for b in range(-8, 9):                               # every residue mod 2^4, from both sides of zero
+            check(1, 2, 2, 4, np.array([signs]), np.array([[0, -1]]), [b], xs)
+    for _ in range(60):
+        units, terms, in_bits = int(rng.integers(1, 4)), int(rng.integers(0, 12)), int(rng.integers(1, 7))
+        acc = int(rng.integers(in_bits, in_bits + 7))
+        sign = rng.choice([-1, 1], (units, terms))
+        exp = -rng.integers(0, in_bits, (units, terms))
+        bias = rng.integers(-(1 << (acc + 1)), 1 << (acc + 1), units)     # beyond the accumulator's range too: it wraps
+        check(units, terms, in_bits, acc, sign, exp, bias, [rng.integers(0, 1 << in_bits, (units, terms)) for _ in range(3)])
+    # a zero bias (and one that is a multiple of 2^acc) leaves the netlist exactly as it was without the argument
+    sign, exp = rng.choice([-1, 1], (2, 9)), -rng.integers(0, 8, (2, 9))
+    plain, _ = C.build_shift_acc(2, 9, 8, sign, exp, 16, fold=fold, cells3=cells3, columns=columns)
+    for zero in ([0, 0], [65536, -65536]):
+        same, _ = C.build_shift_acc(2, 9, 8, sign, exp, 16, fold=fold, cells3=cells3, columns=columns, bias=zero)
+        assert (same.gtype, same.in0, same.in1, same.in2) == (plain.gtype, plain.in0, plain.in1, plain.in2)
+
+
+def test_bias_costs_one_adder_in_the_trees_and_none_in_the_columns():
+    sign, exp = np.ones((1, 4), np.int64), np.zeros((1, 4), np.int64)
+    base, _ = C.build_shift_acc(1, 4, 8, sign, exp, 16)
+    with_b, _ = C.build_shift_acc(1, 4, 8, sign, exp, 16, bias=[1000])
+    assert len(with_b.gtype) - len(base.gtype) == 2 + 14 * 5 + 2 == 74   # a capped 16-bit adder: no carry out of the top bit
+    # with column compression the constant only adds wires to the columns: at most a few cells more
+    cols, _ = C.build_shift_acc(1, 4, 8, sign, exp, 16, fold=True, cells3=True, columns=True)
+    cols_b, _ = C.build_shift_acc(1, 4, 8, sign, exp, 16, fold=True, cells3=True, columns=True, bias=[1000])
+    assert len(cols_b.gtype) - len(cols.gtype) <= 16
+    # plain network with biases: a bias of 2^15 - 1 on the first conv saturates nothing (wraps mod 2^16 as defined)
+    img = np.arange(25).reshape(5, 5) * 10
+    w = (np.ones((2, 3, 3, 1), np.int64), np.zeros((2, 3, 3, 1), np.int64))
+    out = C.plain_conv(img[..., None], w[0], w[1], 16, bias=[7, -7])
+    assert out[0, 0, 0] == img[:3, :3].sum() + 7 and out[0, 0, 1] == img[:3, :3].sum() - 7
