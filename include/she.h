@@ -45,8 +45,12 @@ typedef struct she_ctx she_ctx; /* opaque: keys (secret ones too), device buffer
 /* TFHE parameter set (Section 4, "TFHE setting", names the three sample levels; the
  * gate-bootstrapping values used by the benchmarks are n=630, N=1024, k=1, bg_bit=7,
  * l=3, ks_t=8, ks_basebit=2, lwe_std=2^-15, bk_std=2^-25).  Supported: k = 1;
- * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8 and 2*l*N*Bg^2 <= 2^32 (so that the
- * FP64 polynomial products round to the exact integers); ks_t*ks_basebit <= 16 with ks_basebit <= 4. */
+ * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8, 2*l*N*Bg^2 <= 2^32 and l*N*Bg <= 2^20; ks_t*ks_basebit
+ * <= 16 with ks_basebit <= 4.  The two gadget bounds belong to the FP64 polynomial products: the second keeps every sum
+ * of products below 2^51 whatever the digits and key words are, which the rounding step needs; under the first the
+ * transforms' rounding errors stay far below 1/2 for digits and key words as they occur (measured, largest distance
+ * from an integer 0.012 at the benchmark's parameters, 0.07 on the bound; she_set_round_tracking records it), so the
+ * rounded results are the exact integers with overwhelming probability rather than by proof. */
 typedef struct {
     uint32_t n;          /* TLWE dimension */
     uint32_t N;          /* ring degree of TRLWE / TRGSW samples */
@@ -130,6 +134,19 @@ int she_eval_gates3(she_ctx *ctx, const uint8_t *type, const uint32_t *in0, cons
 int she_shift_acc(she_ctx *ctx, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
                   const int8_t *w_sign, const int8_t *w_exp, uint32_t acc_bits, const uint32_t *out_ids,
                   uint64_t *gates_out);
+
+/* Section 5 / Table 3 (the layer sequences C-B-A-P: a batch normalisation sits between the linear layer and the
+ * activation; with plaintext weights its scale folds into the weights and its shift is a constant per unit).
+ * she_shift_acc with a plaintext constant per unit:
+ *   out = bias[u] + sum_t w_sign[t] * (x_t >> -w_exp[t])   modulo 2^acc_bits,
+ * bias [units] (NULL = all zero; any int32 value, it wraps like the sum).  The constant enters as noiseless trivial
+ * ciphertexts: with the adder trees a constant that is not 0 modulo 2^acc_bits costs one more acc_bits-wide adder
+ * on the positive tree's sum (most of its gates fold away under SHE_OPT_FOLD_CONSTANTS); under
+ * SHE_OPT_COLUMN_ADDER it joins the negative terms' constants in plain arithmetic and costs no adder.
+ * Everything else as she_shift_acc, which is this call with bias = NULL. */
+int she_shift_acc_bias(she_ctx *ctx, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
+                       const int8_t *w_sign, const int8_t *w_exp, const int32_t *bias, uint32_t acc_bits,
+                       const uint32_t *out_ids, uint64_t *gates_out);
 
 /* Section 3.1 (ReLU(x) = max(x, 0) from Boolean gates).  x_ids [count][bits] two's
  * complement, out_ids [count][bits]; every lower bit is masked by the sign bit, the
@@ -222,6 +239,15 @@ int she_eval_mux(she_ctx *ctx, const uint32_t *sel, const uint32_t *in1, const u
  * MUX entry).  Any output pointer may be NULL.  Same argument checks as the operators. */
 int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
                        uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
+int she_plan_shift_acc_bias(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                            const int32_t *bias, uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels,
+                            uint64_t *rotations);
+/* Section 3.3 (the accumulator's adders are sized by the bits they can receive; the weights and constants are
+ * plaintext, so the server knows the range).  *bits_out = the smallest two's-complement width that holds
+ * bias[u] + sum_t w_sign[t] * (x_t >> -w_exp[t]) for every unit u and all unsigned in_bits-bit inputs, at least
+ * in_bits; a layer run at this acc_bits gives the same integers as at any larger one.  bias may be NULL.  Host only. */
+int she_plan_accumulator_bits(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                              const int32_t *bias, uint32_t *bits_out);
 int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations);
 int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
                      uint64_t *rotations);
@@ -322,15 +348,6 @@ int she_get_round_error(she_ctx *ctx, double *max_abs_frac, int reset);
  * combination, ms[1] blind rotation + extraction, ms[2] key switch, ms[3] levels launched. */
 int she_set_timing(she_ctx *ctx, int on);
 int she_last_timing(she_ctx *ctx, double ms[4]);
-
-/* Issue rate of one FP64 vector instruction form on this device, measured with 2 wavefronts per SIMD like the
- * blind rotation (form 0: fma with scalar multiplier and addend, 1: fma with three vector-register operands, 2: add
- * of two vector registers, 3: the additions of form 2 with the blind rotation's memory instructions beside them:
- * per 64 additions 6 LDS reads, 3 LDS writes and 2 global loads of 16 bytes per lane, the loads streaming the
- * context's spectral bootstrapping key).  ns_per_instruction is per FP64 instruction and SIMD; tflops_as_fma
- * prices every FP64 instruction as an FMA over the whole chip, the figure to hold against the published FP64
- * vector peak.  Either pointer may be NULL. */
-int she_probe_fp64_rate(she_ctx *ctx, int form, double *ns_per_instruction, double *tflops_as_fma);
 
 /* Text of the last error of this context ("" if none).  ctx may be NULL: then the text
  * of the last failed she_keygen of the calling thread. */

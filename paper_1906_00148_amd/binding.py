@@ -45,8 +45,8 @@ _lib = None
 
 
 def lib_path() -> str:
-    """Path of the built library; SHE_HIP_LIB overrides it (to compare builds of the kernels)."""
-    return os.environ.get("SHE_HIP_LIB") or os.path.join(_HERE, "libshe_hip.so")
+    """Path of the built library (next to this file)."""
+    return os.path.join(_HERE, "libshe_hip.so")
 
 
 def load_library() -> C.CDLL:
@@ -63,7 +63,7 @@ def load_library() -> C.CDLL:
     # process holds one runtime only (two runtimes do not share the device).
     import torch  # noqa: F401
     L = C.CDLL(path)
-    u8p, u32p, i8p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint32), C.POINTER(C.c_int8)
+    u8p, u32p, i8p, i32p = C.POINTER(C.c_uint8), C.POINTER(C.c_uint32), C.POINTER(C.c_int8), C.POINTER(C.c_int32)
     ctx, u64p = C.c_void_p, C.POINTER(C.c_uint64)
     sigs = {
         "she_keygen": (C.c_int, [C.POINTER(_CParams), C.c_uint64, C.c_uint32, C.POINTER(C.c_void_p)]),
@@ -72,6 +72,10 @@ def load_library() -> C.CDLL:
         "she_decrypt": (C.c_int, [ctx, u32p, C.c_size_t, u8p]),
         "she_eval_gates": (C.c_int, [ctx, u8p, u32p, u32p, u32p, C.c_size_t]),
         "she_shift_acc": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, u32p, u64p]),
+        "she_shift_acc_bias": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, i32p, C.c_uint32, u32p, u64p]),
+        "she_plan_shift_acc_bias": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, i32p, C.c_uint32, C.c_int, u64p,
+                                              C.POINTER(C.c_uint32), u64p]),
+        "she_plan_accumulator_bits": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, i32p, C.POINTER(C.c_uint32)]),
         "she_relu": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_relu_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
@@ -153,14 +157,38 @@ def _plan(rc, gates, levels):
     return gates.value, levels.value
 
 
+def _bias(bias, units):
+    """int32 array [units] and its pointer, or (None, NULL)"""
+    if bias is None:
+        return None, None
+    b = np.ascontiguousarray(bias, dtype=np.int32).reshape(units)
+    return b, _p(b, C.c_int32)
+
+
 def plan_shift_acc(units: int, terms: int, in_bits: int, w_sign, w_exp, acc_bits: int, fold: bool = False,
-                   cells3: bool = False, columns: bool = False):
-    """(gates, levels) of she_shift_acc for these weights; runs on the host, no GPU needed."""
+                   cells3: bool = False, columns: bool = False, bias=None):
+    """(gates, levels) of she_shift_acc(_bias) for these weights; runs on the host, no GPU needed."""
     w_sign, w_exp = _i8(w_sign).reshape(units, terms), _i8(w_exp).reshape(units, terms)
     g, lv = C.c_uint64(0), C.c_uint32(0)
-    return _plan(load_library().she_plan_shift_acc(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
-                                                   acc_bits, _options(fold, False, cells3, columns), C.byref(g),
-                                                   C.byref(lv), None), g, lv)
+    keep, bp = _bias(bias, units)
+    return _plan(load_library().she_plan_shift_acc_bias(units, terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
+                                                        bp, acc_bits, _options(fold, False, cells3, columns), C.byref(g),
+                                                        C.byref(lv), None), g, lv)
+
+
+def plan_accumulator_bits(w_sign, w_exp, in_bits: int, bias=None) -> int:
+    """she_plan_accumulator_bits for weights [units][terms] (leading axes are flattened into units)."""
+    w_sign, w_exp = _i8(w_sign), _i8(w_exp)
+    terms = w_sign.shape[-1]
+    units = int(np.prod(w_sign.shape[:-1]))
+    w_sign, w_exp = w_sign.reshape(units, terms), w_exp.reshape(units, terms)
+    keep, bp = _bias(bias, units)
+    bits = C.c_uint32(0)
+    rc = load_library().she_plan_accumulator_bits(w_sign.shape[0], terms, in_bits, _p(w_sign, C.c_int8), _p(w_exp, C.c_int8),
+                                                  bp, C.byref(bits))
+    if rc:
+        raise SheError(rc, "she_plan_accumulator_bits rejected its arguments")
+    return int(bits.value)
 
 
 def plan_relu(count: int, bits: int, fold: bool = False):
@@ -293,14 +321,21 @@ class Context:
         self._check(self._L.she_eval_gates3(self._h, _p(gtype, C.c_uint8), _p(in0, C.c_uint32), _p(in1, C.c_uint32),
                                             _p(in2, C.c_uint32), _p(out, C.c_uint32), gtype.size))
 
-    def shift_acc(self, x_ids, w_sign, w_exp, acc_bits: int, out_ids) -> int:
+    def shift_acc(self, x_ids, w_sign, w_exp, acc_bits: int, out_ids, bias=None) -> int:
+        """she_shift_acc, or she_shift_acc_bias when a constant per unit is given"""
         x_ids = _u32(x_ids)
         units, terms, in_bits = x_ids.shape
         w_sign, w_exp, out_ids = _i8(w_sign), _i8(w_exp), _u32(out_ids)
         assert w_sign.shape == (units, terms) == w_exp.shape and out_ids.shape == (units, acc_bits)
         gates = C.c_uint64(0)
-        self._check(self._L.she_shift_acc(self._h, _p(x_ids, C.c_uint32), units, terms, in_bits, _p(w_sign, C.c_int8),
-                                          _p(w_exp, C.c_int8), acc_bits, _p(out_ids, C.c_uint32), C.byref(gates)))
+        if bias is None:
+            self._check(self._L.she_shift_acc(self._h, _p(x_ids, C.c_uint32), units, terms, in_bits, _p(w_sign, C.c_int8),
+                                              _p(w_exp, C.c_int8), acc_bits, _p(out_ids, C.c_uint32), C.byref(gates)))
+        else:
+            keep, bp = _bias(bias, units)
+            self._check(self._L.she_shift_acc_bias(self._h, _p(x_ids, C.c_uint32), units, terms, in_bits,
+                                                   _p(w_sign, C.c_int8), _p(w_exp, C.c_int8), bp, acc_bits,
+                                                   _p(out_ids, C.c_uint32), C.byref(gates)))
         return gates.value
 
     def relu(self, x_ids, out_ids) -> int:

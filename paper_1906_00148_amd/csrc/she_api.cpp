@@ -5,6 +5,7 @@
 #include <new>
 
 #include "she_ctx.h"
+#include "../../include/she_diag.h"
 
 using namespace she;
 
@@ -13,8 +14,25 @@ thread_local std::string g_keygen_error;
 
 int fail(she_ctx *c, int code, const std::string &msg)
 {
-    if (c) c->err = msg; else g_keygen_error = msg;
+    try {
+        if (c) c->err = msg; else g_keygen_error = msg;
+    } catch (...) {          // no memory for the text: the code still goes back
+    }
     return code;
+}
+
+// what an exception that reached the C boundary becomes
+int fail_exception(she_ctx *c)
+{
+    try {
+        throw;
+    } catch (const std::bad_alloc &) {
+        return fail(c, SHE_ENOMEM, "host allocation failed");
+    } catch (const std::exception &e) {
+        return fail(c, SHE_EDEVICE, std::string("unexpected failure: ") + e.what());
+    } catch (...) {
+        return fail(c, SHE_EDEVICE, "unexpected failure");
+    }
 }
 }  // namespace she
 
@@ -71,7 +89,7 @@ int ensure_gate_arrays(she_ctx *c, size_t gates)
     if (gates <= c->d_gate_cap) return SHE_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (c->d_type) { hipFree(c->d_type); hipFree(c->d_in0); hipFree(c->d_in1); hipFree(c->d_in2); hipFree(c->d_out); }
-    c->d_type = nullptr; c->d_gate_cap = 0;
+    c->d_type = nullptr; c->d_in0 = c->d_in1 = c->d_in2 = c->d_out = nullptr; c->d_gate_cap = 0;
     gates += gates / 4;
     HIP_TRY(c, hipMalloc((void **)&c->d_type, gates));
     HIP_TRY(c, hipMalloc((void **)&c->d_in0, gates * sizeof(uint32_t)));
@@ -98,7 +116,7 @@ int ensure_mux_arrays(she_ctx *c, size_t muxes)
     if (muxes <= c->d_mux_cap) return SHE_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (c->d_mtype) { hipFree(c->d_mtype); hipFree(c->d_min0); hipFree(c->d_min1); hipFree(c->d_mout); }
-    c->d_mtype = nullptr; c->d_mux_cap = 0;
+    c->d_mtype = nullptr; c->d_min0 = c->d_min1 = c->d_mout = nullptr; c->d_mux_cap = 0;
     muxes += muxes / 4;
     HIP_TRY(c, hipMalloc((void **)&c->d_mtype, 2 * muxes));
     HIP_TRY(c, hipMalloc((void **)&c->d_min0, 2 * muxes * sizeof(uint32_t)));
@@ -192,6 +210,11 @@ bool params_supported(const she_params &P, std::string &why)
     // l = 2, Bg = 2^10) sums of products with every digit at full magnitude land within 0.07 of an integer.
     if ((uint64_t)2 * P.l * P.N * ((uint64_t)1 << (2 * P.bg_bit)) > ((uint64_t)1 << 32)) {
         why = "need 2*l*N*Bg^2 <= 2^32 (exactness of the FP64 polynomial products)"; return false;
+    }
+    // the kernels round by adding 1.5*2^52 and keeping the low word, which is right for |v| < 2^51: the largest sum that
+    // any digits and key words can produce is 2*l*N * Bg/2 * 2^31, so l*N*Bg must stay at or below 2^20
+    if ((uint64_t)P.l * P.N * ((uint64_t)1 << P.bg_bit) > ((uint64_t)1 << 20)) {
+        why = "need l*N*Bg <= 2^20 (the sums of products must stay below 2^51 for the rounding step)"; return false;
     }
     if (P.ks_t < 1 || P.ks_basebit < 1 || P.ks_basebit > 4 || P.ks_t * P.ks_basebit > 16) {
         why = "need ks_basebit <= 4 and ks_t*ks_basebit <= 16"; return false;
@@ -299,7 +322,7 @@ int check_disjoint(she_ctx *c, const uint32_t *ins, size_t n_in, const uint32_t 
 extern "C" {
 
 int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, she_ctx **out)
-{
+try {
     if (!params || !out) return fail(nullptr, SHE_EINVAL, "null argument");
     *out = nullptr;
     std::string why;
@@ -308,7 +331,8 @@ int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(nullptr, SHE_EDEVICE, "no HIP device");
 
-    std::unique_ptr<she_ctx> c(new (std::nothrow) she_ctx);
+    // she_free as the deleter: an exception on the way out releases the device buffers too
+    std::unique_ptr<she_ctx, void (*)(she_ctx *)> c(new (std::nothrow) she_ctx, she_free);
     if (!c) return fail(nullptr, SHE_ENOMEM, "host allocation");
     c->P = *params;
     c->cap = pool_capacity;
@@ -376,7 +400,7 @@ int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, 
     if (rc) return bail(rc);
     *out = c.release();
     return SHE_OK;
-}
+} SHE_NOTHROW(nullptr)
 
 void she_free(she_ctx *c)
 {
@@ -394,7 +418,7 @@ void she_free(she_ctx *c)
 }
 
 int she_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t nbits, uint64_t enc_seed, const uint32_t *dst_ids)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (nbits == 0) return SHE_OK;
     if (!bits || !dst_ids) return fail(c, SHE_EINVAL, "null argument");
@@ -413,7 +437,7 @@ int she_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t nbits, uint64_t enc
     HIP_TRY(c, launch_scatter(space(c), c->d_stage, d_ids, nbits, c->P.n, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 static int fetch(she_ctx *c, const uint32_t *ids, size_t count, std::vector<uint32_t> &host)
 {
@@ -430,7 +454,7 @@ static int fetch(she_ctx *c, const uint32_t *ids, size_t count, std::vector<uint
 }
 
 int she_decrypt(she_ctx *c, const uint32_t *ids, size_t count, uint8_t *bits_out)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (count == 0) return SHE_OK;
     if (!ids || !bits_out) return fail(c, SHE_EINVAL, "null argument");
@@ -440,11 +464,11 @@ int she_decrypt(she_ctx *c, const uint32_t *ids, size_t count, uint8_t *bits_out
     if ((rc = fetch(c, ids, count, host))) return rc;
     phases_to_bits(c->P, c->hk.lwe_key, host.data(), count, bits_out);
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *out,
                    size_t ngates)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (ngates == 0) return SHE_OK;
     if (!type || !in0 || !in1 || !out) return fail(c, SHE_EINVAL, "null argument");
@@ -466,11 +490,11 @@ int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const u
     if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return finish_timing(c);
-}
+} SHE_NOTHROW(c)
 
 int she_eval_gates3(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                     const uint32_t *out, size_t ngates)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (ngates == 0) return SHE_OK;
     if (!type || !in0 || !in1 || !in2 || !out) return fail(c, SHE_EINVAL, "null argument");
@@ -495,22 +519,22 @@ int she_eval_gates3(she_ctx *c, const uint8_t *type, const uint32_t *in0, const 
     if ((rc = enqueue_level(c, c->d_type, c->d_in0, c->d_in1, c->d_out, ngates, c->d_in2))) return rc;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return finish_timing(c);
-}
+} SHE_NOTHROW(c)
 
 int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
                           const uint32_t *d_out, size_t ngates)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (ngates == 0) return SHE_OK;
     if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
     int rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK));
     if (rc) return rc;
     return enqueue_level(c, d_type, d_in0, d_in1, d_out, ngates);
-}
+} SHE_NOTHROW(c)
 
 int she_eval_gates_device_noalloc(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, const uint32_t *d_in1,
                                   const uint32_t *d_out, size_t ngates)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (ngates == 0) return SHE_OK;
     if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
@@ -538,11 +562,11 @@ int she_eval_gates_device_noalloc(she_ctx *c, const uint8_t *d_type, const uint3
     // nothing in the scratch has to start at zero: every word a live gate reads is written earlier in the same call,
     // and what the key switch computes from stale digits of gates past the end is discarded
     return enqueue_level_on(c, W, false, d_type, d_in0, d_in1, d_out, ngates);
-}
+} SHE_NOTHROW(c)
 
 int she_eval_mux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
                  size_t nmux)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (nmux == 0) return SHE_OK;
     if (!sel || !in1 || !in0 || !out) return fail(c, SHE_EINVAL, "null argument");
@@ -575,12 +599,15 @@ int she_eval_mux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uin
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host staging");
     }
-}
+} SHE_NOTHROW(c)
 
 // ---- netlist construction shared by the operators and the planning calls ----
+// bias: one plaintext constant per unit, or null.  With the adder trees a constant that is not 0 modulo 2^acc_bits is
+// one more acc_bits-wide addition of trivial wires to the positive tree's sum, before the subtraction; with column
+// compression it joins the negative terms' constants in plain arithmetic.
 static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids, uint32_t units, uint32_t terms,
                                              uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
-                                             uint32_t acc_bits)
+                                             uint32_t acc_bits, const int32_t *bias = nullptr)
 {
     std::vector<uint32_t> wires;
     wires.reserve((size_t)units * acc_bits);
@@ -592,7 +619,7 @@ static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids,
             signed_terms[t].bits.assign(x_ids + k * in_bits + std::min(drop, in_bits), x_ids + (k + 1) * in_bits);
             signed_terms[t].sign = w_sign[k] > 0 ? 1 : -1;
         }
-        const std::vector<uint32_t> total = nl_columns(nl, signed_terms, acc_bits);
+        const std::vector<uint32_t> total = nl_columns(nl, signed_terms, acc_bits, bias ? (int64_t)bias[u] : 0);
         wires.insert(wires.end(), total.begin(), total.end());
     }
     for (uint32_t u = 0; !nl.columns && u < units; u++) {
@@ -607,6 +634,8 @@ static std::vector<uint32_t> wires_shift_acc(Netlist &nl, const uint32_t *x_ids,
         }
         const bool has_neg = !neg.empty();
         std::vector<uint32_t> total = nl_tree(nl, std::move(pos), in_bits, acc_bits);
+        if (bias && ((uint64_t)(int64_t)bias[u] & (((uint64_t)1 << acc_bits) - 1)))
+            total = nl_add(nl, total, nl_constant(nl, bias[u], acc_bits), acc_bits);
         if (has_neg) total = nl_sub(nl, total, nl_tree(nl, std::move(neg), in_bits, acc_bits));
         wires.insert(wires.end(), total.begin(), total.end());
     }
@@ -671,6 +700,13 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
                   const int8_t *w_sign, const int8_t *w_exp, uint32_t acc_bits, const uint32_t *out_ids,
                   uint64_t *gates_out)
 {
+    return she_shift_acc_bias(c, x_ids, units, terms, in_bits, w_sign, w_exp, nullptr, acc_bits, out_ids, gates_out);
+}
+
+int she_shift_acc_bias(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t terms, uint32_t in_bits,
+                       const int8_t *w_sign, const int8_t *w_exp, const int32_t *bias, uint32_t acc_bits,
+                       const uint32_t *out_ids, uint64_t *gates_out)
+try {
     if (!c) return SHE_EINVAL;
     if (gates_out) *gates_out = 0;
     if (units == 0) return SHE_OK;
@@ -687,16 +723,16 @@ int she_shift_acc(she_ctx *c, const uint32_t *x_ids, uint32_t units, uint32_t te
         return fail(c, SHE_EINVAL, "SHE_OPT_COLUMN_ADDER needs SHE_OPT_FOLD_CONSTANTS and SHE_OPT_GATE3_CELLS");
     try {
         Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
-        const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits);
+        const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits, bias);
         return run_netlist(c, nl, wires, out_ids, gates_out);
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
-}
+} SHE_NOTHROW(c)
 
 int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, const uint32_t *out_ids,
              uint64_t *gates_out)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (gates_out) *gates_out = 0;
     if (count == 0) return SHE_OK;
@@ -714,11 +750,11 @@ int she_relu(she_ctx *c, const uint32_t *x_ids, uint32_t count, uint32_t bits, c
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
-}
+} SHE_NOTHROW(c)
 
 int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                 const uint32_t *out_ids, uint64_t *gates_out)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (gates_out) *gates_out = 0;
     const uint32_t Ho = H / 2, Wo = W / 2;
@@ -737,11 +773,11 @@ int she_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint3
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
-}
+} SHE_NOTHROW(c)
 
 int she_relu_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                      const uint32_t *out_ids, uint64_t *gates_out)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (gates_out) *gates_out = 0;
     const uint32_t Ho = H / 2, Wo = W / 2;
@@ -760,7 +796,7 @@ int she_relu_maxpool(she_ctx *c, const uint32_t *x_ids, uint32_t H, uint32_t W, 
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
-}
+} SHE_NOTHROW(c)
 
 int she_set_option(she_ctx *c, int option, int value)
 {
@@ -845,7 +881,7 @@ static std::string circuit_to_netlist(Netlist &nl, const uint8_t *type, const ui
 
 int she_eval_circuit(she_ctx *c, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                      size_t ngates, const uint32_t *out_refs, const uint32_t *out_ids, size_t nout, uint64_t *entries_out)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (entries_out) *entries_out = 0;
     if (nout == 0) return SHE_OK;                                      // nothing asked for: nothing to evaluate
@@ -892,11 +928,11 @@ int she_eval_circuit(she_ctx *c, const uint8_t *type, const uint32_t *in0, const
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
-}
+} SHE_NOTHROW(c)
 
 int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0, const uint32_t *in1, const uint32_t *in2,
                      size_t ngates, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
-{
+try {
     if (ngates && (!type || !in0 || !in1)) return SHE_EINVAL;
     if (capacity == 0 || capacity > 0x3FFFFFF0u || ngates >= SHE_WIRE_GATE - 2) return SHE_EINVAL;
     try {
@@ -910,7 +946,7 @@ int she_plan_circuit(uint32_t capacity, const uint8_t *type, const uint32_t *in0
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
-}
+} SHE_NOTHROW(nullptr)
 
 // ---- planning: the operators' netlists without a GPU (inputs are wires 0, 1, 2, ... in argument order) ----
 static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
@@ -925,6 +961,38 @@ static int plan_finish(Netlist &nl, uint64_t *gates, uint32_t *levels, uint64_t 
 int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
                        uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
 {
+    return she_plan_shift_acc_bias(units, terms, in_bits, w_sign, w_exp, nullptr, acc_bits, options, gates, levels, rotations);
+}
+
+// Smallest two's-complement width that holds bias + every sum of the unit, for each unit; the widest of them.
+int she_plan_accumulator_bits(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                              const int32_t *bias, uint32_t *bits_out)
+try {
+    if (!bits_out || in_bits < 1 || in_bits > 32 || (terms && units && (!w_sign || !w_exp))) return SHE_EINVAL;
+    const char *why = "";
+    if (!weights_ok(w_sign, w_exp, (size_t)units * terms, in_bits, &why)) return SHE_EINVAL;
+    const int64_t top = ((int64_t)1 << in_bits) - 1;                 // largest input
+    uint32_t bits = in_bits;
+    for (uint32_t u = 0; u < units; u++) {
+        // extreme sums: every positive-weight input at its maximum and the others at zero, and the other way round
+        int64_t hi = bias ? bias[u] : 0, lo = hi;
+        for (uint32_t t = 0; t < terms; t++) {
+            const size_t k = (size_t)u * terms + t;
+            const int64_t most = top >> -(int)w_exp[k];
+            if (w_sign[k] > 0) hi += most; else lo -= most;
+        }
+        uint32_t b = 1;
+        while (b < 63 && !(lo >= -((int64_t)1 << (b - 1)) && hi <= ((int64_t)1 << (b - 1)) - 1)) b++;
+        bits = std::max(bits, b);
+    }
+    *bits_out = bits;
+    return SHE_OK;
+} SHE_NOTHROW(nullptr)
+
+int she_plan_shift_acc_bias(uint32_t units, uint32_t terms, uint32_t in_bits, const int8_t *w_sign, const int8_t *w_exp,
+                            const int32_t *bias, uint32_t acc_bits, int options, uint64_t *gates, uint32_t *levels,
+                            uint64_t *rotations)
+try {
     if (in_bits < 1 || in_bits > acc_bits || acc_bits > 32) return SHE_EINVAL;
     const size_t n_in = (size_t)units * terms * in_bits;
     if (n_in > 0x40000000u || (terms && units && (!w_sign || !w_exp))) return SHE_EINVAL;
@@ -936,15 +1004,15 @@ int she_plan_shift_acc(uint32_t units, uint32_t terms, uint32_t in_bits, const i
         for (size_t k = 0; k < n_in; k++) ids[k] = (uint32_t)k;
         Netlist nl((uint32_t)std::max<size_t>(n_in, 1), (options & SHE_OPT_FOLD_CONSTANTS) != 0, (options & SHE_OPT_NATIVE_MUX) != 0,
                    (options & SHE_OPT_GATE3_CELLS) != 0, (options & SHE_OPT_COLUMN_ADDER) != 0);
-        wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits);
+        wires_shift_acc(nl, ids.data(), units, terms, in_bits, w_sign, w_exp, acc_bits, bias);
         return plan_finish(nl, gates, levels, rotations);
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
-}
+} SHE_NOTHROW(nullptr)
 
 int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, uint32_t *levels, uint64_t *rotations)
-{
+try {
     if (bits < 2 || bits > 64 || (size_t)count * bits > 0x40000000u) return SHE_EINVAL;
     try {
         std::vector<uint32_t> ids((size_t)count * bits);
@@ -956,11 +1024,11 @@ int she_plan_relu(uint32_t count, uint32_t bits, int options, uint64_t *gates, u
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
-}
+} SHE_NOTHROW(nullptr)
 
 int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
                           uint64_t *rotations)
-{
+try {
     const size_t n_in = (size_t)H * W * C * bits;
     if (bits < 2 || bits > 64 || n_in > 0x40000000u) return SHE_EINVAL;
     try {
@@ -973,11 +1041,11 @@ int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
-}
+} SHE_NOTHROW(nullptr)
 
 int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int options, uint64_t *gates, uint32_t *levels,
                      uint64_t *rotations)
-{
+try {
     const size_t n_in = (size_t)H * W * C * bits;
     if (bits < 2 || bits > 64 || n_in > 0x40000000u) return SHE_EINVAL;
     try {
@@ -990,37 +1058,37 @@ int she_plan_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int opti
     } catch (const std::bad_alloc &) {
         return SHE_ENOMEM;
     }
-}
+} SHE_NOTHROW(nullptr)
 
 int she_read_ct(she_ctx *c, uint32_t id, uint32_t *dst)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (!dst) return fail(c, SHE_EINVAL, "null argument");
     if (id >= c->cap) return fail(c, SHE_ERANGE, "she_read_ct: id outside the pool");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(dst, c->pool + (size_t)id * c->stride, (c->P.n + 1) * 4, hipMemcpyDeviceToHost));
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_write_ct(she_ctx *c, uint32_t id, const uint32_t *src)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (!src) return fail(c, SHE_EINVAL, "null argument");
     if (id >= c->cap) return fail(c, SHE_ERANGE, "she_write_ct: id outside the pool");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     HIP_TRY(c, hipMemcpy(c->pool + (size_t)id * c->stride, src, (c->P.n + 1) * 4, hipMemcpyHostToDevice));
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_export_keys(she_ctx *c, uint8_t *lwe_key, uint8_t *ring_key, uint32_t *bk, uint32_t *ks)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (lwe_key) std::memcpy(lwe_key, c->hk.lwe_key.data(), c->hk.lwe_key.size());
     if (ring_key) std::memcpy(ring_key, c->hk.ring_key.data(), c->hk.ring_key.size());
     if (bk) std::memcpy(bk, c->hk.bk.data(), c->hk.bk.size() * 4);
     if (ks) std::memcpy(ks, c->hk.ks.data(), c->hk.ks.size() * 4);
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_set_stream(she_ctx *c, void *hip_stream)
 {
@@ -1051,7 +1119,7 @@ int she_set_round_tracking(she_ctx *c, int on)
 }
 
 int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (!max_abs_frac) return fail(c, SHE_EINVAL, "null argument");
     unsigned raw = 0;
@@ -1062,10 +1130,10 @@ int she_get_round_error(she_ctx *c, double *max_abs_frac, int reset)
     *max_abs_frac = f;
     if (reset) HIP_TRY(c, hipMemset(c->d_round_err, 0, sizeof(unsigned)));
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_probe_fp64_rate(she_ctx *c, int form, double *ns_per_instruction, double *tflops_as_fma)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (form < 0 || form > 3 || (!ns_per_instruction && !tflops_as_fma)) return fail(c, SHE_EINVAL, "form must be 0, 1, 2 or 3");
     // form 3 streams the spectral bootstrapping key in rows of 64 x 16 bytes
@@ -1093,20 +1161,20 @@ int she_probe_fp64_rate(she_ctx *c, int form, double *ns_per_instruction, double
     if (ns_per_instruction) *ns_per_instruction = ns;
     if (tflops_as_fma) *tflops_as_fma = 128.0 * 4.0 * c->dk.cus / ns / 1e3;   // 64 lanes x 2 flop, 4 SIMDs per compute unit
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_set_timing(she_ctx *c, int on)
-{
+try {
     if (!c) return SHE_EINVAL;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->timer.clear();
     c->timer_levels = 0;
     c->timing = on != 0;
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_last_timing(she_ctx *c, double ms[4])
-{
+try {
     if (!c || !ms) return SHE_EINVAL;
     if (!c->timer.ev.empty()) {          // events of she_eval_gates_device calls still pending
         HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1115,7 +1183,7 @@ int she_last_timing(she_ctx *c, double ms[4])
     }
     for (int i = 0; i < 4; i++) ms[i] = c->last_ms[i];
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 const char *she_last_error(const she_ctx *c) { return c ? c->err.c_str() : g_keygen_error.c_str(); }
 

@@ -300,10 +300,11 @@ std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const 
 // majority wire in the next one (none beyond the top column); what is left of the column follows unchanged.  In the
 // new column the carries from below come first, then the parities, then the leftovers; a wire that folding proves
 // zero is dropped.  Once no column holds more than two wires a ripple adder of cells finishes the sum.
-std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits)
+// `bias` is the unit's plaintext constant: it joins the constants of the negative terms.
+std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits, int64_t bias)
 {
     std::vector<std::vector<uint32_t>> cols(acc_bits);
-    uint64_t constant = 0;                                   // mod 2^acc_bits at the end (acc_bits <= 32)
+    uint64_t constant = (uint64_t)bias;                      // mod 2^acc_bits at the end (acc_bits <= 32)
     for (const SignedTerm &term : terms) {
         for (size_t b = 0; b < term.bits.size() && b < acc_bits; b++)
             cols[b].push_back(term.sign > 0 ? term.bits[b] : term.bits[b] ^ WIRE_NEG);
@@ -352,6 +353,14 @@ std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &ter
         if (have_carry && carry == nl.zero()) have_carry = false;
     }
     return out;
+}
+
+// two's complement of a plaintext integer as trivial wires, least significant bit first: no gate
+std::vector<uint32_t> nl_constant(Netlist &nl, int64_t value, uint32_t bits)
+{
+    std::vector<uint32_t> wires(bits);
+    for (uint32_t i = 0; i < bits; i++) wires[i] = (((uint64_t)value >> i) & 1u) ? nl.one() : nl.zero();
+    return wires;
 }
 
 std::vector<uint32_t> nl_tree(Netlist &nl, std::vector<std::vector<uint32_t>> terms, uint32_t in_bits, uint32_t acc_bits)

@@ -69,7 +69,11 @@ struct she_ctx {
 
 namespace she {
 extern thread_local std::string g_keygen_error;        // message of a failed she_keygen (no context yet)
-int fail(she_ctx *c, int code, const std::string &msg); // records the message, returns the code
+int fail(she_ctx *c, int code, const std::string &msg); // records the message, returns the code; never throws
+int fail_exception(she_ctx *c);                         // inside a catch block: maps the exception in flight to a code
+// Nothing may be thrown across the C boundary: every extern "C" function that can allocate on the host or start a
+// thread is a function-try-block that ends with this handler.
+#define SHE_NOTHROW(ctx) catch (...) { return she::fail_exception(ctx); }
 int ensure_stage(she_ctx *c, size_t words);             // grows she_ctx::d_stage
 void free_leveled(she_ctx *c);                          // releases the leveled-mode pools
 }  // namespace she

@@ -152,6 +152,7 @@ std::vector<uint32_t> nl_max(Netlist &nl, const std::vector<uint32_t> &x, const 
 // signed sum of unsigned terms (wires LSB first, no padding; sign +1 / -1) mod 2^acc_bits by column compression;
 // the netlist must fold constants and use three-input cells
 struct SignedTerm { std::vector<uint32_t> bits; int sign; };
-std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits);
+std::vector<uint32_t> nl_columns(Netlist &nl, const std::vector<SignedTerm> &terms, uint32_t acc_bits, int64_t bias = 0);
+std::vector<uint32_t> nl_constant(Netlist &nl, int64_t value, uint32_t bits);   // trivial wires of a plaintext integer
 
 }  // namespace she

@@ -259,11 +259,9 @@ __device__ __forceinline__ void lds_barrier()
 }
 
 constexpr int largest_divisor_up_to(int v, int cap) { int d = cap < v ? cap : v; while (d > 1 && v % d) d--; return d < 1 ? 1 : d; }
-#ifndef SHE_SPLIT_KD
-#define SHE_SPLIT_KD 16
-#endif
+constexpr int SPLIT_KD = 16;       // key values in flight per wavefront of the split kernel (measured: 8 is slower)
 // LR > 0: the gadget has LR levels (l == LR) and a wavefront transforms its LR digit polynomials side by side
-// (forward_pipelined), streaming the key rows through SHE_SPLIT_KD values in flight; LR == 0: any l, one at a time.
+// (forward_pipelined), streaming the key rows through SPLIT_KD values in flight; LR == 0: any l, one at a time.
 template <class PL, bool TRACK, int GB, int LR>
 __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
     const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
@@ -315,7 +313,7 @@ __global__ __launch_bounds__(128 * GB, 2) void k_blind_rotate_split(
     }
     // LR > 0: key value j = (p*2 + o)*P + k of this component's LR rows sits at rows[j*L]
     // (KD divides NV, so that a value keeps its place in the ring from one step to the next)
-    constexpr int NV = LR * 2 * P, KD = LR > 0 ? largest_divisor_up_to(NV, SHE_SPLIT_KD) : 1;
+    constexpr int NV = LR * 2 * P, KD = LR > 0 ? largest_divisor_up_to(NV, SPLIT_KD) : 1;
     double2 kv[KD];
     if constexpr (LR > 0) {
         const double2 *rows = bk_hat + (size_t)(c * LR) * row_elems + t;
@@ -527,7 +525,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
                                                            uint32_t bg_bit, const double2 *__restrict__ tw_table,
                                                            unsigned *round_err)
 {
-    constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N;
+    constexpr int P = PL::P, L = PL::L, N = PL::N;
     static_assert(PL::GPW == 1, "one transform per wavefront");
     __shared__ double2 s_xch[BR_WAVES][PL::XSLOTS];
     __shared__ double2 s_tw[TwTable<PL>::COUNT];
@@ -935,11 +933,7 @@ static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_
     hipLaunchKernelGGL((k_blind_rotate_split<PL, TRACK, GB, LR>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l,  \
                        P.bg_bit, K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs,     \
                        d_out, raw_ext)
-#ifdef SHE_NO_TRIPLE
-        const bool triple = false;
-#else
         const bool triple = P.l == 3;
-#endif
         if (triple) {
             if (d_round_err) { if (two) SHE_LAUNCH_SPLIT(true, 2, 3); else SHE_LAUNCH_SPLIT(true, 1, 3); }
             else { if (two) SHE_LAUNCH_SPLIT(false, 2, 3); else SHE_LAUNCH_SPLIT(false, 1, 3); }

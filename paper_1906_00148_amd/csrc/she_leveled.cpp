@@ -50,7 +50,7 @@ void free_leveled(she_ctx *c)
 extern "C" {
 
 int she_leveled_init(she_ctx *c, uint32_t trgsw_capacity, uint32_t trlwe_capacity)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (!trgsw_capacity || !trlwe_capacity) return fail(c, SHE_EINVAL, "capacities must be positive");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -63,10 +63,10 @@ int she_leveled_init(she_ctx *c, uint32_t trgsw_capacity, uint32_t trlwe_capacit
     HIP_TRY(c, hipMemsetAsync(c->lev.trlwe, 0, (size_t)trlwe_capacity * 2 * c->P.N * sizeof(uint32_t), c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_trgsw_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t count, uint64_t seed, const uint32_t *dst_ids)
-{
+try {
     if (!c) return SHE_EINVAL;
     int rc;
     if ((rc = need_pools(c))) return rc;
@@ -90,7 +90,7 @@ int she_trgsw_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t count, uint64
         HIP_TRY(c, hipStreamSynchronize(c->stream));
     }
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 // Device order of a TRLWE component (the order the CMux kernel's lanes read it in): lane t of a transform works on
 // the coefficients t + 64 m and t + 64 m + N/2 (m < N/128), and the 16-byte word (q, t) holds those of m = 2q and
@@ -118,7 +118,7 @@ static int upload_trlwe(she_ctx *c, const uint32_t *host, size_t count, const ui
 }
 
 int she_trlwe_encrypt(she_ctx *c, const uint32_t *mu, size_t count, uint64_t seed, const uint32_t *dst_ids)
-{
+try {
     if (!c) return SHE_EINVAL;
     int rc;
     if ((rc = need_pools(c))) return rc;
@@ -129,10 +129,10 @@ int she_trlwe_encrypt(she_ctx *c, const uint32_t *mu, size_t count, uint64_t see
     try { host.resize(count * 2 * c->P.N); } catch (const std::bad_alloc &) { return fail(c, SHE_ENOMEM, "host staging"); }
     fresh_trlwe(c->P, c->hk.ring_key, mu, count, seed, host.data());
     return upload_trlwe(c, host.data(), count, dst_ids);
-}
+} SHE_NOTHROW(c)
 
 int she_trlwe_write(she_ctx *c, const uint32_t *samples, size_t count, const uint32_t *dst_ids)
-{
+try {
     if (!c) return SHE_EINVAL;
     int rc;
     if ((rc = need_pools(c))) return rc;
@@ -140,10 +140,10 @@ int she_trlwe_write(she_ctx *c, const uint32_t *samples, size_t count, const uin
     if (!samples || !dst_ids) return fail(c, SHE_EINVAL, "null argument");
     if ((rc = check_range(c, dst_ids, count, c->lev.trlwe_cap, "she_trlwe_write"))) return rc;
     return upload_trlwe(c, samples, count, dst_ids);
-}
+} SHE_NOTHROW(c)
 
 int she_trlwe_read(she_ctx *c, const uint32_t *ids, size_t count, uint32_t *samples)
-{
+try {
     if (!c) return SHE_EINVAL;
     int rc;
     if ((rc = need_pools(c))) return rc;
@@ -162,10 +162,10 @@ int she_trlwe_read(she_ctx *c, const uint32_t *ids, size_t count, uint32_t *samp
             for (uint32_t j = 0; j < N; j++)
                 samples[k * words + comp * N + j] = dev[k * words + comp * N + device_pos(N, j)];
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_trlwe_phase(she_ctx *c, const uint32_t *ids, size_t count, uint32_t *phases)
-{
+try {
     if (!c) return SHE_EINVAL;
     if (count == 0) return SHE_OK;
     if (!phases) return fail(c, SHE_EINVAL, "null argument");
@@ -175,11 +175,11 @@ int she_trlwe_phase(she_ctx *c, const uint32_t *ids, size_t count, uint32_t *pha
     if (rc) return rc;
     trlwe_phases(c->P, c->hk.ring_key, host.data(), count, phases);
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 int she_eval_cmux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
                   size_t count)
-{
+try {
     if (!c) return SHE_EINVAL;
     int rc;
     if ((rc = need_pools(c))) return rc;
@@ -226,6 +226,6 @@ int she_eval_cmux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const ui
         c->last_ms[0] = 0; c->last_ms[1] = ms; c->last_ms[2] = 0; c->last_ms[3] = 1;   // the CMux kernel, one level
     }
     return SHE_OK;
-}
+} SHE_NOTHROW(c)
 
 }  // extern "C"

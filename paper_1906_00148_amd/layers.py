@@ -12,20 +12,11 @@ from __future__ import annotations
 import numpy as np
 
 
-def accumulator_bits(w_sign, w_exp, in_bits: int) -> int:
-    """Smallest two's-complement width that holds every sum  sum_i sign_i * (x_i >> |exp_i|)  over unsigned in_bits-bit
-    inputs, for weights [units][terms] (the weights are plaintext, so the server knows the range; Section 3.3 sizes
-    the accumulator's adders by the bits they can receive).  A layer run at this width gives the same integers as at
-    any larger one."""
-    w_sign, w_exp = np.asarray(w_sign, np.int64), np.asarray(w_exp, np.int64)
-    w_sign, w_exp = w_sign.reshape(-1, w_sign.shape[-1]), w_exp.reshape(-1, w_exp.shape[-1])
-    top = ((1 << in_bits) - 1) >> (-w_exp)
-    hi = int(np.where(w_sign > 0, top, 0).sum(axis=1).max(initial=0))
-    lo = int(np.where(w_sign < 0, top, 0).sum(axis=1).max(initial=0))
-    bits = 1
-    while not (lo <= (1 << (bits - 1)) and hi <= (1 << (bits - 1)) - 1):
-        bits += 1
-    return max(bits, in_bits)
+def accumulator_bits(w_sign, w_exp, in_bits: int, bias=None) -> int:
+    """Smallest accumulator width for these plaintext weights (and per-unit constants): the library's host-only
+    planning call she_plan_accumulator_bits (Section 3.3 sizes the adders by the bits they can receive)."""
+    from .binding import plan_accumulator_bits
+    return plan_accumulator_bits(w_sign, w_exp, in_bits, bias)
 
 
 class Chain:
@@ -43,9 +34,10 @@ class Chain:
         return ids
 
     # ---- linear layers (Section 3.2 / 3.3)
-    def conv(self, x_ids, w_sign, w_exp, acc_bits: int) -> np.ndarray:
+    def conv(self, x_ids, w_sign, w_exp, acc_bits: int, bias=None) -> np.ndarray:
         """Valid convolution, stride 1.  x_ids [H][W][C][bits] unsigned inputs, w_sign / w_exp
-        [OC][k][k][C]; returns ids [H-k+1][W-k+1][OC][acc_bits] (two's complement)."""
+        [OC][k][k][C], bias [OC] plaintext constants per channel (a folded batch normalisation's shift) or None;
+        returns ids [H-k+1][W-k+1][OC][acc_bits] (two's complement)."""
         x_ids = np.asarray(x_ids, np.uint32)
         H, W, Cin, bits = x_ids.shape
         OC, k = w_sign.shape[0], w_sign.shape[1]
@@ -60,12 +52,15 @@ class Chain:
         s_units = np.broadcast_to(w_sign.reshape(1, 1, OC, terms), (oh, ow, OC, terms)).reshape(-1, terms)
         e_units = np.broadcast_to(w_exp.reshape(1, 1, OC, terms), (oh, ow, OC, terms)).reshape(-1, terms)
         out = self.alloc((oh, ow, OC, acc_bits))
+        b_units = None if bias is None else np.ascontiguousarray(np.broadcast_to(np.asarray(bias, np.int32).reshape(1, 1, OC),
+                                                                                   (oh, ow, OC))).reshape(-1)
         self.gates += self.ctx.shift_acc(np.ascontiguousarray(x_units), np.ascontiguousarray(s_units),
-                                         np.ascontiguousarray(e_units), acc_bits, out.reshape(-1, acc_bits))
+                                         np.ascontiguousarray(e_units), acc_bits, out.reshape(-1, acc_bits), bias=b_units)
         return out
 
-    def dense(self, x_ids, w_sign, w_exp, acc_bits: int) -> np.ndarray:
-        """Fully-connected layer.  x_ids [...][bits] (flattened to F inputs), w_sign / w_exp [O][F]; returns [O][acc_bits]."""
+    def dense(self, x_ids, w_sign, w_exp, acc_bits: int, bias=None) -> np.ndarray:
+        """Fully-connected layer.  x_ids [...][bits] (flattened to F inputs), w_sign / w_exp [O][F], bias [O] or None;
+        returns [O][acc_bits]."""
         x_ids = np.asarray(x_ids, np.uint32)
         bits = x_ids.shape[-1]
         flat = x_ids.reshape(-1, bits)
@@ -73,7 +68,7 @@ class Chain:
         assert w_sign.shape == (O, flat.shape[0]) == w_exp.shape
         out = self.alloc((O, acc_bits))
         x_units = np.ascontiguousarray(np.broadcast_to(flat[None], (O,) + flat.shape))
-        self.gates += self.ctx.shift_acc(x_units, w_sign, w_exp, acc_bits, out)
+        self.gates += self.ctx.shift_acc(x_units, w_sign, w_exp, acc_bits, out, bias=bias)
         return out
 
     # ---- non-linear layers (Section 3.1)

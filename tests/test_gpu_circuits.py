@@ -234,3 +234,30 @@ def test_paper_bitwidths_five_bit_inputs_mixed_width_tree(ctx):
     assert gates == len(nl.gtype) and gates < 0.6 * len(wide.gtype)
     assert np.array_equal(OC.from_bits(ctx.decrypt(out), True), OC.plain_shift_acc(x, sign, exp, 16))
     print(f"\nb=5: {gates} gates mixed-width against {len(wide.gtype)} with 16-bit adders throughout")
+
+
+def test_chained_network_with_folded_batchnorm_constants(ctx):
+    """The C-B-A-P ... layer sequence with the batch normalisations folded into per-channel constants: conv + bias, ReLU,
+    pool, conv + bias, ReLU, pool, dense + bias on the device; the ten class scores against the plain network."""
+    import paper_1906_00148_amd as pkg
+    from paper_1906_00148_amd.layers import Chain
+    img, w1, w2, w3 = S.cfg6_network()
+    rng = np.random.default_rng(S.data_seed(9))
+    b1, b2, b3 = rng.integers(-300, 300, w1[0].shape[0]), rng.integers(-300, 300, w2[0].shape[0]), rng.integers(-2000, 2000, w3[0].shape[0])
+    want = OC.plain_network(img, w1, w2, w3, biases=(b1, b2, b3))
+    assert not np.array_equal(want, OC.plain_network(img, w1, w2, w3))          # the constants matter
+    for modes in ((0, 0, 0, 0), (1, 1, 1, 1)):
+        for opt, v in zip((pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER), modes):
+            ctx.set_option(opt, v)
+        try:
+            x_ids = encrypt_values(ctx, img[..., None], 8, S.data_seed(6))
+            net = Chain(ctx, x_ids.size)
+            a = net.maxpool(net.relu(net.conv(x_ids, w1[0], w1[1], 16, bias=b1)))
+            b = net.maxpool(net.relu(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16, bias=b2)))
+            scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16, bias=b3)
+            got = OC.from_bits(ctx.decrypt(scores), True)
+            print(f"\nnetwork with constants (modes {modes}): {net.gates} entries, scores {got.tolist()}")
+            assert np.array_equal(got, want)
+        finally:
+            for opt in (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER):
+                ctx.set_option(opt, 0)

@@ -420,11 +420,11 @@ def test_maxpool_with_native_mux_matches_oracle_netlist_toy(toy_ctx, toy_keys):
 @pytest.mark.parametrize("shape", [dict(n=64, N=256, l=2, bg_bit=10, ks_t=5, ks_basebit=3),
                                    dict(n=80, N=512, l=4, bg_bit=6, ks_t=4, ks_basebit=4),
                                    dict(n=48, N=1024, l=2, bg_bit=8, ks_t=16, ks_basebit=1),
-                                   dict(n=40, N=1024, l=2, bg_bit=10, ks_t=8, ks_basebit=2)])
+                                   dict(n=40, N=512, l=2, bg_bit=10, ks_t=8, ks_basebit=2)])
 def test_other_parameter_shapes_use_the_generic_key_switch(shape):
     """Gadget lengths 1..4 and key-switch bases other than 4 (these take the select-and-subtract
-    key-switch kernel, not the MFMA one; the last shape has the MFMA one's base and the largest gadget base the
-    parameter rule admits at N = 1024): gates and a native MUX, every word against the oracle."""
+    key-switch kernel, not the MFMA one; the last shape has the MFMA one's base and sits on both bounds of the
+    parameter rule, 2*l*N*Bg^2 = 2^31 and l*N*Bg = 2^20): gates and a native MUX, every word against the oracle."""
     pkg = she()
     K = O.keygen(O.Params(**shape), 77)
     with pkg.Context(pkg.Params(**shape), 77, 256) as ctx:
@@ -435,7 +435,7 @@ def test_other_parameter_shapes_use_the_generic_key_switch(shape):
         ctx.set_round_tracking(True)
         ctx.get_round_error(reset=True)
         ctx.eval_gates(codes, in_ids[0::2], in_ids[1::2], out_ids)
-        assert ctx.get_round_error() < 0.2          # the last shape sits on the bound 2*l*N*Bg^2 = 2^32
+        assert ctx.get_round_error() < 0.2          # the last shape sits on the parameter rule's bounds
         ctx.set_round_tracking(False)
         pool = np.zeros((64, shape["n"] + 1), np.uint32)
         pool[:40] = O.encrypt_bits(K, bits, 17)
@@ -527,6 +527,47 @@ def test_shift_acc_by_column_compression_matches_oracle_netlist_toy(toy_ctx, toy
         pool = nl.run_encrypted(toy_keys, fresh, threads=8)
         assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
         assert np.array_equal(OC.from_bits(toy_ctx.decrypt(out_ids), True), OC.plain_shift_acc(x, sign, exp, acc_bits))
+    finally:
+        for opt in (pkg.OPT_COLUMN_ADDER, pkg.OPT_GATE3_CELLS, pkg.OPT_FOLD_CONSTANTS):
+            toy_ctx.set_option(opt, 0)
+
+
+@pytest.mark.parametrize("fold,cells,columns", [(False, False, False), (True, False, False), (False, True, False),
+                                                (True, True, False), (True, True, True)])
+def test_shift_acc_with_bias_matches_oracle_netlist_toy(toy_ctx, toy_keys, fold, cells, columns):
+    """she_shift_acc_bias (a plaintext constant per unit: the folded batch-normalisation shift of the C-B-A-P layer
+    sequences): every output word against the oracle's netlist with the same constants, in every option mode; the
+    decrypted sums against bias + sum sign (x >> |e|) mod 2^acc.  Units: positive, negative, zero (the netlist must be
+    the one without a constant) and out-of-range constants; an all-negative unit; a unit without terms is its bias."""
+    pkg = she()
+    x = np.array([[5, 7, 2, 6, 1], [3, 3, 0, 7, 4], [7, 7, 7, 7, 7], [1, 2, 3, 4, 5]])
+    sign = np.array([[1, -1, 1, 1, -1], [1, 1, 1, 1, 1], [-1, -1, -1, -1, -1], [1, -1, 1, -1, 1]], np.int8)
+    exp = np.array([[0, -1, 0, -2, 0], [0, 0, -1, -2, 0], [0, 0, 0, -1, -2], [0, 0, 0, 0, 0]], np.int8)
+    bias = np.array([9, -13, 0, 200], np.int32)
+    in_bits, acc_bits = 3, 6
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 91, 0)
+    out_ids = np.arange(1000, 1000 + 4 * acc_bits, dtype=np.uint32).reshape(4, acc_bits)
+    toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, int(fold))
+    toy_ctx.set_option(pkg.OPT_GATE3_CELLS, int(cells))
+    toy_ctx.set_option(pkg.OPT_COLUMN_ADDER, int(columns))
+    try:
+        gates = toy_ctx.shift_acc(ids.reshape(4, 5, in_bits), sign, exp, acc_bits, out_ids, bias=bias)
+        nl, outs = OC.build_shift_acc(4, 5, in_bits, sign, exp, acc_bits, fold=fold, cells3=cells, columns=columns, bias=bias)
+        assert gates == len(nl.gtype)
+        pool = nl.run_encrypted(toy_keys, fresh, threads=8)
+        assert np.array_equal(toy_ctx.read_cts(out_ids), OC.Netlist.read_encrypted(pool, np.array(outs)))
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(out_ids), True), OC.plain_shift_acc(x, sign, exp, acc_bits, bias))
+        # no terms: the result is the constant itself; under folding it stays trivial ciphertexts and costs nothing,
+        # otherwise the adder of the constant bootstraps its trivial operands like any other gate
+        none = np.arange(2000, 2000 + acc_bits, dtype=np.uint32).reshape(1, acc_bits)
+        g0 = toy_ctx.shift_acc(np.zeros((1, 0, in_bits), np.uint32), np.zeros((1, 0), np.int8), np.zeros((1, 0), np.int8),
+                               acc_bits, none, bias=[-7])
+        nl0, _ = OC.build_shift_acc(1, 0, in_bits, np.zeros((1, 0)), np.zeros((1, 0)), acc_bits, fold=fold, cells3=cells,
+                                    columns=columns, bias=[-7])
+        assert g0 == len(nl0.gtype) and (g0 == 0) == fold
+        assert int(OC.from_bits(toy_ctx.decrypt(none), True)[0]) == -7
+        if fold:
+            assert not toy_ctx.read_cts(none)[:, : toy_keys.params.n].any()
     finally:
         for opt in (pkg.OPT_COLUMN_ADDER, pkg.OPT_GATE3_CELLS, pkg.OPT_FOLD_CONSTANTS):
             toy_ctx.set_option(opt, 0)

@@ -16,9 +16,13 @@ def lib():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "she.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(she_[a-z_]+)\s*\(", text)))
+    """every function declared in include/*.h (the problem's calls in she.h, the diagnostics in she_diag.h)"""
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(she_[a-z_0-9]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_seven_calls():
@@ -44,7 +48,8 @@ def test_bad_parameters_are_rejected_before_any_gpu_work(lib):
     from paper_1906_00148_amd.binding import _CParams
     h = ctypes.c_void_p()
     for bad in (dict(k=2), dict(N=300), dict(n=0), dict(l=5, bg_bit=7), dict(ks_t=9, ks_basebit=2),
-                dict(N=1024, l=1, bg_bit=12)):
+                dict(N=1024, l=1, bg_bit=12),                 # 2*l*N*Bg^2 = 2^35
+                dict(N=1024, l=2, bg_bit=10)):                # passes that bound, but l*N*Bg = 2^21: sums may reach 2^51
         kw = dict(n=128, N=256, k=1, bg_bit=7, l=3, ks_t=8, ks_basebit=2, lwe_std=2.0 ** -15, bk_std=2.0 ** -25)
         kw.update(bad)
         cp = _CParams(**kw)
@@ -123,13 +128,14 @@ def test_planning_calls_match_the_oracle_netlists():
 
 def test_fp64_products_round_to_the_exact_integers_under_the_parameter_rule():
     """The library multiplies in Z[X]/(X^N+1) with FP64 transforms and rounds; she_keygen admits a parameter set only
-    if 2*l*N*Bg^2 <= 2^32.  The same arithmetic on the CPU (numpy's FP64 FFT on the folded, twisted polynomial, no code
+    if 2*l*N*Bg^2 <= 2^32 and l*N*Bg <= 2^20 (the second keeps every sum below 2^51, where the kernels' rounding step is
+    valid whatever the digits and key words are).  The same arithmetic on the CPU (numpy's FP64 FFT on the folded, twisted polynomial, no code
     of the library), on digits and key coefficients of the admitted sizes with every digit at full magnitude: the sums
     of 2*l products land within a small fraction of 1/2 of the exact integers, which Python integers give."""
     import numpy as np
     rng = np.random.default_rng(2030)
-    for N, l, bg_bit in ((1024, 3, 7), (256, 3, 7), (512, 2, 9), (1024, 2, 10)):
-        assert 2 * l * N * 4 ** bg_bit <= 1 << 32
+    for N, l, bg_bit in ((1024, 3, 7), (256, 3, 7), (512, 2, 10), (1024, 2, 9), (2048, 3, 7)):
+        assert 2 * l * N * 4 ** bg_bit <= 1 << 32 and l * N * 2 ** bg_bit <= 1 << 20
         M, half = N // 2, 1 << (bg_bit - 1)
         twist = np.exp(1j * np.pi * np.arange(M) / N)
 
@@ -171,3 +177,34 @@ def test_accumulator_bits_is_the_smallest_width_that_holds_every_sum():
         lo = max(sum(top >> -e for s, e in zip(sign[u], exp[u]) if s < 0) for u in range(units))
         fits = lambda b: -(1 << (b - 1)) <= -lo and hi <= (1 << (b - 1)) - 1
         assert fits(bits) and bits >= in_bits and (bits == in_bits or not fits(bits - 1))
+
+
+def test_accumulator_bits_with_constants_and_shift_acc_bias_plans_like_the_oracle():
+    """The planning calls with a constant per unit: she_plan_accumulator_bits against the extreme sums written out,
+    she_plan_shift_acc_bias (entries and levels) against the oracle's netlists in every option mode."""
+    import numpy as np
+
+    import paper_1906_00148_amd as pkg
+    from oracle import circuits as OC
+    rng = np.random.default_rng(6)
+    for _ in range(40):
+        units, terms, in_bits = int(rng.integers(1, 5)), int(rng.integers(0, 30)), int(rng.integers(1, 9))
+        sign = rng.choice([-1, 1], (units, terms))
+        exp = -rng.integers(0, in_bits, (units, terms))
+        bias = rng.integers(-3000, 3000, units)
+        bits = pkg.plan_accumulator_bits(sign, exp, in_bits, bias)
+        top = (1 << in_bits) - 1
+        fits = lambda b: all(
+            -(1 << (b - 1)) <= int(bias[u]) - sum(top >> -e for s, e in zip(sign[u], exp[u]) if s < 0)
+            and int(bias[u]) + sum(top >> -e for s, e in zip(sign[u], exp[u]) if s > 0) <= (1 << (b - 1)) - 1
+            for u in range(units))
+        assert fits(bits) and bits >= in_bits and (bits == in_bits or not fits(bits - 1))
+        acc = min(max(bits, in_bits), 32)
+        for fold, cells3, columns in ((False, False, False), (True, False, False), (True, True, False), (True, True, True)):
+            nl, _ = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, fold=fold, cells3=cells3, columns=columns, bias=bias)
+            lev = nl.levels()
+            want = (len(nl.gtype), int(lev.max()) if lev.size else 0)
+            assert pkg.plan_shift_acc(units, terms, in_bits, sign, exp, acc, fold, cells3, columns, bias=bias) == want
+    # no constants: the same width as without the argument
+    sign, exp = rng.choice([-1, 1], (3, 9)), -rng.integers(0, 8, (3, 9))
+    assert pkg.plan_accumulator_bits(sign, exp, 8) == pkg.plan_accumulator_bits(sign, exp, 8, [0, 0, 0])
