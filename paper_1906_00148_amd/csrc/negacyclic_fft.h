@@ -154,11 +154,94 @@ __device__ __forceinline__ void wave_lds_fence()
 //   s = 0: exp(i*pi*t*(1+4k)/N)                    (twist psi^t merged with the first pass)
 //   s > 0: exp(2*pi*i*k*(t mod T)/(P*T)), T = P^(K-1-s)
 // which depends on t only through t mod T, so pass s stores P*T entries: [k][t mod T].
+// Plans with a node-ordered forward transform (below) append its table: rows of P/2 entries (cos, tan), one row per
+// value of the node index that the lane contributes, for every pass after the first.
 template <class PL> struct TwTable {
     static constexpr int period(int s) { return ipow(PL::P, PL::K - 1 - s); }              // T of pass s
     static constexpr int offset(int s) { return s == 0 ? 0 : offset(s - 1) + PL::P * period(s - 1); }
-    static constexpr int COUNT = PL::K > 1 ? offset(PL::K - 1) : 1;                          // complex entries
+    static constexpr int COUNT_PASSES = PL::K > 1 ? offset(PL::K - 1) : 1;                   // complex entries
+    // node-ordered forward transform: only written out for three passes of radix 8 (N = 1024)
+    static constexpr bool NODE_FORWARD = PL::LOGP == 3 && PL::K == 3;
+    static constexpr int ROW = PL::P / 2;                                                    // entries per lane and pass
+    static constexpr int node_offset(int pass) { return COUNT_PASSES + (pass == 1 ? 0 : ROW * PL::P); }   // pass 1, pass 2
+    static constexpr int COUNT = COUNT_PASSES + (NODE_FORWARD ? ROW * PL::P + ROW * PL::P * PL::P : 0);
 };
+
+// ---- node-ordered forward transform ------------------------------------------------------------------------------
+// The same transform X_k = sum_j u_j exp(2*pi*i*j*(4k+1)/(4M)) computed as m = log2(M) stages of radix-2 butterflies
+// (a, b) -> (a + w b, a - w b) on positions j, j + M/2^(s+1) (stage s = 0..m-1), in place.  Splitting the sum by the
+// top bit of j shows that the two halves are again sums of this form, of half the length, with the shift 1/4 replaced
+// by (1/4 + r)/2^s, r = the s low bits of k that the earlier stages fixed: the butterflies of one such sub-sum (a
+// "node") share ONE twiddle
+//     w(s, r) = exp(i*pi*(1 + 4r) / 2^(s+2)),
+// the twist needs no multiplication of its own, and no twiddle is trivial, so every butterfly is six fused
+// multiply-adds with w = c*(1 + i*t):  p = b + i*t*b (2), a +- c*p (4).  Further w(s, r + 2^(s-1)) = i*w(s, r): a node
+// whose most recently fixed bit is 1 uses its sibling's entry on i*b, which only renames and negates operands.
+// Position q ends up holding X_k with k = the bits of q reversed.  With P points of a lane covering the top log2(P)
+// position bits in the first pass and the exchanges of forward_n(), pass p's node index is r = R + (bits fixed inside
+// the pass) * 2^(p*log2 P), R given by the lane; a lane needs P/2 entries per pass: for stage e of the pass, entry
+// w(p*log2 P + e, R + 2^(p*log2 P) * (index of the node among those of the stage, most recent bit dropped)).
+// The first pass has R = 0: compile-time constants.  Spectra land in the lane and register that forward_n() and
+// inverse_n() use, so the two forward transforms are interchangeable.
+struct CosTan { double c, t; };
+__host__ __device__ inline long double node_angle(int s, int r)       // of w(s, r), in units of pi
+{
+    return (long double)(1 + 4 * r) / (long double)(1ll << (s + 2));
+}
+// constants of the first pass (R = 0): stage e entry i is w(e, i), i < max(1, 2^(e-1)); up to 16 points per lane
+__host__ __device__ constexpr CosTan first_pass_entry(int e, int i)
+{
+    // cos and tan of pi*(1+4i)/2^(e+2): e=0: pi/4; e=1: pi/8; e=2: pi/16, 5pi/16; e=3: pi/32, 5pi/32, 9pi/32, 13pi/32
+    constexpr CosTan v[8] = {
+        {0.70710678118654752440, 1.0},
+        {0.92387953251128675613, 0.41421356237309504880},
+        {0.98078528040323044913, 0.19891236737965800691},
+        {0.55557023301960222474, 1.49660576266548901760},
+        {0.99518472667219688624, 0.09849140335716425308},
+        {0.88192126434835502971, 0.53451113595079164641},
+        {0.63439328416364549822, 1.21850352558797634479},
+        {0.29028467725446236764, 3.29655820893832042688},
+    };
+    return v[e == 0 ? 0 : (1 << (e - 1)) + i];
+}
+
+// y0 = a + w*b -> a, y1 = a - w*b -> b, with w = c*(1 + i*t), or i times that when ROT
+template <bool ROT>
+__host__ __device__ __forceinline__ void node_butterfly(double &ar, double &ai, double &br, double &bi, double c, double t)
+{
+    double pr, pi;
+    if (!ROT) { pr = __builtin_fma(-t, bi, br); pi = __builtin_fma(t, br, bi); }
+    else      { pr = __builtin_fma(-t, br, -bi); pi = __builtin_fma(-t, bi, br); }       // (1 + i*t) * (i*b)
+    const double sr = __builtin_fma(c, pr, ar), si = __builtin_fma(c, pi, ai);
+    br = __builtin_fma(-c, pr, ar); bi = __builtin_fma(-c, pi, ai);
+    ar = sr; ai = si;
+}
+
+// One pass: log2(P) stages on the P points of a lane; register index = the pass's position bits, top bit first fixed.
+// e[] = the lane's P/2 entries in stage order (1, 1, 2, 4, ... per stage).
+template <int P> __host__ __device__ __forceinline__ void node_pass(double (&xr)[P], double (&xi)[P], const CosTan (&e)[P / 2])
+{
+    constexpr int LOGP = __builtin_ctz(P);
+#pragma unroll
+    for (int st = 0; st < LOGP; st++) {
+        const int half = P >> (st + 1);                  // distance of the pair
+#pragma unroll
+        for (int base = 0; base < P; base += 2 * half) {
+            const int fixed = base / (2 * half);         // the st bits fixed so far, first fixed = highest
+            // node index inside the pass = those bits reversed; its top (most recent) bit selects the rotated form
+            int rev = 0;
+            for (int i = 0; i < st; i++) rev |= ((fixed >> (st - 1 - i)) & 1) << i;
+            const bool rot = st > 0 && ((rev >> (st - 1)) & 1);
+            const int idx = st > 0 ? (rev & ((1 << (st - 1)) - 1)) : 0;
+            const CosTan w = e[st == 0 ? 0 : (1 << (st - 1)) + idx];
+#pragma unroll
+            for (int j = 0; j < half; j++) {
+                if (rot) node_butterfly<true>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
+                else node_butterfly<false>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
+            }
+        }
+    }
+}
 
 template <class PL> inline void make_twiddles(double *out /* [TwTable::COUNT][2] */)
 {
@@ -173,6 +256,25 @@ template <class PL> inline void make_twiddles(double *out /* [TwTable::COUNT][2]
                 o[0] = (double)cosl(ang);
                 o[1] = (double)sinl(ang);
             }
+    }
+    if constexpr (TwTable<PL>::NODE_FORWARD) {
+        // pass p (1, 2): row per lane value R; entries of stage e: w(p*LOGP + e, R + 2^(p*LOGP) * i), i < max(1, 2^(e-1))
+        constexpr int P = PL::P, LOGP = PL::LOGP, ROW = TwTable<PL>::ROW;
+        for (int pass = 1; pass < PL::K; pass++) {
+            const int rows = ipow(P, pass), s0 = pass * LOGP;
+            for (int lane_part = 0; lane_part < rows; lane_part++) {
+                // pass 1: R = k0 = the row; pass 2: the lane is 8*k0 + k1 and R = k0 + 8*k1
+                const int R = pass == 1 ? lane_part : (lane_part / P) + P * (lane_part % P);
+                double *row = out + 2 * ((size_t)TwTable<PL>::node_offset(pass) + (size_t)lane_part * ROW);
+                for (int e = 0; e < LOGP; e++)
+                    for (int i = 0; i < (e == 0 ? 1 : 1 << (e - 1)); i++) {
+                        const long double ang = pi * node_angle(s0 + e, R + (1 << s0) * i);
+                        const int slot = e == 0 ? 0 : (1 << (e - 1)) + i;
+                        row[2 * slot] = (double)cosl(ang);
+                        row[2 * slot + 1] = (double)tanl(ang);
+                    }
+            }
+        }
     }
 }
 
@@ -212,6 +314,101 @@ template <class PL> __device__ __forceinline__ void load_twiddles(double2 *lds, 
     __syncthreads();
 }
 
+// The lane's entries of one pass of the node-ordered forward transform: constants in the first pass, one table row
+// (requested together, ahead of the butterflies) in the others.
+template <class PL> __device__ __forceinline__ void node_entries(const LaneCtx<PL> &lc, int pass, CosTan (&e)[PL::P / 2])
+{
+    constexpr int P = PL::P, ROW = P / 2;
+    if (pass == 0) {
+#pragma unroll
+        for (int st = 0; st < PL::LOGP; st++)
+#pragma unroll
+            for (int i = 0; i < (st == 0 ? 1 : 1 << (st - 1)); i++) e[st == 0 ? 0 : (1 << (st - 1)) + i] = first_pass_entry(st, i);
+    } else {
+        const int lane_part = lc.t / ipow(P, PL::K - 1 - pass);
+        const double2 *row = lc.tw + TwTable<PL>::node_offset(pass) + ROW * lane_part;
+#pragma unroll
+        for (int i = 0; i < ROW; i++) { const double2 v = row[i]; e[i].c = v.x; e[i].t = v.y; }
+    }
+}
+
+// Node-ordered forward transform of NB polynomials side by side (see node_pass): same input and output layout as
+// forward_n()'s other branch.
+template <class PL, int NB>
+__device__ __forceinline__ void forward_nodes(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                              double (&xi)[NB][PL::P])
+{
+    constexpr int P = PL::P, K = PL::K, LOGP = PL::LOGP;
+#pragma unroll
+    for (int pass = 0; pass < K; pass++) {
+        CosTan e[P / 2];
+        node_entries<PL>(lc, pass, e);
+#pragma unroll
+        for (int b = 0; b < NB; b++) node_pass<P>(xr[b], xi[b], e);
+        if (pass == K - 1) break;
+        wave_lds_fence();
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+#pragma unroll
+            for (int m = 0; m < P; m++)                      // row = the bits fixed in this pass, first fixed lowest
+                xch[b][brev(m, LOGP) * PL::XROW + lc.t] = make_double2(xr[b][m], xi[b][m]);
+        wave_lds_fence();
+        const int Tn = ipow(P, K - 2 - pass);
+#pragma unroll
+        for (int b = 0; b < NB; b++)
+#pragma unroll
+            for (int m = 0; m < P; m++) {
+                const double2 v = xch[b][lc.rd_base[pass] + m * Tn];
+                xr[b][m] = v.x; xi[b][m] = v.y;
+            }
+    }
+    // register m holds the frequency whose top digit is brev(m): hand the registers back in frequency order
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        double yr[P], yi[P];
+#pragma unroll
+        for (int m = 0; m < P; m++) { yr[brev(m, LOGP)] = xr[b][m]; yi[brev(m, LOGP)] = xi[b][m]; }
+#pragma unroll
+        for (int m = 0; m < P; m++) { xr[b][m] = yr[m]; xi[b][m] = yi[m]; }
+    }
+}
+
+// The same through ONE exchange buffer, software-pipelined like forward_pipelined().
+template <class PL, int NB>
+__device__ __forceinline__ void forward_nodes_pipelined(const LaneCtx<PL> &lc, double (&xr)[NB][PL::P], double (&xi)[NB][PL::P])
+{
+    constexpr int P = PL::P, K = PL::K, LOGP = PL::LOGP;
+#pragma unroll
+    for (int pass = 0; pass < K; pass++) {
+        CosTan e[P / 2];
+        node_entries<PL>(lc, pass, e);
+        const int Tn = pass < K - 1 ? ipow(P, K - 2 - pass) : 1;
+#pragma unroll
+        for (int b = 0; b < NB; b++) {
+            node_pass<P>(xr[b], xi[b], e);
+            if (pass < K - 1) {
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < P; m++) lc.xch[brev(m, LOGP) * PL::XROW + lc.t] = make_double2(xr[b][m], xi[b][m]);
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < P; m++) {
+                    const double2 v = lc.xch[lc.rd_base[pass] + m * Tn];
+                    xr[b][m] = v.x; xi[b][m] = v.y;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < NB; b++) {
+        double yr[P], yi[P];
+#pragma unroll
+        for (int m = 0; m < P; m++) { yr[brev(m, LOGP)] = xr[b][m]; yi[brev(m, LOGP)] = xi[b][m]; }
+#pragma unroll
+        for (int m = 0; m < P; m++) { xr[b][m] = yr[m]; xi[b][m] = yi[m]; }
+    }
+}
+
 // Forward transform of NB independent polynomials held by the same lanes (NB register sets, NB
 // exchange buffers); their passes are written side by side so that one set's arithmetic can fill the
 // other's LDS round trips.  In: xr/xi[b][m] = u_{t + L*m} (folded, not yet twisted).  Out: spectra in
@@ -221,6 +418,7 @@ __device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const 
                                           double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
+    if constexpr (TwTable<PL>::NODE_FORWARD) { forward_nodes<PL, NB>(lc, xch, xr, xi); return; }
     // register-dependent part of the twist: psi^(L*m) = exp(i*pi*m/(2P))
 #pragma unroll
     for (int b = 0; b < NB; b++)
@@ -278,6 +476,7 @@ template <class PL, int NB>
 __device__ __forceinline__ void forward_pipelined(const LaneCtx<PL> &lc, double (&xr)[NB][PL::P], double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
+    if constexpr (TwTable<PL>::NODE_FORWARD) { forward_nodes_pipelined<PL, NB>(lc, xr, xi); return; }
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
