@@ -193,8 +193,9 @@ def network(ctx_factory):
 
 
 def cmux_level(ctx_factory, count: int = 4096, reps: int = 5):
-    """Leveled mode: one level of `count` independent CMuxes (TRGSW selector x TRLWE data) at N=1024; the kernel's
-    time from the library's HIP events, and a check that every output carries the selected branch's message."""
+    """Leveled mode: one level of `count` independent CMuxes (TRGSW selector x TRLWE data) at the context's ring degree
+    (1024, or Section 4's N-bar = 2048); the kernel's time from the library's HIP events, and a check that every
+    output carries the selected branch's message."""
     import numpy as np
 
     ctx = ctx_factory(16)
@@ -219,10 +220,12 @@ def cmux_level(ctx_factory, count: int = 4096, reps: int = 5):
         assert np.array_equal(phases[k] > 0, want.astype(np.int32) > 0), "CMux selected the wrong branch"
     ctx.close()
     best = float(np.median(ms))
-    flop = 0.258e6 * count                      # the same count per CMux as one step of the blind rotation
+    # per CMux 8 transforms of N/2 complex points (5 (N/2) log2(N/2) + 6 (N/2) flops) and 12 (N/2) complex multiply-adds:
+    # 0.258 MFLOP at N = 1024 (one step of the blind rotation), 0.557 MFLOP at N = 2048
+    flop = (8 * (5 * (N // 2) * int(np.log2(N // 2)) + 6 * (N // 2)) + 12 * (N // 2) * 8) * count
     # bytes that must move: two TRLWE operands in, one out (8 KiB each) per CMux, every distinct selector (96 KiB) once
     moved = count * 3 * 2 * N * 4 + nsel * 2 * 3 * 2 * (N // 2) * 16
-    return {"workload": f"one level of {count} CMuxes over {nsel} distinct selectors, N=1024 l=3 Bgbit=7 "
+    return {"workload": f"one level of {count} CMuxes over {nsel} distinct selectors, N={N} l=3 Bgbit=7 "
                         "(leveled mode: no bootstrap)",
             "kernel_ms": best, "cmux_per_s": count / (best * 1e-3), "achieved_tflops": flop / (best * 1e-3) / 1e12,
             "algorithmic_bytes": moved, "achieved_gb_per_s": moved / (best * 1e-3) / 1e9}
@@ -256,7 +259,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU path)"
     torch.cuda.set_device(0)
     if args.leveled_only:
-        print(json.dumps({"cmux_level": cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), reps=args.steps)}))
+        print(json.dumps({"cmux_level": cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), reps=args.steps),
+                          "cmux_level_section4_2048": cmux_level(lambda cap: she.Context(she.SECTION4_LEVELED, S.KEY_SEED, cap),
+                                                                 reps=args.steps)}))
         return
     G = GATES_PER_LEVEL
     bits, codes = S.cfg2_real_level(G)
@@ -354,6 +359,8 @@ def main():
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)
+        # the ring degree of the paper's leveled setting (Section 4: n = 500, N-bar = 2048)
+        out["cmux_level_section4_2048"] = cmux_level(lambda cap: she.Context(she.SECTION4_LEVELED, S.KEY_SEED, cap))
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["cpu_baseline_single_thread"] = cpu_baseline(args.cpu_sample_gates)
     print(json.dumps(out))

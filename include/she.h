@@ -45,7 +45,8 @@ typedef struct she_ctx she_ctx; /* opaque: keys (secret ones too), device buffer
 /* TFHE parameter set (Section 4, "TFHE setting", names the three sample levels; the
  * gate-bootstrapping values used by the benchmarks are n=630, N=1024, k=1, bg_bit=7,
  * l=3, ks_t=8, ks_basebit=2, lwe_std=2^-15, bk_std=2^-25).  Supported: k = 1;
- * N in {256, 512, 1024}; 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8, 2*l*N*Bg^2 <= 2^32 and l*N*Bg <= 2^20; ks_t*ks_basebit
+ * N in {256, 512, 1024, 2048} (2048, the N-bar of Section 4's leveled setting, for the leveled calls only: the gate and
+ * layer-operator calls return SHE_EINVAL there); 1 <= n <= 4096; l*bg_bit <= 31 with l <= 8, 2*l*N*Bg^2 <= 2^32 and l*N*Bg <= 2^20; ks_t*ks_basebit
  * <= 16 with ks_basebit <= 4.  The two gadget bounds belong to the FP64 polynomial products: the second keeps every sum
  * of products below 2^51 whatever the digits and key words are, which the rounding step needs; under the first the
  * transforms' rounding errors stay far below 1/2 for digits and key words as they occur (measured, largest distance
@@ -256,6 +257,8 @@ int she_plan_relu_maxpool(uint32_t H, uint32_t W, uint32_t C, uint32_t bits, int
 
 /* ---- leveled mode (Section 4, "TFHE setting": the three sample levels TLWE / TRLWE / TRGSW used
  * without bootstrapping) ----
+ * Ring degrees: every supported N, including Section 4's N-bar = 2048 (with that section's n = 500 or any other n;
+ * the leveled calls use the ring key only).
  * Selector bits are TRGSW samples, data are TRLWE samples of torus polynomials, and the one
  * homomorphic operation is the CMux  out = d0 + C [.] (d1 - d0)  (the external product of the
  * blind rotation's inner step): out carries d1's message if C encrypts 1 and d0's if 0, and the

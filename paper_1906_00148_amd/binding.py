@@ -40,6 +40,7 @@ class Params:
 
 TOY = Params(n=128, N=256)
 REAL = Params(n=630, N=1024)
+SECTION4_LEVELED = Params(n=500, N=2048)   # Section 4's leveled setting (TLWE n = 500, N-bar = 2048): CMux levels only
 
 _lib = None
 

@@ -58,7 +58,20 @@ template <int LOGP_, int K_> struct Plan {
     static constexpr int XROW = L + 1;                // padded row of the exchange buffer, 16-byte slots
                                                       // (measured: +0 costs 18 %, +8 17 %, +2 +3 +4 +5 +9 are no better than +1)
     static constexpr int XSLOTS = P * XROW;           // exchange slots per transform
+    static constexpr int XP = P;                      // points that one exchange moves per lane
+    static constexpr bool NODES = false;              // radix-P passes below; true: node-ordered stages (Plan2048)
     static_assert(L >= 1 && L <= 64 && 64 % L == 0, "one transform must fit a wavefront");
+};
+
+// Ring degree 2048: M = 1024 complex points, 16 per lane on 64 lanes, which is not a power of the radix.  The top
+// position bit stays in the register index for the whole transform: the first pass couples the two halves and then
+// each half of 512 points (8 registers) goes through the two exchanges of the 512-point plan on its own, through the
+// same buffer one after the other.  All stages are the node-ordered butterflies described below.
+struct Plan2048 {
+    static constexpr int LOGP = 4, P = 16, K = 3, M = 1024, N = 2048, L = 64, GPW = 1;
+    static constexpr int XP = 8, LOGXP = 3;           // one half
+    static constexpr int XROW = L + 1, XSLOTS = XP * XROW;
+    static constexpr bool NODES = true;
 };
 
 // ---- radix-P DFT on registers ------------------------------------------------------------
@@ -154,20 +167,21 @@ __device__ __forceinline__ void wave_lds_fence()
 //   s = 0: exp(i*pi*t*(1+4k)/N)                    (twist psi^t merged with the first pass)
 //   s > 0: exp(2*pi*i*k*(t mod T)/(P*T)), T = P^(K-1-s)
 // which depends on t only through t mod T, so pass s stores P*T entries: [k][t mod T].
-// Plans with a node-ordered forward transform (below) append its table: rows of P/2 entries (cos, tan), one row per
-// value of the node index that the lane contributes, for every pass after the first.
 template <class PL> struct TwTable {
     static constexpr int period(int s) { return ipow(PL::P, PL::K - 1 - s); }              // T of pass s
     static constexpr int offset(int s) { return s == 0 ? 0 : offset(s - 1) + PL::P * period(s - 1); }
-    static constexpr int COUNT_PASSES = PL::K > 1 ? offset(PL::K - 1) : 1;                   // complex entries
-    // node-ordered forward transform: only written out for three passes of radix 8 (N = 1024)
-    static constexpr bool NODE_FORWARD = PL::LOGP == 3 && PL::K == 3;
-    static constexpr int ROW = PL::P / 2;                                                    // entries per lane and pass
-    static constexpr int node_offset(int pass) { return COUNT_PASSES + (pass == 1 ? 0 : ROW * PL::P); }   // pass 1, pass 2
-    static constexpr int COUNT = COUNT_PASSES + (NODE_FORWARD ? ROW * PL::P + ROW * PL::P * PL::P : 0);
+    static constexpr int COUNT = PL::K > 1 ? offset(PL::K - 1) : 1;                          // complex entries
 };
 
-// ---- node-ordered forward transform ------------------------------------------------------------------------------
+// Plan2048: rows of four entries (cos, tan) per value R of the node index that lane and half contribute:
+// 16 rows for the second pass (stages 4-6), 128 rows for the third (stages 7-9).
+template <> struct TwTable<Plan2048> {
+    static constexpr int ROW = 4;
+    static constexpr int node_offset(int pass) { return pass == 1 ? 0 : 16 * ROW; }
+    static constexpr int COUNT = 16 * ROW + 128 * ROW;
+};
+
+// ---- node-ordered transform (used by Plan2048) -----------------------------------------------------------------
 // The same transform X_k = sum_j u_j exp(2*pi*i*j*(4k+1)/(4M)) computed as m = log2(M) stages of radix-2 butterflies
 // (a, b) -> (a + w b, a - w b) on positions j, j + M/2^(s+1) (stage s = 0..m-1), in place.  Splitting the sum by the
 // top bit of j shows that the two halves are again sums of this form, of half the length, with the shift 1/4 replaced
@@ -181,8 +195,11 @@ template <class PL> struct TwTable {
 // position bits in the first pass and the exchanges of forward_n(), pass p's node index is r = R + (bits fixed inside
 // the pass) * 2^(p*log2 P), R given by the lane; a lane needs P/2 entries per pass: for stage e of the pass, entry
 // w(p*log2 P + e, R + 2^(p*log2 P) * (index of the node among those of the stage, most recent bit dropped)).
-// The first pass has R = 0: compile-time constants.  Spectra land in the lane and register that forward_n() and
-// inverse_n() use, so the two forward transforms are interchangeable.
+// The first pass has R = 0: compile-time constants.  The inverse transform undoes the stages in reverse order:
+// (y0, y1) -> (y0 + y1, conj(w) (y0 - y1)), eight instructions, the factor 1/2 per stage collected into one 1/M.
+// (For N = 1024 the forward half of this was built into the radix-8 plan and measured: 216 instead of 243 FP64
+// instructions per transform, bit-exact, but 0.5-1 % slower, because its fused multiply-adds take three vector
+// registers each, which issue about 17 % slower than the additions that dominate the radix-8 passes.)
 struct CosTan { double c, t; };
 __host__ __device__ inline long double node_angle(int s, int r)       // of w(s, r), in units of pi
 {
@@ -219,7 +236,11 @@ __host__ __device__ __forceinline__ void node_butterfly(double &ar, double &ai, 
 
 // One pass: log2(P) stages on the P points of a lane; register index = the pass's position bits, top bit first fixed.
 // e[] = the lane's P/2 entries in stage order (1, 1, 2, 4, ... per stage).
-template <int P> __host__ __device__ __forceinline__ void node_pass(double (&xr)[P], double (&xi)[P], const CosTan (&e)[P / 2])
+struct NoEmit { __host__ __device__ void operator()(int) const {} };
+// `done(m)` is called for each register as soon as the last stage has produced it (the exchange stores go there, so that
+// they overlap the remaining butterflies).
+template <int P, class EMIT = NoEmit>
+__host__ __device__ __forceinline__ void node_pass(double (&xr)[P], double (&xi)[P], const CosTan (&e)[P / 2], EMIT done = EMIT())
 {
     constexpr int LOGP = __builtin_ctz(P);
 #pragma unroll
@@ -238,6 +259,43 @@ template <int P> __host__ __device__ __forceinline__ void node_pass(double (&xr)
             for (int j = 0; j < half; j++) {
                 if (rot) node_butterfly<true>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
                 else node_butterfly<false>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
+                if (st == LOGP - 1) { done(base + j); done(base + j + half); }
+            }
+        }
+    }
+}
+
+// a = y0 + y1, b = conj(w) * (y0 - y1) (twice the forward pass's inputs), w as in node_butterfly
+template <bool ROT>
+__host__ __device__ __forceinline__ void node_butterfly_inverse(double &ar, double &ai, double &br, double &bi, double c, double t)
+{
+    const double dr = ar - br, di = ai - bi;
+    ar += br; ai += bi;
+    const double gr = __builtin_fma(t, di, dr), gi = __builtin_fma(-t, dr, di);          // (1 - i*t) * d
+    if (!ROT) { br = c * gr; bi = c * gi; }
+    else      { br = c * gi; bi = -c * gr; }                                             // conj(i*w) = -i * conj(w)
+}
+
+// The mirror of node_pass: last stage first.
+template <int P>
+__host__ __device__ __forceinline__ void node_pass_inverse(double (&xr)[P], double (&xi)[P], const CosTan (&e)[P / 2])
+{
+    constexpr int LOGP = __builtin_ctz(P);
+#pragma unroll
+    for (int st = LOGP - 1; st >= 0; st--) {
+        const int half = P >> (st + 1);
+#pragma unroll
+        for (int base = 0; base < P; base += 2 * half) {
+            const int fixed = base / (2 * half);
+            int rev = 0;
+            for (int i = 0; i < st; i++) rev |= ((fixed >> (st - 1 - i)) & 1) << i;
+            const bool rot = st > 0 && ((rev >> (st - 1)) & 1);
+            const int idx = st > 0 ? (rev & ((1 << (st - 1)) - 1)) : 0;
+            const CosTan w = e[st == 0 ? 0 : (1 << (st - 1)) + idx];
+#pragma unroll
+            for (int j = 0; j < half; j++) {
+                if (rot) node_butterfly_inverse<true>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
+                else node_butterfly_inverse<false>(xr[base + j], xi[base + j], xr[base + j + half], xi[base + j + half], w.c, w.t);
             }
         }
     }
@@ -245,6 +303,23 @@ template <int P> __host__ __device__ __forceinline__ void node_pass(double (&xr)
 
 template <class PL> inline void make_twiddles(double *out /* [TwTable::COUNT][2] */)
 {
+    if constexpr (PL::NODES) {
+        // pass p = 1, 2 (stages s0 = 3p+1 ...): row R holds w(s0, R), w(s0+1, R), w(s0+2, R), w(s0+2, R + 2^s0)
+        const long double pi = 3.14159265358979323846264338327950288L;
+        for (int pass = 1; pass <= 2; pass++) {
+            const int s0 = 3 * pass + 1, rows = 1 << s0;
+            for (int R = 0; R < rows; R++) {
+                double *row = out + 2 * ((size_t)TwTable<PL>::node_offset(pass) + (size_t)R * TwTable<PL>::ROW);
+                const int st[4] = {s0, s0 + 1, s0 + 2, s0 + 2}, rr[4] = {R, R, R, R + rows};
+                for (int q = 0; q < 4; q++) {
+                    const long double ang = pi * node_angle(st[q], rr[q]);
+                    row[2 * q] = (double)cosl(ang);
+                    row[2 * q + 1] = (double)tanl(ang);
+                }
+            }
+        }
+        return;
+    } else {
     const long double pi = 3.14159265358979323846264338327950288L;
     for (int s = 0; s + 1 < PL::K; s++) {
         const int T = TwTable<PL>::period(s);
@@ -257,24 +332,6 @@ template <class PL> inline void make_twiddles(double *out /* [TwTable::COUNT][2]
                 o[1] = (double)sinl(ang);
             }
     }
-    if constexpr (TwTable<PL>::NODE_FORWARD) {
-        // pass p (1, 2): row per lane value R; entries of stage e: w(p*LOGP + e, R + 2^(p*LOGP) * i), i < max(1, 2^(e-1))
-        constexpr int P = PL::P, LOGP = PL::LOGP, ROW = TwTable<PL>::ROW;
-        for (int pass = 1; pass < PL::K; pass++) {
-            const int rows = ipow(P, pass), s0 = pass * LOGP;
-            for (int lane_part = 0; lane_part < rows; lane_part++) {
-                // pass 1: R = k0 = the row; pass 2: the lane is 8*k0 + k1 and R = k0 + 8*k1
-                const int R = pass == 1 ? lane_part : (lane_part / P) + P * (lane_part % P);
-                double *row = out + 2 * ((size_t)TwTable<PL>::node_offset(pass) + (size_t)lane_part * ROW);
-                for (int e = 0; e < LOGP; e++)
-                    for (int i = 0; i < (e == 0 ? 1 : 1 << (e - 1)); i++) {
-                        const long double ang = pi * node_angle(s0 + e, R + (1 << s0) * i);
-                        const int slot = e == 0 ? 0 : (1 << (e - 1)) + i;
-                        row[2 * slot] = (double)cosl(ang);
-                        row[2 * slot + 1] = (double)tanl(ang);
-                    }
-            }
-        }
     }
 }
 
@@ -293,9 +350,9 @@ template <class PL> struct LaneCtx {
         tw = tw_lds;
 #pragma unroll
         for (int s = 0; s < PL::K - 1; s++) {
-            const int Ts = ipow(PL::P, PL::K - 1 - s);       // sub-transform length after pass s
-            const int Tn = Ts / PL::P;
-            const int q = t / Tn, tn = t % Tn, ks = q % PL::P, kap = q / PL::P;
+            const int Ts = ipow(PL::XP, PL::K - 1 - s);      // sub-transform length after pass s
+            const int Tn = Ts / PL::XP;
+            const int q = t / Tn, tn = t % Tn, ks = q % PL::XP, kap = q / PL::XP;
             rd_base[s] = ks * PL::XROW + tn + Ts * kap;
         }
     }
@@ -314,98 +371,124 @@ template <class PL> __device__ __forceinline__ void load_twiddles(double2 *lds, 
     __syncthreads();
 }
 
-// The lane's entries of one pass of the node-ordered forward transform: constants in the first pass, one table row
-// (requested together, ahead of the butterflies) in the others.
-template <class PL> __device__ __forceinline__ void node_entries(const LaneCtx<PL> &lc, int pass, CosTan (&e)[PL::P / 2])
+// ---- Plan2048: node-ordered transforms on two halves -------------------------------------------------------------
+// Register m = 8h + m8 holds position t + 64 m: h is the top position bit (the lowest frequency bit once the first
+// stage has run), m8 the next three.  After the transform lane t = 8 k0 + k1, register 8h + k2 holds the frequency
+// k = h + 2 k0 + 16 k1 + 128 k2.
+template <class PL> __device__ __forceinline__ void half_entries(const LaneCtx<PL> &lc, int pass, int h, CosTan (&e)[4])
 {
-    constexpr int P = PL::P, ROW = P / 2;
-    if (pass == 0) {
+    // node index that the lane and the half contribute: pass 1: h + 2 k0; pass 2: h + 2 k0 + 16 k1
+    const int R = pass == 1 ? h + 2 * (lc.t >> 3) : h + 2 * (lc.t >> 3) + 16 * (lc.t & 7);
+    const double2 *row = lc.tw + TwTable<PL>::node_offset(pass) + 4 * R;
 #pragma unroll
-        for (int st = 0; st < PL::LOGP; st++)
-#pragma unroll
-            for (int i = 0; i < (st == 0 ? 1 : 1 << (st - 1)); i++) e[st == 0 ? 0 : (1 << (st - 1)) + i] = first_pass_entry(st, i);
-    } else {
-        const int lane_part = lc.t / ipow(P, PL::K - 1 - pass);
-        const double2 *row = lc.tw + TwTable<PL>::node_offset(pass) + ROW * lane_part;
-#pragma unroll
-        for (int i = 0; i < ROW; i++) { const double2 v = row[i]; e[i].c = v.x; e[i].t = v.y; }
-    }
+    for (int i = 0; i < 4; i++) { const double2 v = row[i]; e[i].c = v.x; e[i].t = v.y; }
 }
 
-// Node-ordered forward transform of NB polynomials side by side (see node_pass): same input and output layout as
-// forward_n()'s other branch.
-template <class PL, int NB>
-__device__ __forceinline__ void forward_nodes(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
-                                              double (&xi)[NB][PL::P])
+__host__ __device__ __forceinline__ void first_pass_entries16(CosTan (&e)[8])
 {
-    constexpr int P = PL::P, K = PL::K, LOGP = PL::LOGP;
 #pragma unroll
-    for (int pass = 0; pass < K; pass++) {
-        CosTan e[P / 2];
-        node_entries<PL>(lc, pass, e);
+    for (int st = 0; st < 4; st++)
 #pragma unroll
-        for (int b = 0; b < NB; b++) node_pass<P>(xr[b], xi[b], e);
-        if (pass == K - 1) break;
-        wave_lds_fence();
+        for (int i = 0; i < (st == 0 ? 1 : 1 << (st - 1)); i++) e[st == 0 ? 0 : (1 << (st - 1)) + i] = first_pass_entry(st, i);
+}
+
+template <class PL, int NB>
+__device__ __forceinline__ void forward_halves(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                               double (&xi)[NB][PL::P])
+{
+    constexpr int H = PL::XP, LOGH = PL::LOGXP;
+    static_assert(PL::P == 2 * H && PL::K == 3, "two halves, three passes");
+    {
+        CosTan e0[8];
+        first_pass_entries16(e0);
 #pragma unroll
-        for (int b = 0; b < NB; b++)
+        for (int b = 0; b < NB; b++) node_pass<16>(xr[b], xi[b], e0);
+    }
 #pragma unroll
-            for (int m = 0; m < P; m++)                      // row = the bits fixed in this pass, first fixed lowest
-                xch[b][brev(m, LOGP) * PL::XROW + lc.t] = make_double2(xr[b][m], xi[b][m]);
-        wave_lds_fence();
-        const int Tn = ipow(P, K - 2 - pass);
+    for (int pass = 1; pass < 3; pass++) {
+        const int Tn = ipow(H, 2 - pass);                    // 8 after the first pass, 1 after the second
 #pragma unroll
-        for (int b = 0; b < NB; b++)
+        for (int h = 0; h < 2; h++) {
+            CosTan e[4];
+            half_entries<PL>(lc, pass, h, e);                // requested before the exchange: they arrive with it
 #pragma unroll
-            for (int m = 0; m < P; m++) {
-                const double2 v = xch[b][lc.rd_base[pass] + m * Tn];
-                xr[b][m] = v.x; xi[b][m] = v.y;
+            for (int b = 0; b < NB; b++) {
+                double(&r)[H] = *reinterpret_cast<double(*)[H]>(&xr[b][H * h]);
+                double(&i)[H] = *reinterpret_cast<double(*)[H]>(&xi[b][H * h]);
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < H; m++) xch[b][brev(m, LOGH) * PL::XROW + lc.t] = make_double2(r[m], i[m]);
+                wave_lds_fence();
+#pragma unroll
+                for (int m = 0; m < H; m++) {
+                    const double2 v = xch[b][lc.rd_base[pass - 1] + m * Tn];
+                    r[m] = v.x; i[m] = v.y;
+                }
+                node_pass<H>(r, i, e);
             }
+        }
     }
-    // register m holds the frequency whose top digit is brev(m): hand the registers back in frequency order
+    // register m8 of a half holds the frequency whose top digit is brev(m8): hand them back in frequency order
 #pragma unroll
-    for (int b = 0; b < NB; b++) {
-        double yr[P], yi[P];
+    for (int b = 0; b < NB; b++)
 #pragma unroll
-        for (int m = 0; m < P; m++) { yr[brev(m, LOGP)] = xr[b][m]; yi[brev(m, LOGP)] = xi[b][m]; }
+        for (int h = 0; h < 2; h++) {
+            double yr[H], yi[H];
 #pragma unroll
-        for (int m = 0; m < P; m++) { xr[b][m] = yr[m]; xi[b][m] = yi[m]; }
-    }
+            for (int m = 0; m < H; m++) { yr[brev(m, LOGH)] = xr[b][H * h + m]; yi[brev(m, LOGH)] = xi[b][H * h + m]; }
+#pragma unroll
+            for (int m = 0; m < H; m++) { xr[b][H * h + m] = yr[m]; xi[b][H * h + m] = yi[m]; }
+        }
 }
 
-// The same through ONE exchange buffer, software-pipelined like forward_pipelined().
+// The exact mirror; out: xr/xi[b][m] = u_{t + 64 m} (the factor 1/M applied at the end, a power of two).
 template <class PL, int NB>
-__device__ __forceinline__ void forward_nodes_pipelined(const LaneCtx<PL> &lc, double (&xr)[NB][PL::P], double (&xi)[NB][PL::P])
+__device__ __forceinline__ void inverse_halves(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                               double (&xi)[NB][PL::P])
 {
-    constexpr int P = PL::P, K = PL::K, LOGP = PL::LOGP;
+    constexpr int H = PL::XP, LOGH = PL::LOGXP;
 #pragma unroll
-    for (int pass = 0; pass < K; pass++) {
-        CosTan e[P / 2];
-        node_entries<PL>(lc, pass, e);
-        const int Tn = pass < K - 1 ? ipow(P, K - 2 - pass) : 1;
+    for (int b = 0; b < NB; b++)
 #pragma unroll
-        for (int b = 0; b < NB; b++) {
-            node_pass<P>(xr[b], xi[b], e);
-            if (pass < K - 1) {
+        for (int h = 0; h < 2; h++) {
+            double yr[H], yi[H];
+#pragma unroll
+            for (int m = 0; m < H; m++) { yr[m] = xr[b][H * h + brev(m, LOGH)]; yi[m] = xi[b][H * h + brev(m, LOGH)]; }
+#pragma unroll
+            for (int m = 0; m < H; m++) { xr[b][H * h + m] = yr[m]; xi[b][H * h + m] = yi[m]; }
+        }
+#pragma unroll
+    for (int pass = 2; pass >= 1; pass--) {
+        const int Tn = ipow(H, 2 - pass);
+#pragma unroll
+        for (int h = 0; h < 2; h++) {
+            CosTan e[4];
+            half_entries<PL>(lc, pass, h, e);
+#pragma unroll
+            for (int b = 0; b < NB; b++) {
+                double(&r)[H] = *reinterpret_cast<double(*)[H]>(&xr[b][H * h]);
+                double(&i)[H] = *reinterpret_cast<double(*)[H]>(&xi[b][H * h]);
+                node_pass_inverse<H>(r, i, e);
+                wave_lds_fence();                            // undo the transposition that preceded this pass
+#pragma unroll
+                for (int m = 0; m < H; m++) xch[b][lc.rd_base[pass - 1] + m * Tn] = make_double2(r[m], i[m]);
                 wave_lds_fence();
 #pragma unroll
-                for (int m = 0; m < P; m++) lc.xch[brev(m, LOGP) * PL::XROW + lc.t] = make_double2(xr[b][m], xi[b][m]);
-                wave_lds_fence();
-#pragma unroll
-                for (int m = 0; m < P; m++) {
-                    const double2 v = lc.xch[lc.rd_base[pass] + m * Tn];
-                    xr[b][m] = v.x; xi[b][m] = v.y;
+                for (int m = 0; m < H; m++) {
+                    const double2 v = xch[b][brev(m, LOGH) * PL::XROW + lc.t];
+                    r[m] = v.x; i[m] = v.y;
                 }
             }
         }
     }
+    CosTan e0[8];
+    first_pass_entries16(e0);
+    constexpr double scale = 1.0 / (double)PL::M;
 #pragma unroll
     for (int b = 0; b < NB; b++) {
-        double yr[P], yi[P];
+        node_pass_inverse<16>(xr[b], xi[b], e0);
 #pragma unroll
-        for (int m = 0; m < P; m++) { yr[brev(m, LOGP)] = xr[b][m]; yi[brev(m, LOGP)] = xi[b][m]; }
-#pragma unroll
-        for (int m = 0; m < P; m++) { xr[b][m] = yr[m]; xi[b][m] = yi[m]; }
+        for (int m = 0; m < PL::P; m++) { xr[b][m] *= scale; xi[b][m] *= scale; }
     }
 }
 
@@ -414,11 +497,10 @@ __device__ __forceinline__ void forward_nodes_pipelined(const LaneCtx<PL> &lc, d
 // other's LDS round trips.  In: xr/xi[b][m] = u_{t + L*m} (folded, not yet twisted).  Out: spectra in
 // the lane/register order that inverse_n() and the pointwise products share.
 template <class PL, int NB>
-__device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
-                                          double (&xi)[NB][PL::P])
+__device__ __forceinline__ void forward_radix(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                              double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
-    if constexpr (TwTable<PL>::NODE_FORWARD) { forward_nodes<PL, NB>(lc, xch, xr, xi); return; }
     // register-dependent part of the twist: psi^(L*m) = exp(i*pi*m/(2P))
 #pragma unroll
     for (int b = 0; b < NB; b++)
@@ -466,6 +548,14 @@ __device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const 
     }
 }
 
+template <class PL, int NB>
+__device__ __forceinline__ void forward_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                          double (&xi)[NB][PL::P])
+{
+    if constexpr (PL::NODES) forward_halves<PL, NB>(lc, xch, xr, xi);
+    else forward_radix<PL, NB>(lc, xch, xr, xi);
+}
+
 // Forward transforms of NB polynomials through ONE exchange buffer, software-pipelined: within a pass, set b's
 // butterflies are followed at once by its exchange (twiddle products, stores, loads), then set b+1's butterflies
 // and exchange, and so on.  A wavefront's LDS operations execute in issue order, so a set's stores cannot overtake
@@ -476,7 +566,6 @@ template <class PL, int NB>
 __device__ __forceinline__ void forward_pipelined(const LaneCtx<PL> &lc, double (&xr)[NB][PL::P], double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
-    if constexpr (TwTable<PL>::NODE_FORWARD) { forward_nodes_pipelined<PL, NB>(lc, xr, xi); return; }
 #pragma unroll
     for (int b = 0; b < NB; b++)
 #pragma unroll
@@ -525,8 +614,8 @@ __device__ __forceinline__ void forward_pipelined(const LaneCtx<PL> &lc, double 
 // ...); a wavefront's LDS operations execute in issue order, so a set's stores cannot overtake the previous
 // set's loads, and a set's round trip overlaps the arithmetic of the sets before it.
 template <class PL, int NB, bool SHARED = false>
-__device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
-                                          double (&xi)[NB][PL::P])
+__device__ __forceinline__ void inverse_radix(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                              double (&xi)[NB][PL::P])
 {
     constexpr int P = PL::P, K = PL::K;
 #pragma unroll
@@ -591,6 +680,14 @@ __device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const 
             xi[b][m] = i * cr - r * ci;
         }
     }
+}
+
+template <class PL, int NB, bool SHARED = false>
+__device__ __forceinline__ void inverse_n(const LaneCtx<PL> &lc, double2 *const (&xch)[NB], double (&xr)[NB][PL::P],
+                                          double (&xi)[NB][PL::P])
+{
+    if constexpr (PL::NODES) inverse_halves<PL, NB>(lc, xch, xr, xi);
+    else inverse_radix<PL, NB, SHARED>(lc, xch, xr, xi);
 }
 
 // One polynomial at a time.

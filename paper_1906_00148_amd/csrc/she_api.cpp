@@ -133,6 +133,7 @@ int ensure_mux_arrays(she_ctx *c, size_t muxes)
 int enqueue_level_on(she_ctx *c, const LevelWork &W, bool timed, const uint8_t *d_type, const uint32_t *d_in0,
                      const uint32_t *d_in1, const uint32_t *d_out, size_t gates, const uint32_t *d_in2 = nullptr)
 {
+    if (c->P.N > 1024) return fail(c, SHE_EINVAL, "gate bootstrapping is built for N <= 1024; N = 2048 serves the leveled calls");
     const CtSpace cs = space(c);
     LevelTimer *timer = timed ? &c->timer : nullptr;
     if (timed) c->timer_levels++;
@@ -162,6 +163,7 @@ int enqueue_level(she_ctx *c, const uint8_t *d_type, const uint32_t *d_in0, cons
 int enqueue_mux_level(she_ctx *c, const uint8_t *d_jtype, const uint32_t *d_jin0, const uint32_t *d_jin1,
                       const uint32_t *d_out, size_t muxes)
 {
+    if (c->P.N > 1024) return fail(c, SHE_EINVAL, "gate bootstrapping is built for N <= 1024; N = 2048 serves the leveled calls");
     const CtSpace cs = space(c);
     LevelTimer *timer = c->timing ? &c->timer : nullptr;
     const size_t step = MAX_LEVEL_CHUNK / 2;
@@ -202,7 +204,7 @@ int finish_timing(she_ctx *c)
 bool params_supported(const she_params &P, std::string &why)
 {
     if (P.k != 1) { why = "k must be 1"; return false; }
-    if (!plan_supported(P.N)) { why = "N must be 256, 512 or 1024"; return false; }
+    if (!plan_supported(P.N)) { why = "N must be 256, 512, 1024 or 2048"; return false; }
     if (P.n < 1 || P.n > 4096) { why = "n must be in [1, 4096]"; return false; }
     if (P.l < 1 || P.l > 8 || P.bg_bit < 1 || P.l * P.bg_bit > 31) { why = "need 1 <= l <= 8 and l*bg_bit <= 31"; return false; }
     // the FP64 transforms stay exact after rounding only while the products are small enough:

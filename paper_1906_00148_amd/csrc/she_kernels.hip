@@ -517,8 +517,10 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
 // samples in HBM.  One CMux per wavefront; the same decomposition, transforms and products as
 // one step of the blind rotation, with the operands streamed from memory instead of LDS.
 // ------------------------------------------------------------------------------------------
+// With 16 points per lane (N = 2048) the two output spectra and one transform fill the register file: the selector's
+// spectra are then fetched where the products need them instead of a row ahead, and one workgroup runs per compute unit.
 template <class PL, bool TRACK>
-__global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
+__global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
                                                            uint32_t *trlwe, const uint32_t *__restrict__ sel,
                                                            const uint32_t *__restrict__ in1, const uint32_t *__restrict__ in0,
                                                            const uint32_t *__restrict__ out, uint32_t count, uint32_t l,
@@ -547,11 +549,14 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     uint32_t *dst = trlwe + (size_t)out[g] * 2 * N;
     const double2 *rows = trgsw_hat + (size_t)sel[g] * 2 * l * 2 * P * L + t;
 
-    double2 bv[2][P];
+    constexpr bool ROW_AHEAD = P <= 8;
+    double2 bv[2][ROW_AHEAD ? P : 1];
+    if constexpr (ROW_AHEAD) {
 #pragma unroll
-    for (int o = 0; o < 2; o++)
+        for (int o = 0; o < 2; o++)
 #pragma unroll
-        for (int k = 0; k < P; k++) bv[o][k] = rows[(o * P + k) * L];
+            for (int k = 0; k < P; k++) bv[o][k] = rows[(o * P + k) * L];
+    }
 
     double sr[2][P], si[2][P];
 #pragma unroll
@@ -584,16 +589,16 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
             for (int o = 0; o < 2; o++)
 #pragma unroll
                 for (int k = 0; k < P; k++) {
-                    const double2 b = bv[o][k];
+                    const double2 b = ROW_AHEAD ? bv[o][k] : rows[(size_t)r * 2 * P * L + (o * P + k) * L];
                     sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
                     si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
                 }
-            if (r + 1 < 2 * l) {
+            if (ROW_AHEAD && r + 1 < 2 * l) {
                 const double2 *row = rows + (size_t)(r + 1) * 2 * P * L;
 #pragma unroll
                 for (int o = 0; o < 2; o++)
 #pragma unroll
-                    for (int k = 0; k < P; k++) bv[o][k] = row[(o * P + k) * L];
+                    for (int k = 0; k < (ROW_AHEAD ? P : 0); k++) bv[o][k] = row[(o * P + k) * L];
             }
         }
     }
@@ -806,7 +811,8 @@ using Plan256 = Plan<1, 7>;
 using Plan512 = Plan<2, 4>;
 using Plan1024 = Plan<3, 3>;
 
-bool plan_supported(uint32_t N) { return N == 256 || N == 512 || N == 1024; }
+// N = 2048 has transforms, key spectra and the leveled CMux; the blind rotation is built for N <= 1024
+bool plan_supported(uint32_t N) { return N == 256 || N == 512 || N == 1024 || N == 2048; }
 
 template <class PL> static size_t tw_doubles() { return 2 * (size_t)TwTable<PL>::COUNT; }
 
@@ -816,6 +822,7 @@ size_t twiddle_doubles(uint32_t N)
     case 256: return tw_doubles<Plan256>();
     case 512: return tw_doubles<Plan512>();
     case 1024: return tw_doubles<Plan1024>();
+    case 2048: return tw_doubles<Plan2048>();
     }
     return 0;
 }
@@ -826,6 +833,7 @@ void fill_twiddles(uint32_t N, double *out)
     case 256: make_twiddles<Plan256>(out); break;
     case 512: make_twiddles<Plan512>(out); break;
     case 1024: make_twiddles<Plan1024>(out); break;
+    case 2048: make_twiddles<Plan2048>(out); break;
     }
 }
 
@@ -857,9 +865,10 @@ static hipError_t cmux_t(const she_params &P, const DeviceKeys &K, const double2
                          const uint32_t *d_sel, const uint32_t *d_in1, const uint32_t *d_in0, const uint32_t *d_out,
                          size_t count, unsigned *d_round_err, hipStream_t st)
 {
-    // persistent: at most the two workgroups per compute unit that fit, each wavefront loops over its share
+    // persistent: at most the workgroups per compute unit that fit (two; one at N = 2048), each wavefront loops over its share
     const size_t wgs = (count + BR_WAVES - 1) / BR_WAVES;
-    const dim3 grid((unsigned)std::min<size_t>(wgs, (size_t)2 * std::max<uint32_t>(K.cus, 1))), block(64 * BR_WAVES);
+    const size_t per_cu = PL::P > 8 ? 1 : 2;
+    const dim3 grid((unsigned)std::min<size_t>(wgs, per_cu * std::max<uint32_t>(K.cus, 1))), block(64 * BR_WAVES);
     if (d_round_err)
         hipLaunchKernelGGL((k_cmux<PL, true>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
                            (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
@@ -877,6 +886,7 @@ hipError_t launch_trgsw_transform(const she_params &P, const DeviceKeys &K, cons
     case 256: return trgsw_transform_t<Plan256>(P, K, d_int, trgsw_hat, d_ids, samples, st);
     case 512: return trgsw_transform_t<Plan512>(P, K, d_int, trgsw_hat, d_ids, samples, st);
     case 1024: return trgsw_transform_t<Plan1024>(P, K, d_int, trgsw_hat, d_ids, samples, st);
+    case 2048: return trgsw_transform_t<Plan2048>(P, K, d_int, trgsw_hat, d_ids, samples, st);
     }
     return hipErrorInvalidValue;
 }
@@ -890,6 +900,7 @@ hipError_t launch_cmux(const she_params &P, const DeviceKeys &K, const double2 *
     case 256: return cmux_t<Plan256>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
     case 512: return cmux_t<Plan512>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
     case 1024: return cmux_t<Plan1024>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
+    case 2048: return cmux_t<Plan2048>(P, K, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out, count, d_round_err, st);
     }
     return hipErrorInvalidValue;
 }
@@ -900,6 +911,7 @@ hipError_t launch_bk_transform(const she_params &P, const uint32_t *d_bk_int, co
     case 256: return bk_transform_t<Plan256>(P, d_bk_int, K, st);
     case 512: return bk_transform_t<Plan512>(P, d_bk_int, K, st);
     case 1024: return bk_transform_t<Plan1024>(P, d_bk_int, K, st);
+    case 2048: return bk_transform_t<Plan2048>(P, d_bk_int, K, st);
     }
     return hipErrorInvalidValue;
 }

@@ -22,3 +22,11 @@ def toy_keys():
 def real_keys():
     from oracle import tfhe
     return tfhe.keygen(tfhe.REAL, 190600148)
+
+
+@pytest.fixture(scope="session")
+def section4_keys():
+    """The ring degree of the paper's leveled setting (Section 4, "TFHE setting": N-bar = 2048) with a short TLWE key:
+    the leveled operations use the ring key only, and a small n keeps the oracle's key generation cheap."""
+    from oracle import tfhe
+    return tfhe.keygen(tfhe.Params(n=16, N=2048), 190600148)

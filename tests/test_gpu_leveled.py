@@ -206,3 +206,93 @@ def test_leveled_argument_errors(toy_ctx):
         fresh.eval_cmux([0], [1], [2], [3])                  # pools not allocated
     assert e.value.code == -1
     fresh.close()
+
+
+# ------------------------------------------------------------------ Section 4's leveled ring degree, N-bar = 2048
+@pytest.fixture(scope="module")
+def s4_ctx():
+    pkg = she()
+    ctx = pkg.Context(pkg.Params(n=16, N=2048), S.KEY_SEED, 64)
+    ctx.leveled_init(64, 1024)
+    yield ctx
+    ctx.close()
+
+
+@pytest.mark.parametrize("count", [1, 5, 301])
+def test_cmux_level_bit_exact_ring_degree_2048(s4_ctx, section4_keys, count):
+    """One level of CMuxes at N-bar = 2048 (16 points per lane, node-ordered transforms on two halves), ragged counts;
+    every TRLWE word against the oracle, the kernel's largest distance from an integer recorded."""
+    P = section4_keys.params
+    rng = np.random.default_rng(2048 + count)
+    nsel, ndat = 24, 400
+    bits = rng.integers(0, 2, nsel).astype(np.uint8)
+    sel_ids = rng.permutation(64)[:nsel].astype(np.uint32)
+    s4_ctx.trgsw_encrypt_bits(bits, 555, sel_ids)
+    sels = O.trgsw_encrypt_bits(section4_keys, bits, 555)
+    mu = messages(rng, ndat, P.N)
+    dat_ids = np.arange(ndat, dtype=np.uint32)
+    s4_ctx.trlwe_encrypt(mu, 777, dat_ids)
+    data = O.trlwe_encrypt(section4_keys, mu, 777)
+    assert np.array_equal(s4_ctx.trlwe_read(dat_ids[:3]), data[:3])
+    s = rng.integers(0, nsel, count)
+    i1, i0 = rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+    out_ids = (ndat + np.arange(count)).astype(np.uint32)
+    s4_ctx.set_round_tracking(True)
+    s4_ctx.get_round_error(reset=True)
+    s4_ctx.eval_cmux(sel_ids[s], dat_ids[i1], dat_ids[i0], out_ids)
+    worst = s4_ctx.get_round_error()
+    print(f"\nN = 2048, {count} CMuxes: largest distance from an integer {worst:.4f}")
+    assert 0 < worst < 0.2
+    s4_ctx.set_round_tracking(False)
+    got = s4_ctx.trlwe_read(out_ids)
+    phases = s4_ctx.trlwe_phase(out_ids)
+    for m in range(count):
+        assert np.array_equal(got[m], O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])), m
+        chosen = mu[i1[m]] if bits[s[m]] else mu[i0[m]]
+        assert np.array_equal(signed(phases[m]) > 0, signed(chosen) > 0), m
+    s4_ctx.eval_cmux(sel_ids[s], dat_ids[i1], dat_ids[i0], out_ids)                 # tracking off: same words
+    assert np.array_equal(s4_ctx.trlwe_read(out_ids), got)
+
+
+def test_lookup_tree_ring_degree_2048_and_gates_are_refused(s4_ctx, section4_keys):
+    """A 16-row plaintext table addressed by 4 encrypted bits at N-bar = 2048: every word of the root against the
+    oracle's tree, its phase the addressed row.  Gate bootstrapping is not built at this ring degree: refused."""
+    pkg = she()
+    P = section4_keys.params
+    rng = np.random.default_rng(22)
+    table = messages(rng, 16, P.N)
+    rows = O.trlwe_trivial(P, table)
+    addrs = [0, 5, 10, 15]
+    abits = np.array([[(a >> b) & 1 for b in range(4)] for a in addrs], np.uint8)
+    sel_ids = np.arange(len(addrs) * 4, dtype=np.uint32).reshape(len(addrs), 4)
+    s4_ctx.trgsw_encrypt_bits(abits.ravel(), 909, sel_ids.ravel())
+    sels = O.trgsw_encrypt_bits(section4_keys, abits.ravel(), 909).reshape(len(addrs), 4, -1)
+    s4_ctx.trlwe_write(rows, np.arange(16, dtype=np.uint32))
+    cur = [list(range(16)) for _ in addrs]
+    ocur = [list(rows) for _ in addrs]
+    nxt = 16
+    for b in range(4):
+        s, i1, i0, out = [], [], [], []
+        for q in range(len(addrs)):
+            new = []
+            for i in range(len(cur[q]) // 2):
+                s.append(sel_ids[q, b]); i1.append(cur[q][2 * i + 1]); i0.append(cur[q][2 * i]); out.append(nxt)
+                new.append(nxt)
+                nxt += 1
+            ocur[q] = [O.cmux(P, sels[q, b], ocur[q][2 * i + 1], ocur[q][2 * i]) for i in range(len(cur[q]) // 2)]
+            cur[q] = new
+        s4_ctx.eval_cmux(s, i1, i0, out)
+    roots = np.array([c[0] for c in cur], np.uint32)
+    got = s4_ctx.trlwe_read(roots)
+    phases = s4_ctx.trlwe_phase(roots)
+    for q, a in enumerate(addrs):
+        assert np.array_equal(got[q], ocur[q][0]), a
+        assert np.array_equal(signed(phases[q]) > 0, signed(table[a]) > 0), a
+    # keys of this context still match the oracle's (the bootstrapping key went through the 2048 transforms on upload)
+    lwe, ring, bk, ks = s4_ctx.export_keys()
+    assert np.array_equal(ring, section4_keys.ring_key) and np.array_equal(bk, section4_keys.bk)
+    s4_ctx.encrypt_bits([0, 1], 3, [0, 1])
+    assert s4_ctx.decrypt([0, 1]).tolist() == [0, 1]
+    with pytest.raises(pkg.SheError) as e:
+        s4_ctx.eval_gates([0], [0], [1], [2])
+    assert e.value.code == -1 and "N <= 1024" in str(e.value)

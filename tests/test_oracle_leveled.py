@@ -33,6 +33,12 @@ def rand_messages(rng, count, N):
     return np.where(rng.integers(0, 2, (count, N)) == 1, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
 
 
+@pytest.fixture(params=["toy", "section4"])
+def lev_keys(request, toy_keys, section4_keys):
+    """every pin below at the toy ring degree 256 and at Section 4's N-bar = 2048"""
+    return toy_keys if request.param == "toy" else section4_keys
+
+
 def test_fresh_trlwe_phase_is_message_plus_small_noise(toy_keys):
     P = toy_keys.params
     rng = np.random.default_rng(1)
@@ -57,7 +63,8 @@ def test_fresh_trlwe_phase_is_message_plus_small_noise(toy_keys):
     assert np.array_equal(tfhe.trlwe_phase(toy_keys.ring_key, exact), mu[0])
 
 
-def test_fresh_trgsw_rows_have_the_gadget_on_their_component(toy_keys):
+def test_fresh_trgsw_rows_have_the_gadget_on_their_component(lev_keys):
+    toy_keys = lev_keys
     P = toy_keys.params
     s_poly = toy_keys.ring_key.astype(np.uint32)
     for bit in (0, 1):
@@ -81,7 +88,8 @@ def test_fresh_trgsw_rows_have_the_gadget_on_their_component(toy_keys):
     assert not np.array_equal(tfhe.trgsw_encrypt_bits(toy_keys, [0], 5)[0, 0, 0, 0], noisy[1, 0, 0, 0])
 
 
-def test_cmux_invariants(toy_keys):
+def test_cmux_invariants(lev_keys):
+    toy_keys = lev_keys
     P = toy_keys.params
     rng = np.random.default_rng(2)
     d = tfhe.trlwe_encrypt(toy_keys, rand_messages(rng, 2, P.N), 3)
@@ -95,7 +103,8 @@ def test_cmux_invariants(toy_keys):
     assert np.array_equal(tfhe.cmux(P, sel, tiny, d[0]), d[0])
 
 
-def test_cmux_phase_identity_with_noiseless_selector(toy_keys):
+def test_cmux_phase_identity_with_noiseless_selector(lev_keys):
+    toy_keys = lev_keys
     P = toy_keys.params
     N = P.N
     rng = np.random.default_rng(3)
@@ -123,7 +132,8 @@ def test_cmux_phase_identity_with_noiseless_selector(toy_keys):
         assert np.abs(err).max() <= (int(toy_keys.ring_key.sum()) + 1) << (31 - P.l * P.bg_bit)
 
 
-def test_cmux_selects_within_the_noise_bound(toy_keys):
+def test_cmux_selects_within_the_noise_bound(lev_keys):
+    toy_keys = lev_keys
     P = toy_keys.params
     rng = np.random.default_rng(4)
     mus = rand_messages(rng, 2, P.N)
@@ -141,7 +151,8 @@ def test_cmux_selects_within_the_noise_bound(toy_keys):
         assert np.array_equal(signed(tfhe.trlwe_phase(toy_keys.ring_key, out)) > 0, signed(mus[bit]) > 0)
 
 
-def test_lookup_tree_returns_the_addressed_table_entry(toy_keys):
+def test_lookup_tree_returns_the_addressed_table_entry(lev_keys):
+    toy_keys = lev_keys
     # 8 plaintext table rows (noiseless samples), 3 encrypted address bits, 7 CMuxes in 3 levels
     P = toy_keys.params
     rng = np.random.default_rng(5)
