@@ -236,7 +236,10 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
     nl.bind_outputs(out_wires, out_ids);
     const size_t G = nl.type.size(), levels = bounds.size() - 1;
     if (gates_out) *gates_out = G;
-    int rc = ensure_temp(c, (size_t)nl.next_temp - nl.cap);
+    // temporaries share slots by lifetime: the buffer holds the widest set of live wires, not one slot per entry
+    const size_t temp_slots = nl.compact_temporaries(bounds);
+    if (!temp_slots) return fail(c, SHE_EDEVICE, "internal error: a temporary lost its slot while it was live");
+    int rc = ensure_temp(c, temp_slots);
     if (rc) return rc;
     // MUX entries become two rotation jobs each, kept in level order in their own arrays
     std::vector<uint8_t> jt;

@@ -233,6 +233,69 @@ std::vector<size_t> Netlist::levelize(std::vector<size_t> *mux_start)
     return bounds;
 }
 
+// Gives every wire that is still a temporary (after levelize and bind_outputs) a slot of the internal buffer that
+// is free while the wire is live: a slot is handed out when the wire's entry runs and taken back once the level of the
+// wire's last reader has run (entries of one level run side by side, so a slot freed by level v serves level v + 1 at
+// the earliest; a wire that a final copy reads is never freed).  The walk checks itself: every operand must still own
+// its slot when it is read.  Returns the number of slots used (the two constants included), 0 if the check failed.
+size_t Netlist::compact_temporaries(const std::vector<size_t> &bounds)
+{
+    const uint32_t first_temp = cap + 2, none = 0xFFFFFFFFu;
+    const size_t wires = next_temp - first_temp, levels = bounds.size() - 1;
+    auto temp_index = [&](uint32_t ref, size_t &idx) {
+        const uint32_t w = ref & ~WIRE_NEG;
+        if (w < first_temp) return false;
+        idx = w - first_temp;
+        return true;
+    };
+    // last level that reads each wire (levels are 1-based; 0 = never read; levels + 1 = read by a final copy)
+    std::vector<uint32_t> last(wires, 0);
+    size_t idx = 0;
+    for (size_t lv = 0; lv < levels; lv++)
+        for (size_t g = bounds[lv]; g < bounds[lv + 1]; g++) {
+            if (temp_index(in0[g], idx)) last[idx] = (uint32_t)lv + 1;
+            if (temp_index(in1[g], idx)) last[idx] = (uint32_t)lv + 1;
+            if (has_third_operand(type[g]) && temp_index(in2[g], idx)) last[idx] = (uint32_t)lv + 1;
+        }
+    for (uint32_t w : copy_src)
+        if (temp_index(w, idx)) last[idx] = (uint32_t)levels + 1;
+    std::vector<uint32_t> slot(wires, none), owner, free_slots;
+    std::vector<std::vector<uint32_t>> expiring(levels + 2);      // wires whose last reader is in that level
+    bool ok = true;
+    auto rename = [&](uint32_t &ref) {
+        size_t i = 0;
+        if (!temp_index(ref, i)) return;
+        if (slot[i] == none || owner[slot[i]] != i) { ok = false; return; }
+        ref = (first_temp + slot[i]) | (ref & WIRE_NEG);
+    };
+    for (size_t lv = 0; lv < levels; lv++) {
+        // what the level before the previous one read last is free now; so is what nobody reads at all
+        if (lv >= 1)
+            for (uint32_t i : expiring[lv]) free_slots.push_back(slot[i]);
+        for (size_t g = bounds[lv]; g < bounds[lv + 1]; g++) {
+            rename(in0[g]); rename(in1[g]);
+            if (has_third_operand(type[g])) rename(in2[g]);
+        }
+        for (size_t g = bounds[lv]; g < bounds[lv + 1]; g++) {
+            size_t i = 0;
+            if (!temp_index(out[g], i)) continue;                  // bound to a caller's pool slot
+            uint32_t s;
+            if (free_slots.empty()) { s = (uint32_t)owner.size(); owner.push_back(none); }
+            else { s = free_slots.back(); free_slots.pop_back(); }
+            slot[i] = s;
+            owner[s] = (uint32_t)i;
+            out[g] = first_temp + s;
+            // a wire read last in level v frees its slot for level v + 1; an unread wire lives for its own level only
+            const uint32_t until = std::max<uint32_t>(last[i], (uint32_t)lv + 1);
+            if (until <= levels) expiring[until].push_back((uint32_t)i);
+        }
+    }
+    for (uint32_t &w : copy_src) rename(w);
+    if (!ok) return 0;
+    next_temp = first_temp + (uint32_t)owner.size();
+    return owner.size() + 2;
+}
+
 // a + b for equally wide unsigned vectors; one more bit than the operands unless that
 // would exceed cap_bits (then the last carry is not formed and the sum wraps).
 std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const std::vector<uint32_t> &b, uint32_t cap_bits)

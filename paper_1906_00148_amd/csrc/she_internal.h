@@ -144,6 +144,10 @@ struct Netlist {
     // stable sort of the entries by (depth, gates before MUX entries); returns the first index of each
     // level (+ end); mux_start[lv] receives the index of level lv's first MUX entry
     std::vector<size_t> levelize(std::vector<size_t> *mux_start = nullptr);
+    // after levelize and bind_outputs: re-numbers the remaining temporaries so that slots are reused once their last
+    // reader's level has run; `bounds` are levelize's.  Returns the slots needed (constants included), 0 on an
+    // internal inconsistency.
+    size_t compact_temporaries(const std::vector<size_t> &bounds);
 };
 std::vector<uint32_t> nl_add(Netlist &nl, const std::vector<uint32_t> &a, const std::vector<uint32_t> &b, uint32_t cap_bits);
 std::vector<uint32_t> nl_sub(Netlist &nl, const std::vector<uint32_t> &p, const std::vector<uint32_t> &q);
