@@ -518,9 +518,11 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
 // one step of the blind rotation, with the operands streamed from memory instead of LDS.
 // ------------------------------------------------------------------------------------------
 // With 16 points per lane (N = 2048) the two output spectra and one transform fill the register file: the selector's
-// spectra are then fetched where the products need them instead of a row ahead, and one workgroup runs per compute unit.
+// spectra are then fetched where the products need them instead of a row ahead and no operand is requested ahead, which
+// keeps the kernel at 256 registers (8 spilled) and two wavefronts per SIMD: 162 against 282 us per 4096 CMuxes with one.
+// (Both halves of a transform through one LDS round trip, in a buffer of twice the size, spills 31 registers: 214 us.)
 template <class PL, bool TRACK>
-__global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
+__global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
                                                            uint32_t *trlwe, const uint32_t *__restrict__ sel,
                                                            const uint32_t *__restrict__ in1, const uint32_t *__restrict__ in0,
                                                            const uint32_t *__restrict__ out, uint32_t count, uint32_t l,
@@ -542,9 +544,23 @@ __global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const
     for (uint32_t p = 1; p <= l; p++) { dec_off += half_bg << (32 - p * bg_bit); flip |= half_bg << (32 - p * bg_bit); }
     float worst = 0.f;
 
-    // a wavefront takes CMux g, g + (wavefronts in the grid), ...; g is uniform, so the four ids are scalar loads
+    // a wavefront takes CMux g, g + (wavefronts in the grid), ...; g is uniform, so the four ids are scalar loads.
+    // Operands are requested ahead into registers that are idle at that moment: the words of d0 that the result is added
+    // to and component 0 of the NEXT CMux before the inverse transforms (the selector row's registers are free then).
+    // (Requesting component 1's words during component 0's last transform as well spills 86 registers: measured 73
+    // against 55 us per 4096 CMuxes; this version 53 us.)
     const uint32_t stride = gridDim.x * BR_WAVES;
-    for (uint32_t g = __builtin_amdgcn_readfirstlane(blockIdx.x * BR_WAVES + wave); g < count; g += stride) {
+    constexpr int Q = P / 2;
+    constexpr bool AHEAD = P <= 8;                                         // 16 points per lane leave no idle registers
+    uint4 pu[Q], pv[Q];                                                    // requested TRLWE words of d1 and d0
+    uint32_t g = __builtin_amdgcn_readfirstlane(blockIdx.x * BR_WAVES + wave);
+    if (AHEAD && g < count) {
+        const uint4 *a1 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in1[g] * 2 * N) + t;
+        const uint4 *a0 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in0[g] * 2 * N) + t;
+#pragma unroll
+        for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
+    }
+    for (; g < count; g += stride) {
     const uint32_t *d1 = trlwe + (size_t)in1[g] * 2 * N, *d0 = trlwe + (size_t)in0[g] * 2 * N;
     uint32_t *dst = trlwe + (size_t)out[g] * 2 * N;
     const double2 *rows = trgsw_hat + (size_t)sel[g] * 2 * l * 2 * P * L + t;
@@ -566,10 +582,14 @@ __global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const
         // TRLWE samples are stored in transform order: the 16-byte word (q, t) of a component holds the coefficients
         // t + L*2q, t + L*2q + M, t + L*(2q+1), t + L*(2q+1) + M, the ones lane t works on
         uint32_t dlo[P], dhi[P];
-        const uint4 *a1 = reinterpret_cast<const uint4 *>(d1 + c * N) + t, *a0 = reinterpret_cast<const uint4 *>(d0 + c * N) + t;
+        if (c == 1 || !AHEAD) {
+            const uint4 *a1 = reinterpret_cast<const uint4 *>(d1 + c * N) + t, *a0 = reinterpret_cast<const uint4 *>(d0 + c * N) + t;
 #pragma unroll
-        for (int q = 0; q < P / 2; q++) {
-            const uint4 u = a1[q * L], v = a0[q * L];
+            for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
+        }
+#pragma unroll
+        for (int q = 0; q < Q; q++) {
+            const uint4 u = pu[q], v = pv[q];
             dlo[2 * q] = (u.x - v.x + dec_off) ^ flip;
             dhi[2 * q] = (u.y - v.y + dec_off) ^ flip;
             dlo[2 * q + 1] = (u.z - v.z + dec_off) ^ flip;
@@ -602,16 +622,31 @@ __global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const
             }
         }
     }
+    // the words of d0 that the products are added to, and the next CMux's first component (this one's again after the
+    // last: harmless), requested ahead of the inverse transforms
+    uint4 base[2][AHEAD ? Q : 1];
+    if constexpr (AHEAD) {
+#pragma unroll
+        for (int o = 0; o < 2; o++) {
+            const uint4 *a0 = reinterpret_cast<const uint4 *>(d0 + o * N) + t;
+#pragma unroll
+            for (int q = 0; q < Q; q++) base[o][q] = a0[q * L];
+        }
+        const uint32_t gn = g + stride < count ? g + stride : g;
+        const uint4 *a1 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in1[gn] * 2 * N) + t;
+        const uint4 *a0 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in0[gn] * 2 * N) + t;
+#pragma unroll
+        for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
+    }
     {
         double2 *const xch2[2] = {lc.xch, lc.xch};
         inverse_n<PL, 2, true>(lc, xch2, sr, si);
     }
 #pragma unroll
     for (int o = 0; o < 2; o++) {
-        const uint4 *a0 = reinterpret_cast<const uint4 *>(d0 + o * N) + t;
         uint4 *ao = reinterpret_cast<uint4 *>(dst + o * N) + t;
 #pragma unroll
-        for (int q = 0; q < P / 2; q++) {
+        for (int q = 0; q < Q; q++) {
             if (TRACK) {
 #pragma unroll
                 for (int m = 2 * q; m < 2 * q + 2; m++) {
@@ -619,7 +654,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, PL::P > 8 ? 1 : 2) void k_cmux(const
                     worst = fmaxf(worst, (float)fabs(si[o][m] - rint(si[o][m])));
                 }
             }
-            uint4 v = a0[q * L];
+            uint4 v = AHEAD ? base[o][AHEAD ? q : 0] : (reinterpret_cast<const uint4 *>(d0 + o * N) + t)[q * L];
             v.x += (uint32_t)__double2loint(sr[o][2 * q] + 6755399441055744.0);
             v.y += (uint32_t)__double2loint(si[o][2 * q] + 6755399441055744.0);
             v.z += (uint32_t)__double2loint(sr[o][2 * q + 1] + 6755399441055744.0);
@@ -867,7 +902,7 @@ static hipError_t cmux_t(const she_params &P, const DeviceKeys &K, const double2
 {
     // persistent: at most the workgroups per compute unit that fit (two; one at N = 2048), each wavefront loops over its share
     const size_t wgs = (count + BR_WAVES - 1) / BR_WAVES;
-    const size_t per_cu = PL::P > 8 ? 1 : 2;
+    const size_t per_cu = 2;
     const dim3 grid((unsigned)std::min<size_t>(wgs, per_cu * std::max<uint32_t>(K.cus, 1))), block(64 * BR_WAVES);
     if (d_round_err)
         hipLaunchKernelGGL((k_cmux<PL, true>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
