@@ -139,8 +139,10 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
             "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
 
 
-def network(ctx_factory):
-    """A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
+def network(ctx_factory, deferred: bool = False):
+    """deferred: the five operator calls are recorded (she_defer_begin) and run as ONE circuit, so that the scheduler
+    overlaps one operator's last levels with the next one's first.
+    A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
     network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX, three-input cells and the column adder on."""
     import numpy as np
 
@@ -178,9 +180,13 @@ def network(ctx_factory):
     ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
     net = Chain(ctx, x_ids.size)
     t0 = time.perf_counter()
+    if deferred:
+        ctx.defer_begin()
     a = net.relu_maxpool(net.conv(x_ids, w1[0], w1[1], 16))
     b = net.relu_maxpool(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))
     scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
+    if deferred:
+        ctx.defer_run()
     dt = time.perf_counter() - t0
     dec = ctx.decrypt(scores).astype(np.int64)
     got = (dec << np.arange(16)).sum(axis=1)
@@ -188,7 +194,9 @@ def network(ctx_factory):
     assert np.array_equal(got, want), "network decrypts wrongly"
     ctx.close()
     return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
-                        "constant folding, native MUX, three-input cells and column-compression accumulators on", "latency_s": dt, "entries": int(net.gates),
+                        "constant folding, native MUX, three-input cells and column-compression accumulators on"
+                        + (", the five operators run as one deferred circuit" if deferred else ""),
+            "latency_s": dt, "entries": int(net.gates),
             "entries_per_s": net.gates / dt}
 
 
@@ -357,6 +365,7 @@ def main():
         out["conv_layer_lean_columns"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True,
                                                     native_mux=True, cells3=True, fused_pool=True, narrow=True, columns=True)
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
+        out["network_deferred"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), deferred=True)
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)
         # the ring degree of the paper's leveled setting (Section 4: n = 500, N-bar = 2048)

@@ -170,6 +170,24 @@ int she_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uin
 int she_relu_maxpool(she_ctx *ctx, const uint32_t *x_ids, uint32_t H, uint32_t W, uint32_t C, uint32_t bits,
                      const uint32_t *out_ids, uint64_t *gates_out);
 
+/* Section 5 / Table 3 (a network is a sequence of layers C-B-A-P-...; Section 3.1-3.3 lower each layer to gates) and
+ * Section 3.1 (gates that do not depend on each other can be evaluated together).  Between she_defer_begin and
+ * she_defer_run the layer operators (she_shift_acc, she_shift_acc_bias, she_relu, she_maxpool, she_relu_maxpool) only
+ * record their netlists: an operator that reads a slot which a recorded operator writes is wired to that operator's
+ * result.  she_defer_run then schedules ALL recorded entries at their earliest depth level and evaluates each level as
+ * one batch, so the last carries of a layer's adders run beside the first comparator stages of the pooling that
+ * follows, instead of one operator after the other; every recorded output still lands in its pool slot.  The results
+ * are the ciphertexts that the same calls give one by one (identical words without SHE_OPT_FOLD_CONSTANTS; with it
+ * the folding also sees constants across operator boundaries, e.g. the zero sign bit after a ReLU, and may spend
+ * fewer gates).  Rules while recording: an operator's out ids must not be read by an earlier recorded operator as an
+ * input of the circuit, nor be written twice (SHE_EINVAL; the scheduler may reorder such accesses); the options
+ * cannot change; every other call that touches the pool returns SHE_EINVAL.  An operator's *gates_out is the number
+ * of entries it recorded; *entries_out (may be NULL) of she_defer_run the number evaluated; she_last_timing then
+ * covers the whole circuit.  A failed she_defer_run, and an operator that fails with SHE_ENOMEM / SHE_ERANGE while
+ * recording, drop the recorded circuit. */
+int she_defer_begin(she_ctx *ctx);
+int she_defer_run(she_ctx *ctx, uint64_t *entries_out);
+
 /* Section 3.1 (every operator of the network is a circuit of homomorphic gates; "Homomorphic Operations" names the
  * 2-input operations and the MUX).  A whole circuit in one call: ngates entries in topological order, entry g of
  * code type[g] reading the references in0[g], in1[g] (and in2[g] for three-input codes and SHE_CIRCUIT_MUX).  A

@@ -82,6 +82,8 @@ def load_library() -> C.CDLL:
         "she_relu_maxpool": (C.c_int, [ctx, u32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, u32p, u64p]),
         "she_plan_relu_maxpool": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, u64p,
                                             C.POINTER(C.c_uint32), u64p]),
+        "she_defer_begin": (C.c_int, [ctx]),
+        "she_defer_run": (C.c_int, [ctx, u64p]),
         "she_set_option": (C.c_int, [ctx, C.c_int, C.c_int]),
         "she_get_option": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_int)]),
         "she_plan_shift_acc": (C.c_int, [C.c_uint32, C.c_uint32, C.c_uint32, i8p, i8p, C.c_uint32, C.c_int, u64p,
@@ -279,6 +281,15 @@ class Context:
 
     def __exit__(self, *exc):
         self.close()
+
+    def defer_begin(self):
+        self._check(self._L.she_defer_begin(self._h))
+
+    def defer_run(self) -> int:
+        """Evaluates the operators recorded since defer_begin as one circuit; returns the entries evaluated."""
+        n = C.c_uint64(0)
+        self._check(self._L.she_defer_run(self._h, C.byref(n)))
+        return n.value
 
     def set_option(self, option: int, value: int):
         self._check(self._L.she_set_option(self._h, option, value))

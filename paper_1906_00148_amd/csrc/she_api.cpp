@@ -322,9 +322,73 @@ int check_disjoint(she_ctx *c, const uint32_t *ins, size_t n_in, const uint32_t 
     return SHE_OK;
 }
 
+// Runs one layer operator, or records it when a deferred circuit is open.  `build(nl, ids)` appends the operator's
+// entries to nl, reading the wires ids[0..n_in), and returns its n_out output wires.
+template <class BUILD>
+int run_operator(she_ctx *c, const uint32_t *x_ids, size_t n_in, const uint32_t *out_ids, size_t n_out, uint64_t *gates_out,
+                 BUILD build)
+{
+    if (!c->deferred) {
+        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
+        const std::vector<uint32_t> wires = build(nl, x_ids);
+        return run_netlist(c, nl, wires, out_ids, gates_out);
+    }
+    Deferred &d = *c->deferred;
+    // the scheduler is free to run this operator's entries before those of earlier operators that do not feed it: its
+    // outputs must not land in a slot that the circuit reads as it was, nor in one that is already written
+    for (size_t k = 0; k < n_out; k++) {
+        if (d.read[out_ids[k]]) return fail(c, SHE_EINVAL, "deferred circuit: an output id is read by an earlier operator");
+        if (d.produced[out_ids[k]] != Deferred::NONE) return fail(c, SHE_EINVAL, "deferred circuit: an output id is written twice");
+    }
+    try {
+        std::vector<uint32_t> ids(n_in);
+        for (size_t k = 0; k < n_in; k++) {
+            const uint32_t w = d.produced[x_ids[k]];
+            ids[k] = w == Deferred::NONE ? x_ids[k] : w;             // an earlier operator's result: its wire, not its slot
+        }
+        const size_t before = d.nl->type.size();
+        const std::vector<uint32_t> wires = build(*d.nl, ids.data());
+        if (d.nl->overflow) { c->deferred.reset(); return fail(c, SHE_ERANGE, "deferred circuit too large for 31-bit wire ids (dropped)"); }
+        for (size_t k = 0; k < n_in; k++)
+            if (d.produced[x_ids[k]] == Deferred::NONE) d.read[x_ids[k]] = 1;
+        for (size_t k = 0; k < n_out; k++) {
+            d.produced[out_ids[k]] = wires[k];
+            d.out_wires.push_back(wires[k]);
+            d.out_ids.push_back(out_ids[k]);
+        }
+        if (gates_out) *gates_out = d.nl->type.size() - before;
+        return SHE_OK;
+    } catch (...) {
+        c->deferred.reset();                                           // the recorded netlist may be half extended
+        throw;
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+int she_defer_begin(she_ctx *c)
+try {
+    if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
+    std::unique_ptr<Deferred> d(new Deferred);
+    d->nl.reset(new Netlist(c->cap, c->fold, c->native_mux, c->cells3, c->columns));
+    d->produced.assign(c->cap, Deferred::NONE);
+    d->read.assign(c->cap, 0);
+    c->deferred = std::move(d);
+    return SHE_OK;
+} SHE_NOTHROW(c)
+
+int she_defer_run(she_ctx *c, uint64_t *entries_out)
+try {
+    if (!c) return SHE_EINVAL;
+    if (entries_out) *entries_out = 0;
+    if (!c->deferred) return fail(c, SHE_EINVAL, "no deferred circuit is open");
+    std::unique_ptr<Deferred> d = std::move(c->deferred);              // closed whatever happens below
+    if (d->out_ids.empty()) return SHE_OK;
+    return run_netlist(c, *d->nl, d->out_wires, d->out_ids.data(), entries_out);
+} SHE_NOTHROW(c)
 
 int she_keygen(const she_params *params, uint64_t seed, uint32_t pool_capacity, she_ctx **out)
 try {
@@ -425,6 +489,7 @@ void she_free(she_ctx *c)
 int she_encrypt_bits(she_ctx *c, const uint8_t *bits, size_t nbits, uint64_t enc_seed, const uint32_t *dst_ids)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (nbits == 0) return SHE_OK;
     if (!bits || !dst_ids) return fail(c, SHE_EINVAL, "null argument");
     for (size_t k = 0; k < nbits; k++)
@@ -461,6 +526,7 @@ static int fetch(she_ctx *c, const uint32_t *ids, size_t count, std::vector<uint
 int she_decrypt(she_ctx *c, const uint32_t *ids, size_t count, uint8_t *bits_out)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (count == 0) return SHE_OK;
     if (!ids || !bits_out) return fail(c, SHE_EINVAL, "null argument");
     int rc = check_ids(c, ids, count, "she_decrypt");
@@ -475,6 +541,7 @@ int she_eval_gates(she_ctx *c, const uint8_t *type, const uint32_t *in0, const u
                    size_t ngates)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (ngates == 0) return SHE_OK;
     if (!type || !in0 || !in1 || !out) return fail(c, SHE_EINVAL, "null argument");
     for (size_t g = 0; g < ngates; g++)
@@ -501,6 +568,7 @@ int she_eval_gates3(she_ctx *c, const uint8_t *type, const uint32_t *in0, const 
                     const uint32_t *out, size_t ngates)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (ngates == 0) return SHE_OK;
     if (!type || !in0 || !in1 || !in2 || !out) return fail(c, SHE_EINVAL, "null argument");
     for (size_t g = 0; g < ngates; g++)
@@ -530,6 +598,7 @@ int she_eval_gates_device(she_ctx *c, const uint8_t *d_type, const uint32_t *d_i
                           const uint32_t *d_out, size_t ngates)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (ngates == 0) return SHE_OK;
     if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
     int rc = ensure_work(c, std::min<size_t>(ngates, MAX_LEVEL_CHUNK));
@@ -541,6 +610,7 @@ int she_eval_gates_device_noalloc(she_ctx *c, const uint8_t *d_type, const uint3
                                   const uint32_t *d_out, size_t ngates)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (ngates == 0) return SHE_OK;
     if (!d_type || !d_in0 || !d_in1 || !d_out) return fail(c, SHE_EINVAL, "null argument");
     if (!c->na_scratch) return fail(c, SHE_EDEVICE, "the static scratch buffer has no address on this device");
@@ -573,6 +643,7 @@ int she_eval_mux(she_ctx *c, const uint32_t *sel, const uint32_t *in1, const uin
                  size_t nmux)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (nmux == 0) return SHE_OK;
     if (!sel || !in1 || !in0 || !out) return fail(c, SHE_EINVAL, "null argument");
     int rc;
@@ -727,9 +798,9 @@ try {
     if (c->columns && !(c->fold && c->cells3))
         return fail(c, SHE_EINVAL, "SHE_OPT_COLUMN_ADDER needs SHE_OPT_FOLD_CONSTANTS and SHE_OPT_GATE3_CELLS");
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
-        const std::vector<uint32_t> wires = wires_shift_acc(nl, x_ids, units, terms, in_bits, w_sign, w_exp, acc_bits, bias);
-        return run_netlist(c, nl, wires, out_ids, gates_out);
+        return run_operator(c, x_ids, n_in, out_ids, n_out, gates_out, [&](Netlist &nl, const uint32_t *ids) {
+            return wires_shift_acc(nl, ids, units, terms, in_bits, w_sign, w_exp, acc_bits, bias);
+        });
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
@@ -749,9 +820,8 @@ try {
     if ((rc = check_ids(c, out_ids, total, "she_relu out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, total, nullptr, 0, out_ids, total))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
-        const std::vector<uint32_t> wires = wires_relu(nl, x_ids, count, bits);
-        return run_netlist(c, nl, wires, out_ids, gates_out);
+        return run_operator(c, x_ids, total, out_ids, total, gates_out,
+                            [&](Netlist &nl, const uint32_t *ids) { return wires_relu(nl, ids, count, bits); });
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
@@ -772,9 +842,8 @@ try {
     if ((rc = check_ids(c, out_ids, n_out, "she_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
-        const std::vector<uint32_t> wires = wires_maxpool(nl, x_ids, H, W, C, bits);
-        return run_netlist(c, nl, wires, out_ids, gates_out);
+        return run_operator(c, x_ids, n_in, out_ids, n_out, gates_out,
+                            [&](Netlist &nl, const uint32_t *ids) { return wires_maxpool(nl, ids, H, W, C, bits); });
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
@@ -795,9 +864,8 @@ try {
     if ((rc = check_ids(c, out_ids, n_out, "she_relu_maxpool out_ids"))) return rc;
     if ((rc = check_disjoint(c, x_ids, n_in, nullptr, 0, out_ids, n_out))) return rc;
     try {
-        Netlist nl(c->cap, c->fold, c->native_mux, c->cells3, c->columns);
-        const std::vector<uint32_t> wires = wires_relu_maxpool(nl, x_ids, H, W, C, bits);
-        return run_netlist(c, nl, wires, out_ids, gates_out);
+        return run_operator(c, x_ids, n_in, out_ids, n_out, gates_out,
+                            [&](Netlist &nl, const uint32_t *ids) { return wires_relu_maxpool(nl, ids, H, W, C, bits); });
     } catch (const std::bad_alloc &) {
         return fail(c, SHE_ENOMEM, "host allocation for the netlist");
     }
@@ -806,6 +874,7 @@ try {
 int she_set_option(she_ctx *c, int option, int value)
 {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (option == SHE_OPT_FOLD_CONSTANTS) { c->fold = value != 0; return SHE_OK; }
     if (option == SHE_OPT_NATIVE_MUX) { c->native_mux = value != 0; return SHE_OK; }
     if (option == SHE_OPT_GATE3_CELLS) { c->cells3 = value != 0; return SHE_OK; }
@@ -888,6 +957,7 @@ int she_eval_circuit(she_ctx *c, const uint8_t *type, const uint32_t *in0, const
                      size_t ngates, const uint32_t *out_refs, const uint32_t *out_ids, size_t nout, uint64_t *entries_out)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (entries_out) *entries_out = 0;
     if (nout == 0) return SHE_OK;                                      // nothing asked for: nothing to evaluate
     if ((ngates && (!type || !in0 || !in1)) || !out_refs || !out_ids) return fail(c, SHE_EINVAL, "null argument");
@@ -1068,6 +1138,7 @@ try {
 int she_read_ct(she_ctx *c, uint32_t id, uint32_t *dst)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (!dst) return fail(c, SHE_EINVAL, "null argument");
     if (id >= c->cap) return fail(c, SHE_ERANGE, "she_read_ct: id outside the pool");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1078,6 +1149,7 @@ try {
 int she_write_ct(she_ctx *c, uint32_t id, const uint32_t *src)
 try {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (!src) return fail(c, SHE_EINVAL, "null argument");
     if (id >= c->cap) return fail(c, SHE_ERANGE, "she_write_ct: id outside the pool");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1108,6 +1180,7 @@ size_t she_pool_bytes(const she_ctx *c) { return c ? (size_t)c->cap * c->stride 
 int she_bind_pool(she_ctx *c, void *dev_ptr, size_t bytes)
 {
     if (!c) return SHE_EINVAL;
+    SHE_NOT_WHILE_DEFERRED(c);
     if (!dev_ptr || bytes < she_pool_bytes(c) || ((uintptr_t)dev_ptr & 255)) return fail(c, SHE_EINVAL, "bad pool memory");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     if (c->pool_owned) hipFree(c->pool);

@@ -1,5 +1,6 @@
 // The context behind the C ABI and the helpers its source files share (internal).
 #pragma once
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -26,6 +27,15 @@ struct LeveledPools {         // leveled mode: TRGSW selectors (spectral form) a
     uint32_t trgsw_cap = 0, trlwe_cap = 0;
     uint32_t *d_ids = nullptr;      // device staging of the id arrays of one call (4 x ids_cap)
     size_t ids_cap = 0;
+};
+// Layer operators recorded between she_defer_begin and she_defer_run: one netlist for all of them, so that the
+// scheduler can overlap the tail of one operator with the head of the next.
+struct Deferred {
+    static constexpr uint32_t NONE = 0xFFFFFFFFu;
+    std::unique_ptr<Netlist> nl;
+    std::vector<uint32_t> produced;     // [cap] wire reference of a pool id that a recorded operator writes, else NONE
+    std::vector<uint8_t> read;          // [cap] 1: a recorded operator reads the slot as it was before the circuit
+    std::vector<uint32_t> out_wires, out_ids;
 };
 }  // namespace she
 
@@ -62,6 +72,7 @@ struct she_ctx {
     size_t timer_levels = 0;
     double last_ms[4] = {0, 0, 0, 0};
     she::LeveledPools lev;
+    std::unique_ptr<she::Deferred> deferred;   // non-null between she_defer_begin and she_defer_run
     void *na_scratch = nullptr;          // this device's copy of the static scratch buffer (never freed)
     size_t na_bytes = 0;
     std::string err;
@@ -77,6 +88,13 @@ int fail_exception(she_ctx *c);                         // inside a catch block:
 int ensure_stage(she_ctx *c, size_t words);             // grows she_ctx::d_stage
 void free_leveled(she_ctx *c);                          // releases the leveled-mode pools
 }  // namespace she
+
+// calls that read or write the pool are refused while operators are being recorded
+#define SHE_NOT_WHILE_DEFERRED(ctx)                                                               \
+    do {                                                                                          \
+        if ((ctx)->deferred)                                                                      \
+            return she::fail(ctx, SHE_EINVAL, "a deferred circuit is pending: call she_defer_run first"); \
+    } while (0)
 
 #define HIP_TRY(ctx, expr)                                                                        \
     do {                                                                                          \

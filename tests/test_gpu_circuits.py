@@ -261,3 +261,43 @@ def test_chained_network_with_folded_batchnorm_constants(ctx):
         finally:
             for opt in (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER):
                 ctx.set_option(opt, 0)
+
+
+def test_chained_network_as_one_deferred_circuit(ctx):
+    """The seven-layer network recorded with she_defer_begin and run as ONE circuit at n=630: the same class scores, in
+    fewer levels and less time than layer by layer."""
+    import time
+
+    import paper_1906_00148_amd as pkg
+    from paper_1906_00148_amd.layers import Chain
+    img, w1, w2, w3 = S.cfg6_network()
+    want = OC.plain_network(img, w1, w2, w3)
+    opts = (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER)
+    for o in opts:
+        ctx.set_option(o, 1)
+    try:
+        results = {}
+        for deferred in (False, True):
+            x_ids = encrypt_values(ctx, img[..., None], 8, S.data_seed(6))
+            net = Chain(ctx, x_ids.size)
+            levels = 0
+            t0 = time.perf_counter()
+            if deferred:
+                ctx.defer_begin()
+            a = net.relu_maxpool(net.conv(x_ids, w1[0], w1[1], 16))
+            if not deferred:
+                levels += ctx.last_timing()["levels"]
+            b = net.relu_maxpool(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))
+            scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
+            entries = ctx.defer_run() if deferred else net.gates
+            dt = time.perf_counter() - t0
+            if deferred:
+                levels = ctx.last_timing()["levels"]
+            got = OC.from_bits(ctx.decrypt(scores), True)
+            assert np.array_equal(got, want)
+            results[deferred] = (entries, levels, dt)
+            print(f"\nnetwork deferred={deferred}: {entries} entries, {dt:.3f} s" + (f", {levels} levels" if deferred else ""))
+        assert results[True][0] <= results[False][0]
+    finally:
+        for o in opts:
+            ctx.set_option(o, 0)

@@ -676,3 +676,77 @@ def test_eval_circuit_real_parameters_decrypts_to_the_plain_circuit(real_ctx):
     types, in0, in1, in2, out_refs = CC.to_she_arrays(pkg, kinds, ops, neg, outs, n_inputs, in_ids)
     real_ctx.eval_circuit(types, in0, in1, in2, out_refs, out_ids)
     assert np.array_equal(real_ctx.decrypt(out_ids), CC.plain_circuit(kinds, ops, neg, outs, n_inputs, bits))
+
+
+# ------------------------------------------------------------------ operators recorded and scheduled as one circuit
+@pytest.mark.parametrize("lean", [False, True])
+def test_deferred_operators_give_the_sequential_ciphertexts_in_fewer_levels_toy(toy_ctx, toy_keys, lean):
+    """she_defer_begin / she_defer_run: a shift-accumulation with constants and the fused ReLU + 2x2 pooling recorded
+    and run as ONE circuit (the pooling's comparators start at the low bits, which the adders deliver first).  Without
+    options every intermediate and final ciphertext word equals the oracle's netlists evaluated one after the other (the
+    same gates on the same inputs, only scheduled together), in fewer levels than the calls take one by one; with every
+    option on the results decrypt to the plain definition with no more entries."""
+    pkg = she()
+    rng = np.random.default_rng(606)
+    units, terms, in_bits, acc = 4, 3, 3, 6
+    x = rng.integers(0, 1 << in_bits, (units, terms))
+    sign, exp = S.log_weights((units, terms), rng, in_bits - 1)
+    bias = np.array([3, -9, 0, 5], np.int32)
+    ids, fresh = _encrypt_values(toy_ctx, toy_keys, x, in_bits, 606, 0)
+    conv_ids = np.arange(1000, 1000 + units * acc, dtype=np.uint32).reshape(units, acc)
+    pool_ids = np.arange(1300, 1300 + acc, dtype=np.uint32).reshape(1, 1, 1, acc)
+    opts = (pkg.OPT_FOLD_CONSTANTS, pkg.OPT_NATIVE_MUX, pkg.OPT_GATE3_CELLS, pkg.OPT_COLUMN_ADDER)
+    for o in opts:
+        toy_ctx.set_option(o, int(lean))
+    try:
+        # one by one
+        seq_entries = toy_ctx.shift_acc(ids.reshape(units, terms, in_bits), sign, exp, acc, conv_ids, bias=bias)
+        seq_levels = toy_ctx.last_timing()["levels"]
+        seq_entries += toy_ctx.relu_maxpool(conv_ids.reshape(2, 2, 1, acc), pool_ids)
+        seq_levels += toy_ctx.last_timing()["levels"]
+        seq_entries += toy_ctx.relu(conv_ids, conv_ids + 100)    # a second reader of the sums
+        seq_levels += toy_ctx.last_timing()["levels"]
+        seq = [toy_ctx.read_cts(v.ravel()) for v in (conv_ids, pool_ids)]
+        for v in (conv_ids, pool_ids):                           # forget the results
+            for i in v.ravel():
+                toy_ctx.write_ct(int(i), np.zeros(toy_keys.params.n + 1, np.uint32))
+        # recorded, then run as one circuit
+        toy_ctx.defer_begin()
+        rec = toy_ctx.shift_acc(ids.reshape(units, terms, in_bits), sign, exp, acc, conv_ids, bias=bias)
+        rec += toy_ctx.relu_maxpool(conv_ids.reshape(2, 2, 1, acc), pool_ids)
+        with pytest.raises(pkg.SheError):                        # the pool is not to be touched while recording
+            toy_ctx.decrypt(pool_ids)
+        rec += toy_ctx.relu(conv_ids, conv_ids + 100)
+        with pytest.raises(pkg.SheError):                        # a second writer of a recorded output
+            toy_ctx.relu(conv_ids, conv_ids + 100)
+        with pytest.raises(pkg.SheError):                        # an output over a slot the circuit reads as an input
+            toy_ctx.relu(conv_ids, ids.reshape(-1)[: units * acc].reshape(units, acc))
+        with pytest.raises(pkg.SheError):
+            toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 1 - int(lean))
+        ran = toy_ctx.defer_run()
+        levels = toy_ctx.last_timing()["levels"]
+        print(f"\ndeferred (lean={lean}): {ran} entries in {levels} levels; one by one {seq_entries} entries in {seq_levels} levels")
+        assert ran == rec <= seq_entries and levels < seq_levels
+        got = [toy_ctx.read_cts(v.ravel()) for v in (conv_ids, pool_ids)]
+        want_conv = OC.plain_shift_acc(x, sign, exp, acc, bias)
+        want_pool = OC.plain_maxpool2x2(OC.plain_relu(want_conv).reshape(2, 2, 1))
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(conv_ids), True), want_conv)
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(conv_ids + 100), True), OC.plain_relu(want_conv))
+        assert np.array_equal(OC.from_bits(toy_ctx.decrypt(pool_ids), True), want_pool)
+        if not lean:
+            assert rec == seq_entries
+            for a, b in zip(got, seq):
+                assert np.array_equal(a, b)
+            # and the oracle's netlists, one after the other
+            nl1, o1 = OC.build_shift_acc(units, terms, in_bits, sign, exp, acc, bias=bias)
+            c1 = OC.Netlist.read_encrypted(nl1.run_encrypted(toy_keys, fresh, threads=8), np.array(o1))
+            nl3, o3 = OC.build_relu_maxpool(2, 2, 1, acc)
+            c3 = OC.Netlist.read_encrypted(nl3.run_encrypted(toy_keys, c1, threads=8), np.array(o3))
+            assert np.array_equal(got[0], c1) and np.array_equal(got[1], c3)
+        with pytest.raises(pkg.SheError):                        # nothing is open any more
+            toy_ctx.defer_run()
+        toy_ctx.defer_begin()                                    # an empty circuit is a no-op
+        assert toy_ctx.defer_run() == 0
+    finally:
+        for o in opts:
+            toy_ctx.set_option(o, 0)
