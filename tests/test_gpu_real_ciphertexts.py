@@ -47,7 +47,7 @@ def sample_entries(nl, count, seed):
     return np.array(sorted(picks))[: max(count, len(picks))]
 
 
-def run_and_check(ctx, keys, nl, in_ids, out_wires, sampled, threads=16):
+def run_and_check(ctx, keys, nl, in_ids, out_wires, sampled, threads=16, OUT0=OUT0, CAP=CAP):
     """Runs the netlist through she_eval_circuit keeping the sampled entries, their operands and out_wires; checks
     every sampled entry against the oracle on the GPU's operand ciphertexts; returns the ciphertexts of out_wires."""
     import paper_1906_00148_amd as pkg
@@ -238,3 +238,53 @@ def test_xor_chain_of_depth_40_word_for_word(ctx, real_keys):
         ph = O.lwe_phase(real_keys.lwe_key, gpu[k])
         err = ((ph - ((1 << 29) if want[k] else -(1 << 29)) + (1 << 31)) % (1 << 32)) - (1 << 31)
         assert abs(err) < (1 << 28)
+
+
+# ------------------------------------------------------------------ the benchmark configurations at their full size
+def test_cfg5_full_size_convolution_sampled_entries_word_for_word(ctx, real_keys):
+    """Config 5 as it is benchmarked: the 28x28 image, 26x26x8 neurons of nine terms, 1,925,248 gates in 36 levels in
+    one she_eval_circuit call; 40 entries spread over the levels against the oracle on the GPU's own operand words, the
+    sums of eight sampled neurons against plain arithmetic."""
+    img, sign, exp = S.cfg5_conv_layer()
+    oc, k = sign.shape[0], sign.shape[1]
+    oh, ow = img.shape[0] - k + 1, img.shape[1] - k + 1
+    in_ids = encrypt_values(ctx, img, 8, S.data_seed(5))
+    x_ids = np.zeros((oh, ow, oc, k * k, 8), np.uint32)
+    for dy in range(k):
+        for dx in range(k):
+            x_ids[:, :, :, dy * k + dx, :] = in_ids[dy:dy + oh, dx:dx + ow, None, :]
+    units = oh * ow * oc
+    w_sign = np.broadcast_to(sign.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(units, k * k)
+    w_exp = np.broadcast_to(exp.reshape(1, 1, oc, k * k), (oh, ow, oc, k * k)).reshape(units, k * k)
+    nl, outs = OC.build_shift_acc(units, k * k, 8, w_sign, w_exp, 16)
+    print(f"\ncfg5 full size: {len(nl.gtype)} entries, {int(nl.levels().max())} levels", flush=True)
+    assert len(nl.gtype) == 1925248
+    picked = S.subset(units, 8, 57)
+    got = run_and_check(ctx, real_keys, nl, x_ids.reshape(-1), np.asarray(outs)[picked].ravel(), sample_entries(nl, 40, 58))
+    patches = np.stack([img[dy:dy + oh, dx:dx + ow] for dy in range(k) for dx in range(k)], axis=-1)      # [oh][ow][k*k]
+    want = [int(OC.plain_shift_acc(patches[u // oc // ow, u // oc % ow][None, :], w_sign[u][None, :], w_exp[u][None, :], 16)[0])
+            for u in picked]
+    assert OC.from_bits(O.decrypt_bits(real_keys, got).reshape(len(picked), 16), True).tolist() == want
+
+
+def test_cfg4_full_size_pooling_sampled_entries_word_for_word(real_keys):
+    """Config 4 as it is benchmarked: ReLU on the 32x32x16 map (245,760 gates), then the 1,376,256-gate pooling circuit
+    on those bootstrapped outputs in one she_eval_circuit call; 40 entries spread over its 70 levels against the oracle
+    on the GPU's own operand words, sampled pooled values against plain arithmetic."""
+    import paper_1906_00148_amd as pkg
+    fm = S.cfg4_feature_map()
+    H, W, C = fm.shape
+    n_in = fm.size * 16
+    cap = 2 * n_in + 4096
+    with pkg.Context(pkg.REAL, S.KEY_SEED, cap) as c:
+        ids = encrypt_values(c, fm, 16, S.data_seed(4))
+        relu_ids = ids + n_in
+        assert c.relu(ids.reshape(-1, 16), relu_ids.reshape(-1, 16)) == H * W * C * 15
+        nl, outs = OC.build_maxpool(H, W, C, 16)
+        print(f"\ncfg4 full size: pooling {len(nl.gtype)} entries, {int(nl.levels().max())} levels", flush=True)
+        assert len(nl.gtype) == 1376256
+        picked = S.subset(len(outs), 8, 47)
+        got = run_and_check(c, real_keys, nl, relu_ids.ravel(), np.asarray(outs)[picked].ravel(), sample_entries(nl, 40, 48),
+                            OUT0=2 * n_in, CAP=cap)
+        want = OC.plain_maxpool2x2(OC.plain_relu(fm)).reshape(-1)[picked]
+        assert np.array_equal(OC.from_bits(O.decrypt_bits(real_keys, got).reshape(len(picked), 16), True), want)
