@@ -521,18 +521,32 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
 // spectra are then fetched where the products need them instead of a row ahead and no operand is requested ahead, which
 // keeps the kernel at 256 registers (8 spilled) and two wavefronts per SIMD: 162 against 282 us per 4096 CMuxes with one.
 // (Both halves of a transform through one LDS round trip, in a buffer of twice the size, spills 31 registers: 214 us.)
-template <class PL, bool TRACK>
+
+// Sixteen bytes per lane from global memory straight into LDS (lane t's word lands at dst_wave + t): no register is
+// held while the load is in flight.  dst_wave is the same for the whole wavefront.
+__device__ __forceinline__ void load_to_lds16(const uint4 *src_lane, uint4 *dst_wave)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src_lane,
+                                     (__attribute__((address_space(3))) void *)dst_wave, 16, 0, 0);
+}
+
+// LC: the gadget length when it is known at compile time (both loops over the rows are then unrolled, and a wait for
+// memory sits at the first use of what was loaded instead of at a loop's entry), 0 for a length read at run time.
+template <class PL, bool TRACK, int LC>
 __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__restrict__ trgsw_hat,
                                                            uint32_t *trlwe, const uint32_t *__restrict__ sel,
                                                            const uint32_t *__restrict__ in1, const uint32_t *__restrict__ in0,
-                                                           const uint32_t *__restrict__ out, uint32_t count, uint32_t l,
+                                                           const uint32_t *__restrict__ out, uint32_t count, uint32_t l_arg,
                                                            uint32_t bg_bit, const double2 *__restrict__ tw_table,
                                                            unsigned *round_err)
 {
     constexpr int P = PL::P, L = PL::L, N = PL::N;
+    const uint32_t l = LC ? (uint32_t)LC : l_arg;
     static_assert(PL::GPW == 1, "one transform per wavefront");
     __shared__ double2 s_xch[BR_WAVES][PL::XSLOTS];
     __shared__ double2 s_tw[TwTable<PL>::COUNT];
+    constexpr bool STAGE = P <= 8;                                        // component 1's operands wait in LDS
+    __shared__ uint4 s_stage[STAGE ? BR_WAVES : 1][STAGE ? P * L : 1];    // [d1 | d0] x P/2 words x 64 lanes
     const int wave = threadIdx.x >> 6, t = threadIdx.x & 63;
     load_twiddles<PL>(s_tw, tw_table);                                    // once per workgroup: the grid is persistent
 
@@ -545,10 +559,10 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     float worst = 0.f;
 
     // a wavefront takes CMux g, g + (wavefronts in the grid), ...; g is uniform, so the four ids are scalar loads.
-    // Operands are requested ahead into registers that are idle at that moment: the words of d0 that the result is added
-    // to and component 0 of the NEXT CMux before the inverse transforms (the selector row's registers are free then).
-    // (Requesting component 1's words during component 0's last transform as well spills 86 registers: measured 73
-    // against 55 us per 4096 CMuxes; this version 53 us.)
+    // Operands are requested ahead, before the inverse transforms: the words of d0 that the result is added to and
+    // component 0 of the NEXT CMux into registers (the selector row's are idle then), component 1 of the next CMux
+    // into LDS, which costs no register.  (Component 1 requested into registers during component 0's last transform
+    // spills 86 of them: 73 us per 4096 CMuxes against 55 with nothing ahead, 53 without component 1, 47 with LDS.)
     const uint32_t stride = gridDim.x * BR_WAVES;
     constexpr int Q = P / 2;
     constexpr bool AHEAD = P <= 8;                                         // 16 points per lane leave no idle registers
@@ -557,6 +571,13 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     if (AHEAD && g < count) {
         const uint4 *a1 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in1[g] * 2 * N) + t;
         const uint4 *a0 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in0[g] * 2 * N) + t;
+        if constexpr (STAGE) {
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                load_to_lds16(a1 + N / 4 + q * L, &s_stage[wave][q * L]);
+                load_to_lds16(a0 + N / 4 + q * L, &s_stage[wave][(Q + q) * L]);
+            }
+        }
 #pragma unroll
         for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
     }
@@ -578,11 +599,15 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
 #pragma unroll
     for (int k = 0; k < P; k++) { sr[0][k] = si[0][k] = sr[1][k] = si[1][k] = 0.0; }
 
+#pragma unroll(LC ? 2 : 1)
     for (int c = 0; c < 2; c++) {
         // TRLWE samples are stored in transform order: the 16-byte word (q, t) of a component holds the coefficients
         // t + L*2q, t + L*2q + M, t + L*(2q+1), t + L*(2q+1) + M, the ones lane t works on
         uint32_t dlo[P], dhi[P];
-        if (c == 1 || !AHEAD) {
+        if (STAGE && c == 1) {
+#pragma unroll
+            for (int q = 0; q < Q; q++) { pu[q] = s_stage[wave][q * L + t]; pv[q] = s_stage[wave][(Q + q) * L + t]; }
+        } else if (c == 1 || !AHEAD) {
             const uint4 *a1 = reinterpret_cast<const uint4 *>(d1 + c * N) + t, *a0 = reinterpret_cast<const uint4 *>(d0 + c * N) + t;
 #pragma unroll
             for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
@@ -595,6 +620,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
             dlo[2 * q + 1] = (u.z - v.z + dec_off) ^ flip;
             dhi[2 * q + 1] = (u.w - v.w + dec_off) ^ flip;
         }
+#pragma unroll(LC ? LC : 1)
         for (uint32_t p = 0; p < l; p++) {
             const uint32_t sh = 32 - (p + 1) * bg_bit;
             const uint32_t r = c * l + p;
@@ -626,15 +652,25 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     // last: harmless), requested ahead of the inverse transforms
     uint4 base[2][AHEAD ? Q : 1];
     if constexpr (AHEAD) {
-#pragma unroll
-        for (int o = 0; o < 2; o++) {
-            const uint4 *a0 = reinterpret_cast<const uint4 *>(d0 + o * N) + t;
-#pragma unroll
-            for (int q = 0; q < Q; q++) base[o][q] = a0[q * L];
-        }
         const uint32_t gn = g + stride < count ? g + stride : g;
         const uint4 *a1 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in1[gn] * 2 * N) + t;
         const uint4 *a0 = reinterpret_cast<const uint4 *>(trlwe + (size_t)in0[gn] * 2 * N) + t;
+        // the next CMux's second component goes to LDS (this one's was consumed before its transforms).  After a
+        // wavefront's last CMux this loads its own words once more: loads return in order, and the result's stores
+        // wait for `base`, requested after it, so no wavefront leaves with such a load in flight.
+        if constexpr (STAGE) {
+#pragma unroll
+            for (int q = 0; q < Q; q++) {
+                load_to_lds16(a1 + N / 4 + q * L, &s_stage[wave][q * L]);
+                load_to_lds16(a0 + N / 4 + q * L, &s_stage[wave][(Q + q) * L]);
+            }
+        }
+#pragma unroll
+        for (int o = 0; o < 2; o++) {
+            const uint4 *b0 = reinterpret_cast<const uint4 *>(d0 + o * N) + t;
+#pragma unroll
+            for (int q = 0; q < Q; q++) base[o][q] = b0[q * L];
+        }
 #pragma unroll
         for (int q = 0; q < Q; q++) { pu[q] = a1[q * L]; pv[q] = a0[q * L]; }
     }
@@ -905,10 +941,13 @@ static hipError_t cmux_t(const she_params &P, const DeviceKeys &K, const double2
     const size_t per_cu = 2;
     const dim3 grid((unsigned)std::min<size_t>(wgs, per_cu * std::max<uint32_t>(K.cus, 1))), block(64 * BR_WAVES);
     if (d_round_err)
-        hipLaunchKernelGGL((k_cmux<PL, true>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
+        hipLaunchKernelGGL((k_cmux<PL, true, 0>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
+                           (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
+    else if (P.l == 3 && PL::P <= 8)
+        hipLaunchKernelGGL((k_cmux<PL, false, 3>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
                            (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
     else
-        hipLaunchKernelGGL((k_cmux<PL, false>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
+        hipLaunchKernelGGL((k_cmux<PL, false, 0>), grid, block, 0, st, trgsw_hat, trlwe, d_sel, d_in1, d_in0, d_out,
                            (uint32_t)count, P.l, P.bg_bit, K.twiddles, d_round_err);
     return hipGetLastError();
 }
