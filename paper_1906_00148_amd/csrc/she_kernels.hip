@@ -517,9 +517,12 @@ __global__ __launch_bounds__(64 * BR_WAVES) void k_bk_transform(const uint32_t *
 // samples in HBM.  One CMux per wavefront; the same decomposition, transforms and products as
 // one step of the blind rotation, with the operands streamed from memory instead of LDS.
 // ------------------------------------------------------------------------------------------
-// With 16 points per lane (N = 2048) the two output spectra and one transform fill the register file: the selector's
-// spectra are then fetched where the products need them instead of a row ahead and no operand is requested ahead, which
-// keeps the kernel at 256 registers (8 spilled) and two wavefronts per SIMD: 162 against 282 us per 4096 CMuxes with one.
+// With 16 points per lane (N = 2048) the two output spectra and one transform fill the register file (192 of 256), so
+// no selector row and no operand is requested ahead there.  What keeps that version at two wavefronts per SIMD and off
+// the scratch memory: the words that the digits are cut from wait in LDS between the rows (32 registers), and the
+// selector's values run through a ring of four points' worth of loads inside the products.  Per 4096 CMuxes: one
+// wavefront per SIMD 282 us; two, every selector value loaded and waited for singly 162 us; the ring 149 us (45
+// registers spilled); the words in LDS as well 101 us (12 spilled).
 // (Both halves of a transform through one LDS round trip, in a buffer of twice the size, spills 31 registers: 214 us.)
 
 // Sixteen bytes per lane from global memory straight into LDS (lane t's word lands at dst_wave + t): no register is
@@ -547,6 +550,10 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     __shared__ double2 s_tw[TwTable<PL>::COUNT];
     constexpr bool STAGE = P <= 8;                                        // component 1's operands wait in LDS
     __shared__ uint4 s_stage[STAGE ? BR_WAVES : 1][STAGE ? P * L : 1];    // [d1 | d0] x P/2 words x 64 lanes
+    // With 16 points per lane the words that the digits are cut from wait in LDS between the rows (each lane reads
+    // back what it wrote): 32 registers that the transform and the products need.
+    constexpr bool WORDS_IN_LDS = P > 8;
+    __shared__ uint4 s_words[WORDS_IN_LDS ? BR_WAVES : 1][WORDS_IN_LDS ? (P / 2) * L : 1];
     const int wave = threadIdx.x >> 6, t = threadIdx.x & 63;
     load_twiddles<PL>(s_tw, tw_table);                                    // once per workgroup: the grid is persistent
 
@@ -603,7 +610,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
     for (int c = 0; c < 2; c++) {
         // TRLWE samples are stored in transform order: the 16-byte word (q, t) of a component holds the coefficients
         // t + L*2q, t + L*2q + M, t + L*(2q+1), t + L*(2q+1) + M, the ones lane t works on
-        uint32_t dlo[P], dhi[P];
+        uint32_t dlo[WORDS_IN_LDS ? 1 : P], dhi[WORDS_IN_LDS ? 1 : P];
         if (STAGE && c == 1) {
 #pragma unroll
             for (int q = 0; q < Q; q++) { pu[q] = s_stage[wave][q * L + t]; pv[q] = s_stage[wave][(Q + q) * L + t]; }
@@ -615,30 +622,64 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_cmux(const double2 *__rest
 #pragma unroll
         for (int q = 0; q < Q; q++) {
             const uint4 u = pu[q], v = pv[q];
-            dlo[2 * q] = (u.x - v.x + dec_off) ^ flip;
-            dhi[2 * q] = (u.y - v.y + dec_off) ^ flip;
-            dlo[2 * q + 1] = (u.z - v.z + dec_off) ^ flip;
-            dhi[2 * q + 1] = (u.w - v.w + dec_off) ^ flip;
+            const uint4 w = make_uint4((u.x - v.x + dec_off) ^ flip, (u.y - v.y + dec_off) ^ flip,
+                                       (u.z - v.z + dec_off) ^ flip, (u.w - v.w + dec_off) ^ flip);
+            if constexpr (WORDS_IN_LDS) {
+                s_words[wave][q * L + t] = w;
+            } else {
+                dlo[2 * q] = w.x; dhi[2 * q] = w.y; dlo[2 * q + 1] = w.z; dhi[2 * q + 1] = w.w;
+            }
         }
 #pragma unroll(LC ? LC : 1)
         for (uint32_t p = 0; p < l; p++) {
             const uint32_t sh = 32 - (p + 1) * bg_bit;
             const uint32_t r = c * l + p;
             double xr[P], xi[P];
+            if constexpr (WORDS_IN_LDS) {
 #pragma unroll
-            for (int m = 0; m < P; m++) {
-                xr[m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], sh, bg_bit);
-                xi[m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], sh, bg_bit);
+                for (int q = 0; q < Q; q++) {
+                    const uint4 w = s_words[wave][q * L + t];
+                    xr[2 * q] = (double)(int)__builtin_amdgcn_sbfe(w.x, sh, bg_bit);
+                    xi[2 * q] = (double)(int)__builtin_amdgcn_sbfe(w.y, sh, bg_bit);
+                    xr[2 * q + 1] = (double)(int)__builtin_amdgcn_sbfe(w.z, sh, bg_bit);
+                    xi[2 * q + 1] = (double)(int)__builtin_amdgcn_sbfe(w.w, sh, bg_bit);
+                }
+            } else {
+#pragma unroll
+                for (int m = 0; m < P; m++) {
+                    xr[m] = (double)(int)__builtin_amdgcn_sbfe(dlo[m], sh, bg_bit);
+                    xi[m] = (double)(int)__builtin_amdgcn_sbfe(dhi[m], sh, bg_bit);
+                }
             }
             forward<PL>(lc, xr, xi);
+            if constexpr (ROW_AHEAD) {
 #pragma unroll
-            for (int o = 0; o < 2; o++)
+                for (int o = 0; o < 2; o++)
+#pragma unroll
+                    for (int k = 0; k < P; k++) {
+                        const double2 b = bv[o][k];
+                        sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
+                        si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
+                    }
+            } else {
+                // no room for a row: the selector's values for RING points are in flight while the products of the
+                // points before them run (a transformed value's registers are free once both outputs have used it)
+                constexpr int RING = 4;
+                const double2 *row = rows + (size_t)r * 2 * P * L;
+                double2 ring[RING][2];
+                __builtin_amdgcn_sched_barrier(0);                        // not into the transform: no register is free there
+#pragma unroll
+                for (int k = 0; k < RING; k++) { ring[k][0] = row[k * L]; ring[k][1] = row[(P + k) * L]; }
 #pragma unroll
                 for (int k = 0; k < P; k++) {
-                    const double2 b = ROW_AHEAD ? bv[o][k] : rows[(size_t)r * 2 * P * L + (o * P + k) * L];
-                    sr[o][k] = __builtin_fma(-xi[k], b.y, __builtin_fma(xr[k], b.x, sr[o][k]));
-                    si[o][k] = __builtin_fma(xi[k], b.x, __builtin_fma(xr[k], b.y, si[o][k]));
+                    const double2 b0 = ring[k % RING][0], b1 = ring[k % RING][1];
+                    if (k + RING < P) { ring[k % RING][0] = row[(k + RING) * L]; ring[k % RING][1] = row[(P + k + RING) * L]; }
+                    sr[0][k] = __builtin_fma(-xi[k], b0.y, __builtin_fma(xr[k], b0.x, sr[0][k]));
+                    si[0][k] = __builtin_fma(xi[k], b0.x, __builtin_fma(xr[k], b0.y, si[0][k]));
+                    sr[1][k] = __builtin_fma(-xi[k], b1.y, __builtin_fma(xr[k], b1.x, sr[1][k]));
+                    si[1][k] = __builtin_fma(xi[k], b1.x, __builtin_fma(xr[k], b1.y, si[1][k]));
                 }
+            }
             if (ROW_AHEAD && r + 1 < 2 * l) {
                 const double2 *row = rows + (size_t)(r + 1) * 2 * P * L;
 #pragma unroll
