@@ -109,14 +109,17 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
     t0 = time.perf_counter()
     g1 = ctx.shift_acc(x_ids.reshape(-1, k * k, 8), w_sign, w_exp, AB, conv_ids.reshape(-1, AB))
     t1 = time.perf_counter()
+    schedules = [ctx.last_level_sizes()]
     if fused_pool:                       # ReLU and pooling as one operator (she_relu_maxpool)
         g2, t2 = 0, t1
         g3 = ctx.relu_maxpool(conv_ids.reshape(oh, ow, oc, AB), pool_ids.reshape(oh // 2, ow // 2, oc, AB))
     else:
         g2 = ctx.relu(conv_ids.reshape(-1, AB), relu_ids.reshape(-1, AB))
         t2 = time.perf_counter()
+        schedules.append(ctx.last_level_sizes())
         g3 = ctx.maxpool(relu_ids.reshape(oh, ow, oc, AB), pool_ids.reshape(oh // 2, ow // 2, oc, AB))
     t3 = time.perf_counter()
+    schedules.append(ctx.last_level_sizes())
     # all 13x13x8 outputs against plain integer arithmetic (16-bit accumulators: the narrow widths hold the same values)
     dec = ctx.decrypt(pool_ids.reshape(-1, AB)).astype(np.int64)
     got = (dec << np.arange(AB)).sum(axis=1)
@@ -136,7 +139,89 @@ def conv_layer(ctx_factory, fold: bool, native_mux: bool = False, cells3: bool =
             "accumulator_bits": int(AB), "column_adder": bool(columns),
             "latency_s": t3 - t0, "gates": int(total), "gates_per_s": total / (t3 - t0),
             "conv_s": t1 - t0, "relu_s": t2 - t1, "pool_s": t3 - t2,
-            "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3)}
+            "conv_gates": int(g1), "relu_gates": int(g2), "pool_gates": int(g3), "schedule": level_histogram(schedules)}
+
+
+def neuron_576(ctx_factory, lean: bool):
+    """Config 3: one neuron of 576 shifted 8-bit terms into a 16-bit accumulator (latency-bound: ~500 gates per
+    level); the literal adder tree, or with folding, three-input cells and column compression (lean)."""
+    import numpy as np
+
+    import synth_inputs as S
+
+    x, sign, exp = S.cfg3_neuron()
+    ctx = ctx_factory(8192)
+    if lean:
+        for opt in (1, 4, 8):
+            ctx.set_option(opt, 1)
+    bits = ((x.reshape(-1)[:, None] >> np.arange(8)) & 1).astype(np.uint8)
+    ids = np.arange(bits.size, dtype=np.uint32)
+    ctx.encrypt_bits(bits.ravel(), S.data_seed(3), ids)
+    out = np.arange(6000, 6016, dtype=np.uint32).reshape(1, 16)
+    best = None
+    for _ in range(3):
+        t0 = time.perf_counter()
+        g = ctx.shift_acc(ids.reshape(1, 576, 8), sign, exp, 16, out)
+        dt = time.perf_counter() - t0
+        best = dt if best is None else min(best, dt)
+    schedule = level_histogram([ctx.last_level_sizes()])
+    got = int((ctx.decrypt(out).astype(np.int64) << np.arange(16)).sum())
+    want = int(((x >> -exp.astype(np.int64)) * sign).sum()) % 65536
+    assert got == want, "the neuron decrypts wrongly"
+    ctx.close()
+    return {"workload": "one neuron: 576 terms x 8 bits, weights sign * 2^e, 16-bit accumulator, n=630 N=1024"
+                        + (", folding + three-input cells + column compression" if lean else ", literal adder tree"),
+            "latency_s": best, "gates": int(g), "gates_per_s": g / best, "schedule": schedule}
+
+
+def relu_pool_map(ctx_factory):
+    """Config 4: ReLU then 2x2 max pooling over a 32x32x16 map of 16-bit values (1.62 M gates as stated netlists)."""
+    import numpy as np
+
+    import synth_inputs as S
+
+    v = S.cfg4_feature_map()
+    H, W, Cn = v.shape
+    bits = (((v % 65536)[..., None] >> np.arange(16)) & 1).astype(np.uint8)
+    n_in = bits.size
+    in_ids = np.arange(n_in, dtype=np.uint32).reshape(H, W, Cn, 16)
+    relu_ids = (n_in + np.arange(n_in, dtype=np.uint32)).reshape(H, W, Cn, 16)
+    pool_ids = (2 * n_in + np.arange(n_in // 4, dtype=np.uint32)).reshape(H // 2, W // 2, Cn, 16)
+    ctx = ctx_factory(int(pool_ids.max()) + 1)
+    ctx.encrypt_bits(bits.ravel(), S.data_seed(4), in_ids.ravel())
+    t0 = time.perf_counter()
+    g1 = ctx.relu(in_ids.reshape(-1, 16), relu_ids.reshape(-1, 16))
+    t1 = time.perf_counter()
+    schedules = [ctx.last_level_sizes()]
+    g2 = ctx.maxpool(relu_ids, pool_ids)
+    t2 = time.perf_counter()
+    schedules.append(ctx.last_level_sizes())
+    dec = ctx.decrypt(pool_ids.reshape(-1, 16)).astype(np.int64)
+    got = (dec << np.arange(16)).sum(axis=1).reshape(H // 2, W // 2, Cn)
+    act = np.maximum(v, 0)
+    want = np.maximum(np.maximum(act[0::2, 0::2], act[0::2, 1::2]), np.maximum(act[1::2, 0::2], act[1::2, 1::2]))
+    assert np.array_equal(got, want), "ReLU + pooling decrypts wrongly"
+    ctx.close()
+    return {"workload": "32x32x16 map of 16-bit values -> ReLU -> maxpool2x2, n=630 N=1024, stated netlists",
+            "latency_s": t2 - t0, "gates": int(g1 + g2), "gates_per_s": (g1 + g2) / (t2 - t0),
+            "relu_s": t1 - t0, "pool_s": t2 - t1, "relu_gates": int(g1), "pool_gates": int(g2),
+            "schedule": level_histogram(schedules)}
+
+
+def level_histogram(schedules):
+    """Entries per level of the circuits a call ran (she_last_level_sizes; a native MUX entry is two blind rotations):
+    how many levels fall into each size class, and the blind rotations they hold."""
+    import numpy as np
+
+    rot = np.concatenate([g.astype(np.int64) + 2 * m.astype(np.int64) for g, m in schedules]) if schedules else np.zeros(0, np.int64)
+    edges = [1, 257, 1025, 2049, 4097, 16385]
+    names = ["1-256", "257-1024", "1025-2048", "2049-4096", "4097-16384", ">16384"]
+    hist = {}
+    for i, name in enumerate(names):
+        lo, hi = edges[i], edges[i + 1] if i + 1 < len(edges) else None
+        pick = (rot >= lo) & ((rot < hi) if hi else True)
+        hist[name] = {"levels": int(pick.sum()), "rotations": int(rot[pick].sum())}
+    return {"levels": int((rot > 0).sum()), "rotations": int(rot.sum()), "rotations_per_level_classes": hist}
 
 
 def network(ctx_factory, deferred: bool = False):
@@ -182,11 +267,19 @@ def network(ctx_factory, deferred: bool = False):
     t0 = time.perf_counter()
     if deferred:
         ctx.defer_begin()
-    a = net.relu_maxpool(net.conv(x_ids, w1[0], w1[1], 16))
-    b = net.relu_maxpool(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))
-    scores = net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16)
+    schedules = []
+
+    def ran(x):                          # the schedule of the operator that just ran (nothing runs while recording)
+        if not deferred:
+            schedules.append(ctx.last_level_sizes())
+        return x
+
+    a = ran(net.relu_maxpool(ran(net.conv(x_ids, w1[0], w1[1], 16))))
+    b = ran(net.relu_maxpool(ran(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))))
+    scores = ran(net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16))
     if deferred:
         ctx.defer_run()
+        schedules.append(ctx.last_level_sizes())
     dt = time.perf_counter() - t0
     dec = ctx.decrypt(scores).astype(np.int64)
     got = (dec << np.arange(16)).sum(axis=1)
@@ -197,7 +290,7 @@ def network(ctx_factory, deferred: bool = False):
                         "constant folding, native MUX, three-input cells and column-compression accumulators on"
                         + (", the five operators run as one deferred circuit" if deferred else ""),
             "latency_s": dt, "entries": int(net.gates),
-            "entries_per_s": net.gates / dt}
+            "entries_per_s": net.gates / dt, "schedule": level_histogram(schedules)}
 
 
 def cmux_level(ctx_factory, count: int = 4096, reps: int = 5):
@@ -364,6 +457,9 @@ def main():
                                                    native_mux=True, cells3=True, fused_pool=True, narrow=True)
         out["conv_layer_lean_columns"] = conv_layer(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), fold=True,
                                                     native_mux=True, cells3=True, fused_pool=True, narrow=True, columns=True)
+        out["neuron_576"] = neuron_576(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), lean=False)
+        out["neuron_576_lean"] = neuron_576(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), lean=True)
+        out["relu_pool_map"] = relu_pool_map(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["network_deferred"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), deferred=True)
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))

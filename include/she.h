@@ -370,6 +370,12 @@ int she_get_round_error(she_ctx *ctx, double *max_abs_frac, int reset);
 int she_set_timing(she_ctx *ctx, int on);
 int she_last_timing(she_ctx *ctx, double ms[4]);
 
+/* The schedule of the last circuit that the context ran (a layer operator, she_eval_circuit, she_defer_run): level v
+ * (0-based, in the order the levels ran) held gates[v] gate entries and muxes[v] native MUX entries (two blind
+ * rotations each).  *levels_out (may be NULL) is the number of levels; at most `capacity` entries of each array are
+ * written (the arrays may be NULL with capacity 0 to ask for the count only). */
+int she_last_level_sizes(const she_ctx *ctx, uint64_t *gates, uint64_t *muxes, size_t capacity, size_t *levels_out);
+
 /* Text of the last error of this context ("" if none).  ctx may be NULL: then the text
  * of the last failed she_keygen of the calling thread. */
 const char *she_last_error(const she_ctx *ctx);

@@ -116,6 +116,8 @@ def load_library() -> C.CDLL:
         "she_probe_fp64_rate": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
         "she_set_timing": (C.c_int, [ctx, C.c_int]),
         "she_last_timing": (C.c_int, [ctx, C.POINTER(C.c_double)]),
+        "she_last_level_sizes": (C.c_int, [ctx, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.c_size_t,
+                                            C.POINTER(C.c_size_t)]),
         "she_last_error": (C.c_char_p, [ctx]),
     }
     for name, (res, args) in sigs.items():
@@ -478,3 +480,13 @@ class Context:
         ms = (C.c_double * 4)()
         self._check(self._L.she_last_timing(self._h, ms))
         return {"lincomb_ms": ms[0], "blind_rotate_ms": ms[1], "key_switch_ms": ms[2], "levels": int(ms[3])}
+
+    def last_level_sizes(self):
+        """(gates, muxes): entries per level of the last circuit, in the order the levels ran."""
+        n = C.c_size_t(0)
+        self._check(self._L.she_last_level_sizes(self._h, None, None, 0, C.byref(n)))
+        gates, muxes = np.zeros(n.value, np.uint64), np.zeros(n.value, np.uint64)
+        if n.value:
+            self._check(self._L.she_last_level_sizes(self._h, gates.ctypes.data_as(C.POINTER(C.c_uint64)),
+                                                     muxes.ctypes.data_as(C.POINTER(C.c_uint64)), n.value, None))
+        return gates, muxes

@@ -257,6 +257,12 @@ int run_netlist(she_ctx *c, Netlist &nl, const std::vector<uint32_t> &out_wires,
         widest = std::max(widest, std::max(mux_start[lv] - bounds[lv], 2 * (bounds[lv + 1] - mux_start[lv])));
     }
     mux_first[levels] = mo.size();
+    c->level_gates.resize(levels);
+    c->level_muxes.resize(levels);
+    for (size_t lv = 0; lv < levels; lv++) {
+        c->level_gates[lv] = mux_start[lv] - bounds[lv];
+        c->level_muxes[lv] = bounds[lv + 1] - mux_start[lv];
+    }
     if ((rc = ensure_work(c, std::min<size_t>(widest, MAX_LEVEL_CHUNK)))) return rc;
     if ((rc = ensure_gate_arrays(c, std::max(G, nl.copy_src.size())))) return rc;
     if (!mo.empty()) {
@@ -1262,6 +1268,15 @@ try {
     for (int i = 0; i < 4; i++) ms[i] = c->last_ms[i];
     return SHE_OK;
 } SHE_NOTHROW(c)
+
+int she_last_level_sizes(const she_ctx *c, uint64_t *gates, uint64_t *muxes, size_t capacity, size_t *levels_out)
+{
+    if (!c || (capacity && (!gates || !muxes))) return SHE_EINVAL;
+    const size_t levels = c->level_gates.size();
+    if (levels_out) *levels_out = levels;
+    for (size_t v = 0; v < levels && v < capacity; v++) { gates[v] = c->level_gates[v]; muxes[v] = c->level_muxes[v]; }
+    return SHE_OK;
+}
 
 const char *she_last_error(const she_ctx *c) { return c ? c->err.c_str() : g_keygen_error.c_str(); }
 

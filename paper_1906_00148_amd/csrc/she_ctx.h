@@ -70,6 +70,7 @@ struct she_ctx {
     bool timing = true;                  // record HIP events around every kernel
     she::LevelTimer timer;               // events not yet folded into last_ms
     size_t timer_levels = 0;
+    std::vector<uint64_t> level_gates, level_muxes;   // schedule of the last circuit (she_last_level_sizes)
     double last_ms[4] = {0, 0, 0, 0};
     she::LeveledPools lev;
     std::unique_ptr<she::Deferred> deferred;   // non-null between she_defer_begin and she_defer_run

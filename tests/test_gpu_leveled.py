@@ -146,6 +146,41 @@ def test_cmux_bit_exact_real_parameters(real_ctx, real_keys):
     assert np.array_equal(got[6], data[0])
 
 
+def test_cmux_level_longer_than_the_grid_real_parameters(real_keys):
+    """N = 1024, l = 3 (the variant with the gadget length fixed at compile time, the next CMux's second component
+    travelling through LDS): more CMuxes than the grid has wavefronts, so every wavefront runs two or three in a row
+    and the entries are regrouped by selector.  A sample spread over all rounds against the oracle word for word, every
+    output's selected branch by its phase; the tracking variant of the kernel gives the same words."""
+    pkg = she()
+    P = real_keys.params
+    count, nsel, ndat = 4500, 24, 48
+    rng = np.random.default_rng(4500)
+    with pkg.Context(pkg.REAL, S.KEY_SEED, 16) as ctx:
+        ctx.leveled_init(nsel, ndat + count)
+        bits = rng.integers(0, 2, nsel).astype(np.uint8)
+        ctx.trgsw_encrypt_bits(bits, 93, np.arange(nsel, dtype=np.uint32))
+        sels = O.trgsw_encrypt_bits(real_keys, bits, 93)
+        mu = messages(rng, ndat, P.N)
+        ctx.trlwe_encrypt(mu, 94, np.arange(ndat, dtype=np.uint32))
+        data = O.trlwe_encrypt(real_keys, mu, 94)
+        s, i1, i0 = rng.integers(0, nsel, count), rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+        out_ids = (ndat + np.arange(count)).astype(np.uint32)
+        ctx.eval_cmux(s, i1, i0, out_ids)
+        phases = ctx.trlwe_phase(out_ids)
+        chosen = np.where(bits[s][:, None] == 1, mu[i1], mu[i0])
+        assert np.array_equal(signed(phases) > 0, signed(chosen) > 0)
+        sample = np.unique(np.concatenate([np.arange(0, count, 211), [1, 2047, 2048, 4095, 4096, count - 1]]))
+        got = ctx.trlwe_read(out_ids[sample])
+        for k, m in enumerate(sample):
+            assert np.array_equal(got[k], O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])), m
+        everything = ctx.trlwe_read(out_ids)
+        ctx.set_round_tracking(True)
+        ctx.get_round_error(reset=True)
+        ctx.eval_cmux(s, i1, i0, out_ids)
+        assert 0 < ctx.get_round_error() < 0.2
+        assert np.array_equal(ctx.trlwe_read(out_ids), everything)
+
+
 def test_lookup_tree_of_cmux_levels(toy_ctx, toy_keys):
     """A 16-row plaintext table addressed by 4 encrypted bits: 4 levels of 8, 4, 2, 1 CMuxes, for 6 addresses
     side by side; the root's phase is the addressed row, every intermediate word equals the oracle's."""
@@ -252,6 +287,38 @@ def test_cmux_level_bit_exact_ring_degree_2048(s4_ctx, section4_keys, count):
         assert np.array_equal(signed(phases[m]) > 0, signed(chosen) > 0), m
     s4_ctx.eval_cmux(sel_ids[s], dat_ids[i1], dat_ids[i0], out_ids)                 # tracking off: same words
     assert np.array_equal(s4_ctx.trlwe_read(out_ids), got)
+
+
+def test_cmux_level_longer_than_the_grid_ring_degree_2048(section4_keys):
+    """N-bar = 2048 with more CMuxes than the grid has wavefronts: a wavefront's second and third CMux reuse the LDS
+    areas of the first (exchange buffer, the words the digits are cut from).  Sampled entries word for word, every
+    output's branch by its phase, and the tracking variant gives the same words."""
+    pkg = she()
+    P = section4_keys.params
+    count, nsel, ndat = 4300, 12, 40
+    rng = np.random.default_rng(4300)
+    with pkg.Context(pkg.Params(n=16, N=2048), S.KEY_SEED, 16) as ctx:
+        ctx.leveled_init(nsel, ndat + count)
+        bits = rng.integers(0, 2, nsel).astype(np.uint8)
+        ctx.trgsw_encrypt_bits(bits, 95, np.arange(nsel, dtype=np.uint32))
+        sels = O.trgsw_encrypt_bits(section4_keys, bits, 95)
+        mu = messages(rng, ndat, P.N)
+        ctx.trlwe_encrypt(mu, 96, np.arange(ndat, dtype=np.uint32))
+        data = O.trlwe_encrypt(section4_keys, mu, 96)
+        s, i1, i0 = rng.integers(0, nsel, count), rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+        out_ids = (ndat + np.arange(count)).astype(np.uint32)
+        ctx.eval_cmux(s, i1, i0, out_ids)
+        phases = ctx.trlwe_phase(out_ids)
+        chosen = np.where(bits[s][:, None] == 1, mu[i1], mu[i0])
+        assert np.array_equal(signed(phases) > 0, signed(chosen) > 0)
+        sample = np.unique(np.concatenate([np.arange(0, count, 331), [2047, 2048, 4095, 4096, count - 1]]))
+        got = ctx.trlwe_read(out_ids[sample])
+        for k, m in enumerate(sample):
+            assert np.array_equal(got[k], O.cmux(P, sels[s[m]], data[i1[m]], data[i0[m]])), m
+        everything = ctx.trlwe_read(out_ids)
+        ctx.set_round_tracking(True)
+        ctx.eval_cmux(s, i1, i0, out_ids)
+        assert np.array_equal(ctx.trlwe_read(out_ids), everything)
 
 
 def test_lookup_tree_ring_degree_2048_and_gates_are_refused(s4_ctx, section4_keys):

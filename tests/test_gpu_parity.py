@@ -416,6 +416,29 @@ def test_maxpool_with_native_mux_matches_oracle_netlist_toy(toy_ctx, toy_keys):
             toy_ctx.set_option(pkg.OPT_FOLD_CONSTANTS, 0)
 
 
+def test_last_level_sizes_is_the_oracle_netlists_earliest_depth_histogram_toy(toy_ctx, toy_keys):
+    """she_last_level_sizes: the schedule the library ran, level by level, against the depth of every entry of the
+    oracle's netlist when each is placed as early as its operands allow (gates and native MUX entries apart)."""
+    pkg = she()
+    vals = np.array([[[-3, 5], [2, -8]], [[1, 7], [-4, 6]]])
+    toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 1)
+    try:
+        ids, _ = _encrypt_values(toy_ctx, toy_keys, vals, 4, 64, 0)
+        pool_ids = np.arange(3000, 3008, dtype=np.uint32)
+        g = toy_ctx.maxpool(ids.reshape(2, 2, 2, 4), pool_ids.reshape(1, 1, 2, 4))
+        gates, muxes = toy_ctx.last_level_sizes()
+        nl, _ = OC.build_maxpool(2, 2, 2, 4, fold=False, native_mux=True)
+        lev = nl.levels()
+        is_mux = np.array([OC.is_mux(t) for t in nl.gtype])
+        depth = int(lev.max())
+        assert len(gates) == len(muxes) == depth == toy_ctx.last_timing()["levels"]
+        assert gates.tolist() == [int(np.sum((lev == v) & ~is_mux)) for v in range(1, depth + 1)]
+        assert muxes.tolist() == [int(np.sum((lev == v) & is_mux)) for v in range(1, depth + 1)]
+        assert int(gates.sum() + muxes.sum()) == g and muxes.sum() > 0
+    finally:
+        toy_ctx.set_option(pkg.OPT_NATIVE_MUX, 0)
+
+
 # ------------------------------------------------------------------ other gadget and key-switch shapes
 @pytest.mark.parametrize("shape", [dict(n=64, N=256, l=2, bg_bit=10, ks_t=5, ks_basebit=3),
                                    dict(n=80, N=512, l=4, bg_bit=6, ks_t=4, ks_basebit=4),
