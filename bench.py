@@ -224,9 +224,12 @@ def level_histogram(schedules):
     return {"levels": int((rot > 0).sum()), "rotations": int(rot.sum()), "rotations_per_level_classes": hist}
 
 
-def network(ctx_factory, deferred: bool = False):
+def network(ctx_factory, deferred: bool = False, batch: int = 1):
     """deferred: the five operator calls are recorded (she_defer_begin) and run as ONE circuit, so that the scheduler
     overlaps one operator's last levels with the next one's first.
+    batch > 1 (deferred only): that many images (the same network; image b is the seeded image with its rows rolled by b)
+    recorded into ONE circuit, so every level holds the entries of all of them: the way a serving loop fills the
+    chip where one image's small levels cannot.
     A second, deeper workload: conv - ReLU - pool - conv - ReLU - pool - dense on a 14x14 8-bit image (the MNIST
     network's layer sequence, shrunk), chained on the device without decrypting in between; folding, native MUX, three-input cells and the column adder on."""
     import numpy as np
@@ -251,16 +254,20 @@ def network(ctx_factory, deferred: bool = False):
         x = np.maximum(x, 0)[: x.shape[0] // 2 * 2, : x.shape[1] // 2 * 2]
         return np.maximum(np.maximum(x[0::2, 0::2], x[0::2, 1::2]), np.maximum(x[1::2, 0::2], x[1::2, 1::2]))
 
-    feat = pool_plain(conv_plain(pool_plain(conv_plain(img[..., None], *w1)), *w2)).reshape(-1)
-    want = ((feat[None, :] >> -w3[1].astype(np.int64)) * w3[0]).sum(axis=1)
-    want = ((want + 32768) % 65536) - 32768
+    assert batch == 1 or deferred
+    imgs = [np.roll(img, b, axis=0) for b in range(batch)]
 
-    ctx = ctx_factory(32768)
+    def plain(im):
+        feat = pool_plain(conv_plain(pool_plain(conv_plain(im[..., None], *w1)), *w2)).reshape(-1)
+        want = ((feat[None, :] >> -w3[1].astype(np.int64)) * w3[0]).sum(axis=1)
+        return ((want + 32768) % 65536) - 32768
+
+    ctx = ctx_factory(32768 * batch)
     ctx.set_option(1, 1)
     ctx.set_option(2, 1)
     ctx.set_option(4, 1)
     ctx.set_option(8, 1)
-    bits = ((img[..., None, None] >> np.arange(8)) & 1).astype(np.uint8)
+    bits = np.stack([((im[..., None, None] >> np.arange(8)) & 1).astype(np.uint8) for im in imgs])
     x_ids = np.arange(bits.size, dtype=np.uint32).reshape(bits.shape)
     ctx.encrypt_bits(bits.ravel(), S.data_seed(6), x_ids.ravel())
     net = Chain(ctx, x_ids.size)
@@ -274,22 +281,26 @@ def network(ctx_factory, deferred: bool = False):
             schedules.append(ctx.last_level_sizes())
         return x
 
-    a = ran(net.relu_maxpool(ran(net.conv(x_ids, w1[0], w1[1], 16))))
-    b = ran(net.relu_maxpool(ran(net.conv(Chain.unsigned_view(a), w2[0], w2[1], 16))))
-    scores = ran(net.dense(Chain.unsigned_view(b), w3[0], w3[1], 16))
+    scores = []
+    for b in range(batch):
+        a1 = ran(net.relu_maxpool(ran(net.conv(x_ids[b], w1[0], w1[1], 16))))
+        a2 = ran(net.relu_maxpool(ran(net.conv(Chain.unsigned_view(a1), w2[0], w2[1], 16))))
+        scores.append(ran(net.dense(Chain.unsigned_view(a2), w3[0], w3[1], 16)))
     if deferred:
         ctx.defer_run()
         schedules.append(ctx.last_level_sizes())
     dt = time.perf_counter() - t0
-    dec = ctx.decrypt(scores).astype(np.int64)
-    got = (dec << np.arange(16)).sum(axis=1)
-    got = np.where(got >= 32768, got - 65536, got)
-    assert np.array_equal(got, want), "network decrypts wrongly"
+    for b in range(batch):
+        dec = ctx.decrypt(scores[b]).astype(np.int64)
+        got = (dec << np.arange(16)).sum(axis=1)
+        got = np.where(got >= 32768, got - 65536, got)
+        assert np.array_equal(got, plain(imgs[b])), "network decrypts wrongly"
     ctx.close()
     return {"workload": "14x14x1 -> conv3x3x4 -> ReLU -> pool -> conv3x3x4 -> ReLU -> pool -> dense 10, n=630 N=1024, "
                         "constant folding, native MUX, three-input cells and column-compression accumulators on"
-                        + (", the five operators run as one deferred circuit" if deferred else ""),
-            "latency_s": dt, "entries": int(net.gates),
+                        + (", the five operators run as one deferred circuit" if deferred else "")
+                        + (f", {batch} images in that one circuit" if batch > 1 else ""),
+            "images": batch, "latency_s": dt, "images_per_s": batch / dt, "entries": int(net.gates),
             "entries_per_s": net.gates / dt, "schedule": level_histogram(schedules)}
 
 
@@ -462,6 +473,7 @@ def main():
         out["relu_pool_map"] = relu_pool_map(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["network"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["network_deferred"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), deferred=True)
+        out["network_deferred_batch8"] = network(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), deferred=True, batch=8)
         out["cmux_level"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap))
         out["cmux_level_16k"] = cmux_level(lambda cap: she.Context(she.REAL, S.KEY_SEED, cap), count=16384)
         # the ring degree of the paper's leveled setting (Section 4: n = 500, N-bar = 2048)
