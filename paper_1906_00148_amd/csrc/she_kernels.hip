@@ -79,14 +79,17 @@ __global__ __launch_bounds__(128) void k_lincomb(CtSpace cs, const uint8_t *__re
 // ------------------------------------------------------------------------------------------
 constexpr int BR_WAVES = 4;     // measured: 2 and 8 wavefronts per workgroup are slower
 
-template <class PL, bool TRACK>
+// LC: the gadget length when it is known at compile time (the loops over the 2 LC rows of a step are then unrolled:
+// shifts and row offsets become constants, measured 1.2 % faster at l = 3 on alternating runs), 0 for any length.
+template <class PL, bool TRACK, int LC>
 __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
-    const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l, uint32_t bg_bit,
+    const uint16_t *__restrict__ bar, uint32_t bar_stride, uint32_t n, uint32_t l_arg, uint32_t bg_bit,
     const double2 *__restrict__ bk_hat, const double2 *__restrict__ tw_table, uint32_t ks_bits,
     uint32_t *__restrict__ ext_b, uint16_t *__restrict__ ksd, uint32_t gates, unsigned *round_err, CtSpace cs,
     const uint32_t *__restrict__ out_ids, uint32_t *__restrict__ raw_ext)
 {
     constexpr int P = PL::P, L = PL::L, M = PL::M, N = PL::N, GPW = PL::GPW;
+    const uint32_t l = LC ? (uint32_t)LC : l_arg;
     __shared__ uint32_t s_acc[BR_WAVES * GPW][2][N];
     __shared__ double2 s_xch[BR_WAVES * GPW][PL::XSLOTS];
     __shared__ double2 s_tw[TwTable<PL>::COUNT];
@@ -139,6 +142,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
 #pragma unroll
         for (int k = 0; k < P; k++) { sr[0][k] = si[0][k] = sr[1][k] = si[1][k] = 0.0; }
 
+#pragma unroll(LC ? 2 : 1)
         for (int c = 0; c < 2; c++) {
             // D_c = X^abar * ACC_c - ACC_c at this lane's 2P coefficients
             uint32_t dlo[P], dhi[P];
@@ -153,6 +157,7 @@ __global__ __launch_bounds__(64 * BR_WAVES, 2) void k_blind_rotate(
                 dlo[m] = (v0 - acc[c][j0] + dec_off) ^ flip;
                 dhi[m] = (v1 - acc[c][j1] + dec_off) ^ flip;
             }
+#pragma unroll(LC ? LC : 1)
             for (uint32_t p = 0; p < l; p++) {
                 const uint32_t sh = 32 - (p + 1) * bg_bit;
                 const uint32_t r = c * l + p;
@@ -1074,10 +1079,13 @@ static hipError_t blind_rotate_t(const she_params &P, const DeviceKeys &K, size_
     const uint32_t per_block = BR_WAVES * PL::GPW;
     const dim3 grid((unsigned)((gates + per_block - 1) / per_block)), block(64 * BR_WAVES);
     if (d_round_err)
-        hipLaunchKernelGGL((k_blind_rotate<PL, true>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
+        hipLaunchKernelGGL((k_blind_rotate<PL, true, 0>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
+                           K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
+    else if (P.l == 3)
+        hipLaunchKernelGGL((k_blind_rotate<PL, false, 3>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
                            K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
     else
-        hipLaunchKernelGGL((k_blind_rotate<PL, false>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
+        hipLaunchKernelGGL((k_blind_rotate<PL, false, 0>), grid, block, 0, st, W.bar, W.bar_stride, P.n, P.l, P.bg_bit,
                            K.bk_hat, K.twiddles, ks_bits, W.ext_b, W.ksd, (uint32_t)gates, d_round_err, cs, d_out, raw_ext);
     return hipGetLastError();
 }
