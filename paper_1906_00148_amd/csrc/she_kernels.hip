@@ -808,7 +808,7 @@ __global__ __launch_bounds__(KS_COLS) void k_key_switch(CtSpace cs, const uint32
 // (|sum| <= 2^20) recombined with shifts give the exact result modulo 2^32.
 // One v_mfma_i32_32x32x32_i8 consumes the 32 k of one i (8 digits x 4 values; the v = 0
 // column of A is always 0).  A wavefront owns 64 gates x 32 output words; a block of four
-// wavefronts shares the key bytes through L1; blockIdx.z splits the i range and partial
+// wavefronts shares the key bytes through LDS; blockIdx.z splits the i range and partial
 // sums are subtracted atomically from the slot that the blind rotation initialised.
 // ------------------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -817,14 +817,22 @@ constexpr int KSM_WAVES = 4, KSM_TILES = 2;   // measured: 1 tile (4 or 6 waves 
 
 __device__ __forceinline__ int onehot_byte(uint32_t d) { return (int)((1u << (d << 3)) & 0xFFFFFF00u); }
 
+// The four wavefronts of a workgroup work on the same 32 output words, so the 4 KiB of key bytes of a step (four byte
+// planes x 64 lanes x 16 bytes) are fetched once per workgroup, wavefront w bringing plane w straight into LDS
+// (global_load_lds), and every wavefront reads them from there.  (Each wavefront loading them for itself through the
+// vector L1 kept that cache's pending-request stall at 60 % of the kernel's time: 0.375 against 0.278 ms per 4096 gates.)
+// Two stages: a step's bytes are requested during the step before; requesting two steps ahead through four stages is
+// no faster (0.284 ms).  Every wavefront of a workgroup meets every barrier: one with no gates of its own still brings
+// its plane.  i_per_block must be even.
 __global__ __launch_bounds__(64 * KSM_WAVES, 3) void k_key_switch_mfma(CtSpace cs, const int8_t *__restrict__ ksb,
                                                                      uint32_t cols_p, const uint16_t *__restrict__ ksd,
                                                                      const uint32_t *__restrict__ out_ids, uint32_t N,
                                                                      uint32_t n, uint32_t gates, uint32_t i_per_block)
 {
+    __shared__ uint4 s_b0[4 * 64], s_b1[4 * 64];                           // [plane][lane], one array per stage
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, c32 = lane & 31;
-    const uint32_t tile0 = (blockIdx.x * KSM_WAVES + wave) * KSM_TILES;          // in units of 32 gates
-    if (tile0 * 32 >= gates) return;
+    const uint32_t tile_first = blockIdx.x * KSM_WAVES * KSM_TILES;              // live: the workgroup exists for it
+    const uint32_t tile0 = tile_first + wave * KSM_TILES;                        // in units of 32 gates
     const uint32_t col = blockIdx.y * 32 + c32;
     const uint32_t i0 = blockIdx.z * i_per_block, i1 = min(N, i0 + i_per_block);
 
@@ -841,31 +849,37 @@ __global__ __launch_bounds__(64 * KSM_WAVES, 3) void k_key_switch_mfma(CtSpace c
 #pragma unroll
     for (int t = 0; t < KSM_TILES; t++) {
         tile_live[t] = (tile0 + t) * 32 < gates;
-        yp[t] = ksd + ((size_t)(tile_live[t] ? tile0 + t : tile0) * N) * KS_GROUP + c32;
+        yp[t] = ksd + ((size_t)(tile_live[t] ? tile0 + t : tile_first) * N) * KS_GROUP + c32;
     }
-    const int8_t *bbase = ksb + ((size_t)col * 32 + 16 * half);
+    // this wavefront's plane of a step: 1 KiB, lane (half, c32) takes the 16 bytes of column c32, half `half`
+    const uint4 *mine = reinterpret_cast<const uint4 *>(ksb + ((size_t)wave * cols_p + col) * 32 + 16 * half);
+    const size_t step_u4 = (size_t)4 * cols_p * 2;                          // one i further, in 16-byte units
     const uint32_t ysh = 8 * (1 - half);
 
-    // the key bytes and digits of step i+1 are requested before the products of step i (one wavefront per SIMD:
-    // nothing else hides the loads); past the end the last step is read again, which is harmless
-    v4i b_next[4];
     uint32_t y_next[KSM_TILES];
-#pragma unroll
-    for (int p = 0; p < 4; p++) b_next[p] = *(const v4i *)(bbase + ((size_t)i0 * 4 + p) * cols_p * 32);
+    load_to_lds16(mine + (size_t)i0 * step_u4, s_b0 + wave * 64);
 #pragma unroll
     for (int t = 0; t < KSM_TILES; t++) y_next[t] = yp[t][(size_t)i0 * KS_GROUP];
-    for (uint32_t i = i0; i < i1; i++) {
-        v4i b[4];
+
+    auto step = [&](uint32_t i, const uint4 *cur, uint4 *other) {
+        // this step's bytes have landed (every wavefront waits for its own plane, then all meet), and nobody still
+        // reads the other stage (its readers waited for their values before their products, a step ago)
+        __builtin_amdgcn_s_waitcnt(0x0F70);                                 // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
         uint32_t yv[KSM_TILES];
 #pragma unroll
-        for (int p = 0; p < 4; p++) b[p] = b_next[p];
-#pragma unroll
         for (int t = 0; t < KSM_TILES; t++) yv[t] = y_next[t];
-        const uint32_t in = min(i + 1, i1 - 1);
-#pragma unroll
-        for (int p = 0; p < 4; p++) b_next[p] = *(const v4i *)(bbase + ((size_t)in * 4 + p) * cols_p * 32);
+        const uint32_t in = min(i + 1, i1 - 1);                             // past the end: the last step again, unused
+        load_to_lds16(mine + (size_t)in * step_u4, other + wave * 64);
 #pragma unroll
         for (int t = 0; t < KSM_TILES; t++) y_next[t] = yp[t][(size_t)in * KS_GROUP];
+        __builtin_amdgcn_sched_barrier(0);                                  // the requests stay ahead of the products
+        v4i b[4];
+#pragma unroll
+        for (int p = 0; p < 4; p++) {
+            const uint4 w = cur[p * 64 + lane];
+            b[p] = v4i{(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+        }
 #pragma unroll
         for (int t = 0; t < KSM_TILES; t++) {
             const uint32_t y = (yv[t] >> ysh) & 0xffu;                                    // this half's four digits
@@ -877,7 +891,13 @@ __global__ __launch_bounds__(64 * KSM_WAVES, 3) void k_key_switch_mfma(CtSpace c
 #pragma unroll
             for (int p = 0; p < 4; p++) acc[t][p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[p], acc[t][p], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);                                  // the next step's wait stays behind the products
+    };
+    for (uint32_t i = i0; i < i1; i += 2) {
+        step(i, s_b0, s_b1);
+        step(i + 1, s_b1, s_b0);
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);                                     // no load into LDS is in flight at the end
 
     if (col > n) return;
 #pragma unroll
@@ -885,7 +905,7 @@ __global__ __launch_bounds__(64 * KSM_WAVES, 3) void k_key_switch_mfma(CtSpace c
         if (!tile_live[t]) continue;
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-            const uint32_t row = 8 * (r / 4) + 4 * half + (r % 4);       // accumulator layout of the 32x32 MFMA
+            const uint32_t row = 8 * (r / 4) + 4 * half + (r % 4);
             const uint32_t g = (tile0 + t) * 32 + row;
             if (g >= gates) continue;
             const uint32_t v = (uint32_t)acc[t][0][r] + ((uint32_t)acc[t][1][r] << 8) + ((uint32_t)acc[t][2][r] << 16) +
@@ -1126,7 +1146,7 @@ hipError_t launch_key_switch(const she_params &P, const DeviceKeys &K, const CtS
         while (split < 32 && gate_blocks * col_tiles * split < 1024 && P.N / (split * 2) >= 8) split *= 2;
         const dim3 grid(gate_blocks, col_tiles, split);
         hipLaunchKernelGGL(k_key_switch_mfma, grid, dim3(64 * KSM_WAVES), 0, st, cs, K.ks_bytes, K.ks_cols, W.ksd, d_out,
-                           P.N, P.n, (uint32_t)gates, P.N / split);
+                           P.N, P.n, (uint32_t)gates, P.N / split);              // N / split: a power of two >= 8
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((gates + KS_GROUP - 1) / KS_GROUP), (P.n + 1 + KS_COLS - 1) / KS_COLS);
