@@ -311,8 +311,9 @@ int she_trlwe_phase(she_ctx *ctx, const uint32_t *ids, size_t count, uint32_t *p
  * to nearest), 2l forward transforms, 2l x 2 pointwise products with the selector's spectra, two
  * inverse transforms, addition of in0.  Results are exact integers (the same rounding argument as
  * the blind rotation).  No out id may equal an in1 / in0 id of the same call or another out id
- * (SHE_EINVAL); ids outside their pools give SHE_ERANGE.  she_last_timing then reports the kernel's
- * time in ms[1]. */
+ * (SHE_EINVAL); ids outside their pools give SHE_ERANGE.  The entries are evaluated in an order of the
+ * library's choosing (grouped by selector, so that entries which share a selector's spectra run
+ * together).  she_last_timing then reports the kernel's time in ms[1]. */
 int she_eval_cmux(she_ctx *ctx, const uint32_t *sel, const uint32_t *in1, const uint32_t *in0, const uint32_t *out,
                   size_t count);
 
