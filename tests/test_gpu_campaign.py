@@ -91,3 +91,36 @@ def test_cfg2_level_larger_sample_real(real_keys):
         pool[: 2 * G] = O.encrypt_bits(real_keys, bits, S.data_seed(2))
         O.eval_gates(real_keys, pool, codes[sub], in_ids[0::2][sub], in_ids[1::2][sub], out_ids[sub], threads=16)
         assert np.array_equal(ctx.read_cts(out_ids[sub]), pool[out_ids[sub]])
+
+
+def test_repeated_levels_give_identical_words_real():
+    """The arithmetic is exact integers, so a level evaluated again must give the same ciphertext words, whatever the
+    order in which wavefronts and workgroups happen to run: full and ragged gate levels through both blind-rotation
+    kernels and the key switch that shares its key bytes through LDS, and a CMux level longer than its grid."""
+    pkg = she()
+    G = 4096
+    bits, codes = S.cfg2_real_level(G)
+    with pkg.Context(pkg.REAL, S.KEY_SEED, 3 * G) as ctx:
+        ids = np.arange(2 * G, dtype=np.uint32)
+        ctx.encrypt_bits(bits, S.data_seed(2), ids)
+        for n, repeats in ((4096, 3), (2049, 3), (257, 5), (33, 5)):
+            out = np.arange(2 * G, 2 * G + n, dtype=np.uint32)
+            ctx.eval_gates(codes[:n], ids[0:2 * n:2], ids[1:2 * n:2], out)
+            first = ctx.read_cts(out)
+            for _ in range(repeats):
+                ctx.eval_gates(codes[:n], ids[0:2 * n:2], ids[1:2 * n:2], out)
+                assert np.array_equal(ctx.read_cts(out), first), n
+    with pkg.Context(pkg.REAL, S.KEY_SEED, 16) as ctx:
+        count, nsel, ndat = 5000, 40, 64
+        ctx.leveled_init(nsel, ndat + count)
+        rng = np.random.default_rng(5)
+        ctx.trgsw_encrypt_bits(rng.integers(0, 2, nsel).astype(np.uint8), 1, np.arange(nsel, dtype=np.uint32))
+        mu = np.where(rng.integers(0, 2, (ndat, 1024)) == 1, 1 << 29, (1 << 32) - (1 << 29)).astype(np.uint32)
+        ctx.trlwe_encrypt(mu, 2, np.arange(ndat, dtype=np.uint32))
+        s, i1, i0 = rng.integers(0, nsel, count), rng.integers(0, ndat, count), rng.integers(0, ndat, count)
+        out = (ndat + np.arange(count)).astype(np.uint32)
+        ctx.eval_cmux(s, i1, i0, out)
+        first = ctx.trlwe_read(out)
+        for _ in range(3):
+            ctx.eval_cmux(s, i1, i0, out)
+            assert np.array_equal(ctx.trlwe_read(out), first)
