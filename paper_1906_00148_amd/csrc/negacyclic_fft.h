@@ -57,7 +57,13 @@ template <int LOGP_, int K_> struct Plan {
     static constexpr int GPW = 64 / L;                // transforms (gates) per wavefront
     static constexpr int XROW = L + 1;                // padded row of the exchange buffer, 16-byte slots
                                                       // (measured: +0 costs 18 %, +8 17 %, +2 +3 +4 +5 +9 are no better than +1)
-    static constexpr int XSLOTS = P * XROW;           // exchange slots per transform
+    // Row length of the exchange that follows pass s.  LDS serves sixteen lanes' 16-byte reads per clock when they fall
+    // into sixteen different slots modulo 16.  With eight points per lane and three passes, lane 8a + b reads slots
+    // a*row + b + 8m after the first pass (row = 8 mod 16 keeps neighbouring a apart: measured 575 against 203 B/ns per
+    // compute unit with row = 65) and b*row + 8a + m after the second (any odd row: 550 B/ns, 76 with row = 72), so
+    // the two exchanges want different rows.  Writes (about 183 B/ns whatever the row) do not care.
+    static constexpr int xrow(int s) { return (P == 8 && K == 3 && s == 0) ? L + 8 : L + 1; }
+    static constexpr int XSLOTS = P * ((P == 8 && K == 3) ? L + 8 : L + 1);   // exchange slots per transform
     static constexpr int XP = P;                      // points that one exchange moves per lane
     static constexpr bool NODES = false;              // radix-P passes below; true: node-ordered stages (Plan2048)
     static_assert(L >= 1 && L <= 64 && 64 % L == 0, "one transform must fit a wavefront");
@@ -70,7 +76,9 @@ template <int LOGP_, int K_> struct Plan {
 struct Plan2048 {
     static constexpr int LOGP = 4, P = 16, K = 3, M = 1024, N = 2048, L = 64, GPW = 1;
     static constexpr int XP = 8, LOGXP = 3;           // one half
-    static constexpr int XROW = L + 1, XSLOTS = XP * XROW;
+    static constexpr int XROW = L + 1;
+    static constexpr int xrow(int s) { return s == 0 ? L + 8 : L + 1; }   // as in the 512-point plan, whose exchanges these are
+    static constexpr int XSLOTS = XP * (L + 8);
     static constexpr bool NODES = true;
 };
 
@@ -353,7 +361,7 @@ template <class PL> struct LaneCtx {
             const int Ts = ipow(PL::XP, PL::K - 1 - s);      // sub-transform length after pass s
             const int Tn = Ts / PL::XP;
             const int q = t / Tn, tn = t % Tn, ks = q % PL::XP, kap = q / PL::XP;
-            rd_base[s] = ks * PL::XROW + tn + Ts * kap;
+            rd_base[s] = ks * PL::xrow(s) + tn + Ts * kap;
         }
     }
     // twiddle of pass s, output k
@@ -417,7 +425,7 @@ __device__ __forceinline__ void forward_halves(const LaneCtx<PL> &lc, double2 *c
                 double(&i)[H] = *reinterpret_cast<double(*)[H]>(&xi[b][H * h]);
                 wave_lds_fence();
 #pragma unroll
-                for (int m = 0; m < H; m++) xch[b][brev(m, LOGH) * PL::XROW + lc.t] = make_double2(r[m], i[m]);
+                for (int m = 0; m < H; m++) xch[b][brev(m, LOGH) * PL::xrow(pass - 1) + lc.t] = make_double2(r[m], i[m]);
                 wave_lds_fence();
 #pragma unroll
                 for (int m = 0; m < H; m++) {
@@ -475,7 +483,7 @@ __device__ __forceinline__ void inverse_halves(const LaneCtx<PL> &lc, double2 *c
                 wave_lds_fence();
 #pragma unroll
                 for (int m = 0; m < H; m++) {
-                    const double2 v = xch[b][brev(m, LOGH) * PL::XROW + lc.t];
+                    const double2 v = xch[b][brev(m, LOGH) * PL::xrow(pass - 1) + lc.t];
                     r[m] = v.x; i[m] = v.y;
                 }
             }
@@ -533,7 +541,7 @@ __device__ __forceinline__ void forward_radix(const LaneCtx<PL> &lc, double2 *co
                     xr[b][k] = r * w[k].x - i * w[k].y;
                     xi[b][k] = r * w[k].y + i * w[k].x;
                 }
-                xch[b][k * PL::XROW + lc.t] = make_double2(xr[b][k], xi[b][k]);   // stores overlap the remaining products
+                xch[b][k * PL::xrow(s) + lc.t] = make_double2(xr[b][k], xi[b][k]);   // stores overlap the remaining products
             }
         }
         wave_lds_fence();
@@ -595,7 +603,7 @@ __device__ __forceinline__ void forward_pipelined(const LaneCtx<PL> &lc, double 
                         xr[b][k] = r * w[k].x - i * w[k].y;
                         xi[b][k] = r * w[k].y + i * w[k].x;
                     }
-                    lc.xch[k * PL::XROW + lc.t] = make_double2(xr[b][k], xi[b][k]);
+                    lc.xch[k * PL::xrow(s) + lc.t] = make_double2(xr[b][k], xi[b][k]);
                 }
                 wave_lds_fence();
 #pragma unroll
@@ -635,7 +643,7 @@ __device__ __forceinline__ void inverse_radix(const LaneCtx<PL> &lc, double2 *co
                     wave_lds_fence();
 #pragma unroll
                     for (int k = 0; k < P; k++) {
-                        const double2 v = xch[b][k * PL::XROW + lc.t];
+                        const double2 v = xch[b][k * PL::xrow(s) + lc.t];
                         xr[b][k] = v.x; xi[b][k] = v.y;
                     }
                 }
@@ -650,7 +658,7 @@ __device__ __forceinline__ void inverse_radix(const LaneCtx<PL> &lc, double2 *co
             for (int b = 0; b < NB; b++)
 #pragma unroll
                 for (int k = 0; k < P; k++) {
-                    const double2 v = xch[b][k * PL::XROW + lc.t];
+                    const double2 v = xch[b][k * PL::xrow(s) + lc.t];
                     xr[b][k] = v.x; xi[b][k] = v.y;
                 }
             }

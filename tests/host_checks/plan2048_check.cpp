@@ -27,7 +27,7 @@ static int rd_base(int t, int s)
 {
     const int Ts = ipow(H, PL::K - 1 - s), Tn = Ts / H;
     const int q = t / Tn, tn = t % Tn, ks = q % H, kap = q / H;
-    return ks * PL::XROW + tn + Ts * kap;
+    return ks * PL::xrow(s) + tn + Ts * kap;
 }
 
 static void entries(int t, int pass, int h, CosTan (&e)[4])
@@ -47,7 +47,7 @@ static void forward_emulated(Lanes &x)
         const int Tn = ipow(H, 2 - pass);
         for (int h = 0; h < 2; h++) {
             for (int t = 0; t < L; t++)
-                for (int m = 0; m < H; m++) { br[brev(m, LOGH) * PL::XROW + t] = x.r[t][H * h + m]; bi[brev(m, LOGH) * PL::XROW + t] = x.i[t][H * h + m]; }
+                for (int m = 0; m < H; m++) { br[brev(m, LOGH) * PL::xrow(pass - 1) + t] = x.r[t][H * h + m]; bi[brev(m, LOGH) * PL::xrow(pass - 1) + t] = x.i[t][H * h + m]; }
             for (int t = 0; t < L; t++) {
                 for (int m = 0; m < H; m++) { x.r[t][H * h + m] = br[rd_base(t, pass - 1) + m * Tn]; x.i[t][H * h + m] = bi[rd_base(t, pass - 1) + m * Tn]; }
                 CosTan e[4];
@@ -83,7 +83,7 @@ static void inverse_emulated(Lanes &x)
                 for (int m = 0; m < H; m++) { br[rd_base(t, pass - 1) + m * Tn] = x.r[t][H * h + m]; bi[rd_base(t, pass - 1) + m * Tn] = x.i[t][H * h + m]; }
             }
             for (int t = 0; t < L; t++)
-                for (int m = 0; m < H; m++) { x.r[t][H * h + m] = br[brev(m, LOGH) * PL::XROW + t]; x.i[t][H * h + m] = bi[brev(m, LOGH) * PL::XROW + t]; }
+                for (int m = 0; m < H; m++) { x.r[t][H * h + m] = br[brev(m, LOGH) * PL::xrow(pass - 1) + t]; x.i[t][H * h + m] = bi[brev(m, LOGH) * PL::xrow(pass - 1) + t]; }
         }
     }
     CosTan e0[8];
