@@ -444,9 +444,15 @@ def main():
                                                                (3, "add_with_the_kernels_lds_and_key_loads"))}
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     br_ns = br_ms * 1e6 / (G * 630 * FP64_INSTR_PER_CMUX / (4.0 * cus))
+    # the LDS pipe of a compute unit, 16 bytes per lane and operation, 8 wavefronts (she_probe_lds_rate): the rows of
+    # the exchange buffers were chosen from these figures; an exchange is 8 stores and 8 loads per lane
+    lds = {name: ctx.probe_lds_rate(form) for form, name in (
+        (0, "loads_consecutive"), (1, "stores_consecutive"), (2, "read_back_after_first_pass_row_72"),
+        (3, "read_back_after_first_pass_row_65"), (4, "read_back_after_second_pass_row_65"))}
     out["diagnostics"] = {
         "note": "issue-rate probes; not part of the roofline, whose fraction is against the published 78.6 TFLOP/s",
         "measured_fp64_issue": probe,
+        "lds_bytes_per_ns_per_compute_unit": lds,
         "blind_rotate_over_measured_fma_rate": achieved / probe["fma_scalar_operands"]["tflops_as_fma"],
         "blind_rotate_ns_per_fp64_instruction_per_simd": br_ns,
         "probe_with_kernel_memory_pattern_over_blind_rotate": probe["add_with_the_kernels_lds_and_key_loads"][

@@ -114,6 +114,7 @@ def load_library() -> C.CDLL:
         "she_set_round_tracking": (C.c_int, [ctx, C.c_int]),
         "she_get_round_error": (C.c_int, [ctx, C.POINTER(C.c_double), C.c_int]),
         "she_probe_fp64_rate": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "she_probe_lds_rate": (C.c_int, [ctx, C.c_int, C.POINTER(C.c_double)]),
         "she_set_timing": (C.c_int, [ctx, C.c_int]),
         "she_last_timing": (C.c_int, [ctx, C.POINTER(C.c_double)]),
         "she_last_level_sizes": (C.c_int, [ctx, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64), C.c_size_t,
@@ -472,6 +473,12 @@ class Context:
         ns, tf = C.c_double(0), C.c_double(0)
         self._check(self._L.she_probe_fp64_rate(self._h, form, C.byref(ns), C.byref(tf)))
         return {"ns_per_instruction_per_simd": ns.value, "tflops_as_fma": tf.value}
+
+    def probe_lds_rate(self, form: int) -> float:
+        """bytes per nanosecond and compute unit (see include/she_diag.h)"""
+        v = C.c_double(0)
+        self._check(self._L.she_probe_lds_rate(self._h, form, C.byref(v)))
+        return v.value
 
     def set_timing(self, on: bool):
         self._check(self._L.she_set_timing(self._h, int(on)))

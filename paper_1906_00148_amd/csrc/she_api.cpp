@@ -1247,6 +1247,32 @@ try {
     return SHE_OK;
 } SHE_NOTHROW(c)
 
+int she_probe_lds_rate(she_ctx *c, int form, double *bytes_per_ns_per_cu)
+try {
+    if (!c) return SHE_EINVAL;
+    if (form < 0 || form > 4 || !bytes_per_ns_per_cu) return fail(c, SHE_EINVAL, "form must be 0..4");
+    const uint32_t blocks = 2 * c->dk.cus;                    // 8 wavefronts per compute unit
+    const int iters = 20000;                                  // 8 KiB per wavefront and iteration: a few ms
+    uint32_t *d_out = nullptr;
+    HIP_TRY(c, hipMalloc((void **)&d_out, (size_t)blocks * 256 * sizeof(uint32_t)));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t rc = hipEventCreate(&e0);
+    if (rc == hipSuccess) rc = hipEventCreate(&e1);
+    if (rc == hipSuccess) rc = launch_lds_probe(form, d_out, blocks, 200, c->stream);           // warm-up
+    if (rc == hipSuccess) rc = hipEventRecord(e0, c->stream);
+    if (rc == hipSuccess) rc = launch_lds_probe(form, d_out, blocks, iters, c->stream);
+    if (rc == hipSuccess) rc = hipEventRecord(e1, c->stream);
+    if (rc == hipSuccess) rc = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (rc == hipSuccess) rc = hipEventElapsedTime(&ms, e0, e1);
+    if (e0) hipEventDestroy(e0);
+    if (e1) hipEventDestroy(e1);
+    hipFree(d_out);
+    if (rc != hipSuccess) return fail(c, SHE_EDEVICE, std::string("LDS probe: ") + hipGetErrorString(rc));
+    *bytes_per_ns_per_cu = 8.0 * 1024.0 * iters * 8.0 / ((double)ms * 1e6);   // 8 operations x 1 KiB x 8 wavefronts
+    return SHE_OK;
+} SHE_NOTHROW(c)
+
 int she_set_timing(she_ctx *c, int on)
 try {
     if (!c) return SHE_EINVAL;

@@ -75,6 +75,7 @@ hipError_t launch_gather(const CtSpace &cs, uint32_t *d_dst /* [count][n+1] */, 
 // diagnostic: `blocks` workgroups of 256 threads, each thread 64*iters dependent-free FP64 instructions of one form
 hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters, const double2 *src, uint32_t src_rows,
                              hipStream_t st);
+hipError_t launch_lds_probe(int form, uint32_t *d_out, uint32_t blocks, int iters, hipStream_t st);
 hipError_t launch_copy_ct(const CtSpace &cs, const uint32_t *d_src_ids, const uint32_t *d_dst_ids, size_t count,
                           uint32_t n, hipStream_t st);
 

@@ -1280,6 +1280,43 @@ template <int FORM> __global__ __launch_bounds__(256) void k_fp64_probe(double *
     out[blockIdx.x * blockDim.x + threadIdx.x] = sum;
 }
 
+// LDS throughput probe: every lane moves 16 bytes per operation, eight operations per iteration, in the exchange
+// buffer's layout; ROW = slots per row.  PATTERN 0: loads of consecutive slots, 1: stores of consecutive slots,
+// 2: loads at a*ROW + b + 8m for lane 8a + b, 3: loads at b*ROW + 8a + m.
+template <int PATTERN, int ROW> __global__ __launch_bounds__(256) void k_lds_probe(uint32_t *out, int iters)
+{
+    __shared__ uint4 buf[4][8 * ROW];
+    const int wave = threadIdx.x >> 6, t = threadIdx.x & 63, a = t >> 3, b8 = t & 7;
+    uint4 acc = make_uint4(t, 1, 2, 3);
+    uint4 *b = buf[wave];
+    for (int k = t; k < 8 * ROW; k += 64) b[k] = acc;
+    wave_lds_fence();
+    for (int i = 0; i < iters; i++) {
+#pragma unroll
+        for (int m = 0; m < 8; m++) {
+            if (PATTERN == 1) { acc.x += i; b[m * ROW + t] = acc; continue; }
+            const uint4 v = PATTERN == 0 ? b[m * ROW + t] : PATTERN == 2 ? b[a * ROW + b8 + 8 * m] : b[b8 * ROW + 8 * a + m];
+            acc.x += v.x; acc.y ^= v.y; acc.z += v.z; acc.w ^= v.w;
+        }
+        wave_lds_fence();
+    }
+    out[blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
+hipError_t launch_lds_probe(int form, uint32_t *d_out, uint32_t blocks, int iters, hipStream_t st)
+{
+    constexpr int ROW0 = Plan1024::xrow(0), ROW1 = Plan1024::xrow(1);
+    switch (form) {
+    case 0: hipLaunchKernelGGL((k_lds_probe<0, ROW1>), dim3(blocks), dim3(256), 0, st, d_out, iters); break;
+    case 1: hipLaunchKernelGGL((k_lds_probe<1, ROW1>), dim3(blocks), dim3(256), 0, st, d_out, iters); break;
+    case 2: hipLaunchKernelGGL((k_lds_probe<2, ROW0>), dim3(blocks), dim3(256), 0, st, d_out, iters); break;
+    case 3: hipLaunchKernelGGL((k_lds_probe<2, 65>), dim3(blocks), dim3(256), 0, st, d_out, iters); break;
+    case 4: hipLaunchKernelGGL((k_lds_probe<3, ROW1>), dim3(blocks), dim3(256), 0, st, d_out, iters); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_fp64_probe(int form, double *d_out, uint32_t blocks, int iters, const double2 *src, uint32_t src_rows,
                              hipStream_t st)
 {
