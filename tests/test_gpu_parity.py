@@ -630,11 +630,11 @@ def test_fp64_issue_rate_probe_is_plausible(toy_ctx):
 
 
 def test_lds_rate_probe_backs_the_exchange_rows(toy_ctx):
-    """The diagnostic behind bench.py's "lds_bytes_per_ns_per_compute_unit": plausible figures (between 32 and 256 bytes
+    """The diagnostic behind bench.py's "lds_bytes_per_ns_per_compute_unit": plausible figures (between 25 and 400 bytes
     per clock of 2.4 GHz), and the reason for the row lengths: the read-back after the first pass is much faster with
     the row the plan uses than with a row of 65 slots, which is right for the read-back after the second pass."""
     r = [toy_ctx.probe_lds_rate(form) for form in range(5)]
-    assert all(75.0 < v < 650.0 for v in r), r
+    assert all(60.0 < v < 1000.0 for v in r), r
     assert r[2] > 1.5 * r[3] and r[4] > 1.5 * r[3], r
     pkg = she()
     with pytest.raises(pkg.SheError):
